@@ -1,0 +1,304 @@
+"""CPU oracle for the FastAV pruned prefill — TEST INFRASTRUCTURE, not product code.
+
+Only the test-suite, the smoke check and the benchmark's ``cpu_baseline`` leg
+may import this module; the HIP library never does, and the two share no code.
+
+It is a plain, slow NumPy implementation (fp64 unless told otherwise) of what the
+pruned prefill computes, written from the paper:
+
+* Section 2.1 / Eq. 1     – the decoder consumes one concatenated sequence
+                            [video | audio | text] of K = M + U + E tokens;
+* Section 2.2, "Global pruning" – at a middle layer, video/audio tokens in later
+                            positions are removed (no scores involved);
+* Section 2.2, "Fine pruning", Eq. 4 – s = mean over heads of
+                            softmax(Q_last K^T); the lowest-P% tokens are removed
+                            at each later layer;
+* Section 3.1, "Implementation details" – video tokens precede audio tokens
+                            (or are frame-interleaved), P = 20 %.
+
+The decoder-layer arithmetic itself (RMSNorm, QKV projection, rotate-half RoPE,
+causal grouped-query attention, output projection, SwiGLU MLP, residuals) is the
+standard pre-norm decoder the paper's two models use; the paper does not restate
+it.
+
+Readings taken where the paper is silent (each is repeated at the function that
+implements it):
+  R1  logits are scaled by 1/sqrt(head_dim): Eq. 4 scores are "the attention
+      weight" of the last query, i.e. the model's own softmax.
+  R2  Q and K in Eq. 4 are the post-RoPE features attention consumes.
+  R3  grouped-query attention: query head h reads KV head h // (Hq/Hkv); the mean
+      of Eq. 4 runs over the Hq query heads.
+  R4  keep count k = min(n, max(n_protected, ceil(r*n - 1e-9))), r = 1 - P.
+  R5  only video/audio tokens are candidates; text tokens and the last n_last
+      positions are always kept and count toward k.
+  R6  ties: higher score wins, equal scores -> lower index wins; NaN ranks as -inf,
+      -0.0 equals +0.0; the kept set is returned in ascending order.
+  R7  a GLOBAL prune at layer l acts on the input of layer l; a FINE prune at
+      layer l uses layer l's own attention and every later layer sees the
+      survivors only.  Both may share a layer (global first).
+  R8  survivors keep their ORIGINAL position ids for RoPE.
+  R9  with only a ratio given, global pruning keeps the protected tokens plus the
+      earliest candidates by position (this reproduces "all video + first 10
+      audio" and "first 4 frames" when k is chosen accordingly).
+  R10 n_last > 1 averages the last n_last causal rows (each sums to 1 over its own
+      visible keys).
+
+Pins (tests/test_oracle_pins.py): brute-force loops on tiny inputs, library
+special cases (torch SDPA / rms_norm / silu, numpy stable argsort), closed forms
+(zero queries -> uniform scores; one dominant key -> one-hot), invariants (rows
+sum to 1, keep ratio 1.0 is the identity, RoPE relative-position property,
+batched == per-sample), and the paper's printed FLOPs column of Table 4 for the
+schedule semantics.  Parity unpinned: the absolute hidden-state values for random
+weights (the paper prints no worked numeric example).
+"""
+from __future__ import annotations
+
+import math
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+TEXT, VIDEO, AUDIO = 0, 1, 2
+GLOBAL, FINE = 0, 1
+
+
+# --------------------------------------------------------------------------- schedule
+def keep_count(n: int, keep_ratio: float, n_protected: int) -> int:
+    """Number of tokens kept out of n (reading R4); "lowest P% removed", Section 2.2 Fine pruning."""
+    k = int(math.ceil(float(keep_ratio) * n - 1e-9))
+    return min(n, max(int(n_protected), k))
+
+
+def protected_mask(spans: Sequence[Tuple[int, int]], n_last: int) -> np.ndarray:
+    """True where a token may never be pruned (reading R5): text spans and the last n_last positions.
+
+    ``spans`` is a list of (modality, length) in sequence order."""
+    n = sum(l for _, l in spans)
+    prot = np.zeros(n, dtype=bool)
+    at = 0
+    for modality, length in spans:
+        if modality == TEXT:
+            prot[at:at + length] = True
+        at += length
+    if n_last > 0:
+        prot[max(0, n - n_last):] = True
+    return prot
+
+
+def token_schedule(n: int, n_protected: int, prunes, n_layers: int) -> List[int]:
+    """Tokens that enter attention at each layer for a sample of n tokens (reading R7).
+
+    A GLOBAL prune at layer l shrinks the input of layer l; a FINE prune at layer l shrinks the input of
+    layer l + 1.  Counts depend only on (n, ratios, n_protected), never on the data."""
+    counts, cur = [], n
+    for l in range(n_layers):
+        here = sorted([p for p in prunes if p.layer == l], key=lambda p: p.kind)
+        for p in here:
+            if p.kind == GLOBAL:
+                cur = keep_count(cur, p.keep_ratio, n_protected)
+        counts.append(cur)
+        for p in here:
+            if p.kind == FINE:
+                cur = keep_count(cur, p.keep_ratio, n_protected)
+    return counts
+
+
+# --------------------------------------------------------------------------- selection
+def _rank_value(scores: np.ndarray) -> np.ndarray:
+    """Scores as comparable fp32 values: NaN -> -inf, -0.0 -> +0.0 (reading R6)."""
+    s = np.asarray(scores, dtype=np.float32).copy()
+    s[np.isnan(s)] = -np.inf
+    s[s == 0] = 0.0
+    return s
+
+
+def select_keep(scores: np.ndarray, prot: np.ndarray, k: int) -> np.ndarray:
+    """Indices kept by a fine prune, ascending (Section 2.2 Fine pruning; readings R5, R6).
+
+    All protected tokens are kept; the remaining k - n_protected slots go to the candidates with the
+    highest score, equal scores resolved toward the lower index."""
+    prot = np.asarray(prot, dtype=bool)
+    n = prot.shape[0]
+    n_prot = int(prot.sum())
+    if not (n_prot <= k <= n):
+        raise ValueError("k must satisfy n_protected <= k <= n")
+    cand = np.nonzero(~prot)[0]
+    s = _rank_value(scores)[cand]
+    order = np.argsort(-s, kind="stable")            # descending score, ascending index among equals
+    chosen = cand[order[: k - n_prot]]
+    keep = np.concatenate([np.nonzero(prot)[0], chosen])
+    keep.sort()
+    return keep.astype(np.int64)
+
+
+def global_keep(prot: np.ndarray, k: int) -> np.ndarray:
+    """Indices kept by global pruning, ascending (Section 2.2 Global pruning; reading R9):
+    every protected token plus the earliest candidates by position."""
+    prot = np.asarray(prot, dtype=bool)
+    n = prot.shape[0]
+    n_prot = int(prot.sum())
+    if not (n_prot <= k <= n):
+        raise ValueError("k must satisfy n_protected <= k <= n")
+    cand = np.nonzero(~prot)[0]
+    keep = np.concatenate([np.nonzero(prot)[0], cand[: k - n_prot]])
+    keep.sort()
+    return keep.astype(np.int64)
+
+
+# --------------------------------------------------------------------------- layer math
+def rmsnorm(x: np.ndarray, g: np.ndarray, eps: float) -> np.ndarray:
+    ms = np.mean(np.square(x), axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * g
+
+
+def rope(x: np.ndarray, pos: np.ndarray, base: float) -> np.ndarray:
+    """Rotate-half rotary embedding on x[n, H, dh] with integer positions pos[n] (reading R8).
+
+    Pair (i, i + dh/2) is rotated by the angle pos * base**(-2i/dh)."""
+    n, H, dh = x.shape
+    half = dh // 2
+    inv_freq = np.asarray(base, dtype=np.float64) ** (-np.arange(half, dtype=np.float64) * 2.0 / dh)
+    ang = pos.astype(np.float64)[:, None] * inv_freq[None, :]          # [n, half]
+    c, s = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+    x1, x2 = x[..., :half], x[..., half:]
+    return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1).astype(x.dtype)
+
+
+def silu(x: np.ndarray) -> np.ndarray:
+    return x / (1.0 + np.exp(-x))
+
+
+def _softmax_rows(z: np.ndarray) -> np.ndarray:
+    z = z - np.max(z, axis=-1, keepdims=True)
+    e = np.exp(z)
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def causal_gqa_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, row_block: int = 1024) -> np.ndarray:
+    """softmax(q k^T / sqrt(dh) + causal mask) v for one sample (readings R1, R3).
+
+    q[n,Hq,dh], k,v[n,Hkv,dh] -> [n,Hq,dh].  Every row is the plain definition (full softmax over its
+    visible keys); the loop over row blocks only bounds the size of the materialised map."""
+    n, Hq, dh = q.shape
+    Hkv = k.shape[1]
+    G = Hq // Hkv
+    out = np.empty_like(q)
+    scale = 1.0 / math.sqrt(dh)
+    for h in range(Hq):
+        kh, vh = k[:, h // G, :], v[:, h // G, :]
+        for r0 in range(0, n, row_block):
+            r1 = min(n, r0 + row_block)
+            z = (q[r0:r1, h, :] @ kh[:r1].T) * scale                      # rows r0..r1-1 see keys < r1 at most
+            rows = np.arange(r0, r1)[:, None]
+            cols = np.arange(r1)[None, :]
+            z = np.where(cols <= rows, z, -np.inf)
+            out[r0:r1, h, :] = _softmax_rows(z) @ vh[:r1]
+    return out
+
+
+def last_query_scores(q: np.ndarray, k: np.ndarray, n_last: int = 1) -> np.ndarray:
+    """Eq. 4: s = mean over heads of softmax(Q_last K^T)  (readings R1, R2, R3, R10).
+
+    q[n,Hq,dh] and k[n,Hkv,dh] are the post-RoPE features of one sample; the result has length n.
+    For n_last > 1 the mean also runs over the last n_last query rows, row r seeing keys 0..r."""
+    n, Hq, dh = q.shape
+    G = Hq // k.shape[1]
+    scale = 1.0 / math.sqrt(dh)
+    s = np.zeros(n, dtype=np.float64)
+    rows = range(max(0, n - n_last), n)
+    for r in rows:
+        for h in range(Hq):
+            z = (k[: r + 1, h // G, :].astype(np.float64) @ q[r, h, :].astype(np.float64)) * scale
+            z -= z.max()
+            e = np.exp(z)
+            s[: r + 1] += e / e.sum()
+    return s / (Hq * len(rows))
+
+
+# --------------------------------------------------------------------------- decoder + pruning
+def layer_qkv(x: np.ndarray, W: Dict[str, np.ndarray], pos: np.ndarray, m) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """RMSNorm -> Q/K/V projections -> RoPE on Q and K.  Weights are [out, in]."""
+    n = x.shape[0]
+    h = rmsnorm(x, W["g_attn"], m.rms_eps)
+    q = (h @ W["wq"].T).reshape(n, m.n_q_heads, m.head_dim)
+    k = (h @ W["wk"].T).reshape(n, m.n_kv_heads, m.head_dim)
+    v = (h @ W["wv"].T).reshape(n, m.n_kv_heads, m.head_dim)
+    return rope(q, pos, m.rope_base), rope(k, pos, m.rope_base), v
+
+
+def layer_finish(x: np.ndarray, attn: np.ndarray, W: Dict[str, np.ndarray], m) -> np.ndarray:
+    """x + attn Wo^T, then x + SwiGLU MLP of its RMSNorm."""
+    n = x.shape[0]
+    x = x + attn.reshape(n, -1) @ W["wo"].T
+    h = rmsnorm(x, W["g_mlp"], m.rms_eps)
+    return x + (silu(h @ W["w_gate"].T) * (h @ W["w_up"].T)) @ W["w_down"].T
+
+
+def prefill_sample(m, weights, x: np.ndarray, spans: Sequence[Tuple[int, int]], prunes, n_last: int = 1,
+                   dtype=np.float64, keep_kv: bool = True, trace: bool = False) -> Dict:
+    """Pruned prefill of ONE sample (Fig. 3; Section 2.2).
+
+    ``weights``: a sequence of per-layer dicts, or a callable ``layer -> dict`` (so big models need not
+    be resident).  ``prunes``: objects with ``layer``, ``kind`` (GLOBAL/FINE), ``keep_ratio``.
+    Returns x_out [n_final, d], kept_pos [n_final] (original positions), per-layer K/V (post-RoPE, of
+    the tokens that survive that layer), and for every prune its scores / kept indices / counts."""
+    get_w = weights if callable(weights) else (lambda l: weights[l])
+    x = np.asarray(x, dtype=dtype)
+    n0 = x.shape[0]
+    pos = np.arange(n0, dtype=np.int64)
+    prot = protected_mask(spans, n_last)
+    out = {"kv": [], "prunes": [], "n_per_layer": []}
+    if trace:
+        out["trace"] = []
+    for l in range(m.n_layers):
+        W = {name: np.asarray(a, dtype=dtype) for name, a in get_w(l).items()}
+        here = sorted([p for p in prunes if p.layer == l], key=lambda p: p.kind)
+        for p in here:
+            if p.kind == GLOBAL:                                            # reading R7: acts on the layer input
+                k_keep = keep_count(x.shape[0], p.keep_ratio, int(prot.sum()))
+                keep = global_keep(prot, k_keep)
+                out["prunes"].append({"layer": l, "kind": GLOBAL, "n_in": x.shape[0], "k": k_keep,
+                                      "keep": keep, "pos_in": pos.copy(), "scores": None})
+                x, pos, prot = x[keep], pos[keep], prot[keep]
+        n = x.shape[0]
+        out["n_per_layer"].append(n)
+        q, k, v = layer_qkv(x, W, pos, m)
+        attn = causal_gqa_attention(q, k, v)
+        keep = None
+        for p in here:
+            if p.kind == FINE:
+                s = last_query_scores(q, k, n_last)
+                k_keep = keep_count(n, p.keep_ratio, int(prot.sum()))
+                keep = select_keep(s.astype(np.float32), prot, k_keep)
+                out["prunes"].append({"layer": l, "kind": FINE, "n_in": n, "k": k_keep, "keep": keep,
+                                      "pos_in": pos.copy(), "scores": s})
+        x_new = layer_finish(x, attn, W, m)
+        if trace:
+            out["trace"].append({"x_in": x, "q": q, "k": k, "v": v, "attn": attn, "x_out": x_new, "pos": pos.copy()})
+        x = x_new
+        if keep is not None:                                                # survivors only from here on
+            x, pos, prot = x[keep], pos[keep], prot[keep]
+            k, v = k[keep], v[keep]
+        if keep_kv:
+            out["kv"].append((k, v))
+    out["x_out"] = x
+    out["kept_pos"] = pos
+    return out
+
+
+def prefill(workload, weights, x: np.ndarray, dtype=np.float64, keep_kv: bool = True, trace: bool = False) -> List[Dict]:
+    """Batched pruned prefill: samples never interact, so the batch is a loop over samples."""
+    outs, row = [], 0
+    for spans in workload.samples:
+        n = sum(l for _, l in spans)
+        outs.append(prefill_sample(workload.model, weights, x[row:row + n], spans, workload.prunes,
+                                   workload.n_last, dtype, keep_kv, trace))
+        row += n
+    return outs
+
+
+# --------------------------------------------------------------------------- FLOPs accounting
+def decoder_flops(token_counts: Sequence[int], d: int, m_dim: int) -> float:
+    """Theoretical FLOPs in the counting the paper adopts for its FLOPs column (Section 3.1,
+    Evaluation protocol): per layer with n tokens, 4 n d^2 + 2 n^2 d + 2 n d m."""
+    return float(sum(4.0 * n * d * d + 2.0 * n * n * d + 2.0 * n * d * m_dim for n in token_counts))

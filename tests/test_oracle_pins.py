@@ -1,0 +1,331 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix, checked without any GPU.
+
+Each test is chosen so that a plausible mistake in ``oracle/fastav_oracle.py`` (a dropped scale, a wrong
+KV-head mapping, an off-by-one in the causal mask, a transposed weight, a wrong tie rule, a misplaced
+prune) fails at least one of them.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import fastav_inputs as fi
+from oracle import brute
+from oracle import fastav_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand_qkv(n, Hq, Hkv, dh, seed, scale=1.0):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((n, Hq, dh)) * scale, rng.standard_normal((n, Hkv, dh)) * scale,
+            rng.standard_normal((n, Hkv, dh)))
+
+
+# ---------------------------------------------------------------- attention and Eq. 4 vs brute force
+@pytest.mark.parametrize("n,Hq,Hkv,dh", [(1, 2, 1, 4), (7, 4, 2, 8), (19, 6, 2, 4), (12, 3, 3, 6)])
+def test_attention_matches_bruteforce(n, Hq, Hkv, dh):
+    q, k, v = _rand_qkv(n, Hq, Hkv, dh, 10 + n)
+    got = orc.causal_gqa_attention(q, k, v, row_block=5)           # row blocks smaller than n
+    want = np.asarray(brute.attention_output(q.tolist(), k.tolist(), v.tolist(), Hq // Hkv))
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("n_last", [1, 2, 5])
+def test_scores_equal_last_rows_of_head_mean_map(n_last):
+    """Eq. 4 == last row(s) of the head-averaged full attention map A of Section 2.2."""
+    n, Hq, Hkv, dh = 17, 4, 2, 8
+    q, k, _ = _rand_qkv(n, Hq, Hkv, dh, 3)
+    got = orc.last_query_scores(q, k, n_last)
+    want = np.asarray(brute.head_mean_last_rows(q.tolist(), k.tolist(), Hq // Hkv, n_last))
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-15)
+    assert abs(got.sum() - 1.0) < 1e-12                           # mean of distributions is a distribution
+
+
+def test_attention_matches_torch_sdpa():
+    n, Hq, Hkv, dh = 96, 8, 2, 16
+    q, k, v = _rand_qkv(n, Hq, Hkv, dh, 4)
+    got = orc.causal_gqa_attention(q, k, v, row_block=40)
+    tq = torch.from_numpy(q).permute(1, 0, 2)[None]
+    tk = torch.from_numpy(k).permute(1, 0, 2).repeat_interleave(Hq // Hkv, dim=0)[None]
+    tv = torch.from_numpy(v).permute(1, 0, 2).repeat_interleave(Hq // Hkv, dim=0)[None]
+    want = F.scaled_dot_product_attention(tq, tk, tv, is_causal=True)[0].permute(1, 0, 2).numpy()
+    np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-12)
+
+
+def test_softmax_rows_sum_to_one_and_scores_sum_to_one():
+    n, Hq, Hkv, dh = 33, 4, 1, 8
+    q, k, v = _rand_qkv(n, Hq, Hkv, dh, 5, scale=3.0)
+    ones = np.ones_like(v)
+    out = orc.causal_gqa_attention(q, k, ones, row_block=8)        # P @ 1 = row sums
+    np.testing.assert_allclose(out, 1.0, rtol=0, atol=1e-12)
+    for n_last in (1, 3, 33):
+        s = orc.last_query_scores(q, k, n_last)
+        assert abs(s.sum() - 1.0) < 1e-12 and (s >= 0).all()
+
+
+def test_scores_closed_forms():
+    n, Hq, Hkv, dh = 40, 4, 2, 8
+    q, k, _ = _rand_qkv(n, Hq, Hkv, dh, 6)
+    # zero query -> zero logits -> exactly uniform
+    s = orc.last_query_scores(np.zeros_like(q), k, 1)
+    np.testing.assert_allclose(s, 1.0 / n, rtol=1e-15)
+    # one key aligned with every head's last query and scaled up -> one-hot
+    k2 = k * 0.01
+    j = 11
+    for g in range(Hkv):
+        k2[j, g] = 50.0 * q[n - 1, g * (Hq // Hkv)] / np.linalg.norm(q[n - 1, g * (Hq // Hkv)])
+    q2 = q.copy()
+    for h in range(Hq):
+        q2[n - 1, h] = q[n - 1, (h // (Hq // Hkv)) * (Hq // Hkv)] * 5.0
+    s = orc.last_query_scores(q2, k2, 1)
+    assert s[j] > 1 - 1e-9
+    # 1/sqrt(dh) scale: two keys with logits differing by known amount
+    q3 = np.zeros((2, 1, 4)); k3 = np.zeros((2, 1, 4))
+    q3[1, 0, 0] = 2.0; k3[0, 0, 0] = 3.0                         # logit(0) = 6/sqrt(4) = 3, logit(1) = 0
+    s = orc.last_query_scores(q3, k3, 1)
+    np.testing.assert_allclose(s, [math.exp(3) / (1 + math.exp(3)), 1 / (1 + math.exp(3))], rtol=1e-14)
+
+
+def test_gqa_head_mapping():
+    """Query head h must read KV head h // G: make KV heads distinguishable."""
+    n, Hq, Hkv, dh = 6, 4, 2, 4
+    q, k, v = _rand_qkv(n, Hq, Hkv, dh, 7)
+    v[:, 0, :] = 1.0
+    v[:, 1, :] = -2.0
+    out = orc.causal_gqa_attention(q, k, v)
+    np.testing.assert_allclose(out[:, :2], 1.0, atol=1e-12)
+    np.testing.assert_allclose(out[:, 2:], -2.0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- row-wise ops vs library routines / loops
+def test_rmsnorm_silu_match_torch_and_loops():
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((5, 24)); g = 1 + 0.1 * rng.standard_normal(24)
+    got = orc.rmsnorm(x, g, 1e-6)
+    want = F.rms_norm(torch.from_numpy(x), (24,), torch.from_numpy(g), 1e-6).numpy()
+    np.testing.assert_allclose(got, want, rtol=1e-12)
+    np.testing.assert_allclose(got[2], brute.rmsnorm_row(x[2].tolist(), g.tolist(), 1e-6), rtol=1e-12)
+    np.testing.assert_allclose(orc.silu(x), F.silu(torch.from_numpy(x)).numpy(), rtol=1e-12)
+
+
+def test_rope_invariants_and_loops():
+    rng = np.random.default_rng(9)
+    n, H, dh, base = 9, 3, 16, 1.0e4
+    x = rng.standard_normal((n, H, dh))
+    pos = np.array([0, 1, 2, 5, 9, 100, 101, 4000, 16383])
+    y = orc.rope(x, pos, base)
+    np.testing.assert_allclose(y[0], x[0], rtol=0, atol=0)                       # position 0 is the identity
+    half = dh // 2
+    np.testing.assert_allclose(y[..., :half] ** 2 + y[..., half:] ** 2,
+                               x[..., :half] ** 2 + x[..., half:] ** 2, rtol=1e-12)  # per-pair norm preserved
+    for t in (3, 7):
+        np.testing.assert_allclose(y[t, 1], brute.rope_vec(x[t, 1].tolist(), int(pos[t]), base), rtol=1e-10, atol=1e-12)
+    # <rope(a,p1), rope(b,p2)> depends only on p1 - p2
+    a, b = rng.standard_normal((1, 1, dh)), rng.standard_normal((1, 1, dh))
+    def dot(p1, p2):
+        return float(np.sum(orc.rope(a, np.array([p1]), base) * orc.rope(b, np.array([p2]), base)))
+    assert abs(dot(7, 3) - dot(1004, 1000)) < 1e-9
+    assert abs(dot(7, 3) - dot(3, 7)) > 1e-3                                       # and is not symmetric
+
+
+def test_weights_are_out_by_in():
+    """layer_qkv / layer_finish multiply by W^T with W stored [out, in]: compare with torch linear."""
+    m = fi.Model(1, 16, 4, 2, 4, 24, 1.0e4, 1e-6, "f32")
+    W = {k: v.astype(np.float64) for k, v in fi.layer_weights(m, 0, seed=3).items()}
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((5, 16))
+    pos = np.zeros(5, dtype=np.int64)                                              # RoPE identity
+    q, k, v = orc.layer_qkv(x, W, pos, m)
+    h = F.rms_norm(torch.from_numpy(x), (16,), torch.from_numpy(W["g_attn"]), 1e-6)
+    np.testing.assert_allclose(q.reshape(5, -1), F.linear(h, torch.from_numpy(W["wq"])).numpy(), rtol=1e-12)
+    np.testing.assert_allclose(v.reshape(5, -1), F.linear(h, torch.from_numpy(W["wv"])).numpy(), rtol=1e-12)
+    attn = rng.standard_normal((5, 4, 4))
+    got = orc.layer_finish(x, attn, W, m)
+    t = torch.from_numpy(x) + F.linear(torch.from_numpy(attn.reshape(5, -1)), torch.from_numpy(W["wo"]))
+    h2 = F.rms_norm(t, (16,), torch.from_numpy(W["g_mlp"]), 1e-6)
+    t = t + F.linear(F.silu(F.linear(h2, torch.from_numpy(W["w_gate"]))) * F.linear(h2, torch.from_numpy(W["w_up"])),
+                     torch.from_numpy(W["w_down"]))
+    np.testing.assert_allclose(got, t.numpy(), rtol=1e-12)
+
+
+# ---------------------------------------------------------------- selection
+@pytest.mark.parametrize("kind", ["softmax", "ties", "equal", "mixed"])
+@pytest.mark.parametrize("n", [1, 2, 13, 64, 257])
+def test_select_equals_full_sort(kind, n):
+    rng = np.random.default_rng(n)
+    s = fi.random_scores(n, 100 + n, kind)
+    for prot_kind in ("none", "ends", "random"):
+        prot = np.zeros(n, dtype=bool)
+        if prot_kind == "ends":
+            prot[: min(2, n)] = True; prot[-1] = True
+        elif prot_kind == "random":
+            prot = rng.random(n) < 0.3
+        n_prot = int(prot.sum())
+        for k in sorted({n_prot, n, (n_prot + n) // 2, min(n, n_prot + 1)}):
+            got = orc.select_keep(s, prot, k)
+            want = brute.topk_by_full_sort(s.tolist(), prot.tolist(), k)
+            assert got.tolist() == want
+            assert len(got) == k and (np.diff(got) > 0).all() and prot[got].sum() == n_prot
+
+
+def test_select_signed_zero_and_nan_rules():
+    s = np.array([0.0, -0.0, np.nan, -np.inf, 1.0], dtype=np.float32)
+    prot = np.zeros(5, dtype=bool)
+    assert orc.select_keep(s, prot, 2).tolist() == [0, 4]          # +0 and -0 tie -> lower index
+    assert orc.select_keep(s, prot, 3).tolist() == [0, 1, 4]
+    assert orc.select_keep(s, prot, 4).tolist() == [0, 1, 2, 4]    # NaN ties with -inf -> lower index
+
+
+def test_keep_count_rule():
+    assert orc.keep_count(2048, 0.6, 0) == 1229
+    assert orc.keep_count(2458, 0.7, 0) == 1721
+    assert orc.keep_count(1721, 0.7, 0) == 1205
+    assert orc.keep_count(5735, 0.7, 0) == 4015
+    assert orc.keep_count(16384, 0.5, 0) == 8192
+    assert orc.keep_count(10, 0.3, 0) == 3                         # 0.3*10 = 3.0000000000000004 must not give 4
+    assert orc.keep_count(10, 0.1, 4) == 4                         # never below the protected count
+    assert orc.keep_count(10, 1.0, 0) == 10
+
+
+def test_global_rule_reproduces_paper_rules():
+    """Section 3.1 Implementation details: VideoLLaMA2 keeps all video + the first 10 audio tokens;
+    video-SALMONN2 (frame-interleaved) keeps the first 4 frames."""
+    M, U, E = 676, 1496, 64
+    spans = [(orc.VIDEO, M), (orc.AUDIO, U), (orc.TEXT, E)]
+    prot = orc.protected_mask(spans, 1)
+    keep = orc.global_keep(prot, E + M + 10)
+    assert keep.tolist() == list(range(M + 10)) + list(range(M + U, M + U + E))
+    frames = []
+    for _ in range(10):
+        frames += [(orc.VIDEO, 30), (orc.AUDIO, 12)]
+    spans = [(orc.TEXT, 5)] + frames + [(orc.TEXT, 9)]
+    prot = orc.protected_mask(spans, 1)
+    keep = orc.global_keep(prot, 5 + 9 + 4 * 42)
+    assert keep.tolist() == list(range(5 + 4 * 42)) + list(range(5 + 10 * 42, 5 + 10 * 42 + 9))
+
+
+def test_table4_flops_fix_prune_placement():
+    """The paper's FLOPs column (Table 4) is reproduced within +-1 point by the schedule semantics of
+    reading R7 on a VideoLLaMA2-shaped sequence; shifting the global prune by one layer, or not
+    compounding the fine prune per layer, misses it."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "table4_flops.txt")) if l.strip() and not l.startswith("#")]
+    printed = {int(p): float(v) for p, v in rows}
+    L, d, mlp = 28, 3584, 18944
+    M, U, E = 676, 1496, 64                       # 1,496 audio tokens; M + E + 10 = 750 survivors
+    n = M + U + E
+    g = (M + 10 + E) / n
+    base = orc.decoder_flops([n] * L, d, mlp)
+
+    def rel(global_layer, P, compound=True):
+        prunes = [fi.Prune(global_layer, fi.GLOBAL, g)]
+        if P > 0:
+            last = L if compound else global_layer + 1
+            prunes += [fi.Prune(l, fi.FINE, 1.0 - P) for l in range(global_layer, last)]
+        counts = orc.token_schedule(n, E, prunes, L)
+        return 100.0 * orc.decoder_flops(counts, d, mlp) / base
+
+    for P, want in printed.items():
+        assert abs(rel(14, P / 100.0) - want) <= 1.0, (P, rel(14, P / 100.0), want)
+    assert abs(rel(13, 0.0) - printed[0]) > 1.0 and abs(rel(15, 0.0) - printed[0]) > 1.0
+    assert abs(rel(14, 0.2, compound=False) - printed[20]) > 1.0
+
+
+# ---------------------------------------------------------------- the pruned prefill as a whole
+def _tiny():
+    m = fi.Model(4, 32, 4, 2, 8, 48, 1.0e4, 1e-6, "f32")
+    w = fi.Workload("t", m, [[(fi.TEXT, 3), (fi.VIDEO, 20), (fi.AUDIO, 14), (fi.TEXT, 4)]],
+                    [fi.Prune(1, fi.GLOBAL, 0.6), fi.Prune(2, fi.FINE, 0.7), fi.Prune(3, fi.FINE, 0.7)], seed=77)
+    weights = [fi.layer_weights(m, l, 5) for l in range(m.n_layers)]
+    for W in weights:                                # larger weights so attention is far from uniform
+        for name in ("wq", "wk"):
+            W[name] = W[name] * 30.0
+    return m, w, weights, fi.embeddings(w)
+
+
+def test_keep_ratio_one_is_identity():
+    m, w, weights, x = _tiny()
+    plain = orc.prefill(fi.unpruned(w), weights, x)[0]
+    w1 = fi.Workload("t1", m, w.samples, [fi.Prune(p.layer, p.kind, 1.0) for p in w.prunes], seed=w.seed)
+    same = orc.prefill(w1, weights, x)[0]
+    assert np.array_equal(plain["x_out"], same["x_out"])
+    assert np.array_equal(same["kept_pos"], np.arange(41))
+
+
+def test_prefill_schedule_structure_and_original_positions():
+    m, w, weights, x = _tiny()
+    out = orc.prefill(w, weights, x, trace=True)[0]
+    n_prot = 7
+    assert out["n_per_layer"] == orc.token_schedule(41, n_prot, w.prunes, m.n_layers)
+    assert out["n_per_layer"] == [41, 25, 25, 18]
+    assert out["x_out"].shape[0] == 13 == len(out["kept_pos"])
+    kp = out["kept_pos"]
+    assert (np.diff(kp) > 0).all() and kp[-1] == 40 and set(range(3)) <= set(kp) and set(range(37, 41)) <= set(kp)
+    # global prune kept the earliest candidates
+    assert out["prunes"][0]["keep"].tolist() == list(range(3 + 18)) + list(range(37, 41))
+    # K/V of a fine layer are compacted, earlier layers untouched
+    assert [kv[0].shape[0] for kv in out["kv"]] == [41, 25, 18, 13]
+    # RoPE used original positions after pruning: layer 3's K equals a fresh projection with pos = kept positions
+    t3 = out["trace"][3]
+    W3 = {k: v.astype(np.float64) for k, v in weights[3].items()}
+    q, k, v = orc.layer_qkv(t3["x_in"], W3, t3["pos"], m)
+    np.testing.assert_array_equal(k, t3["k"])
+    assert t3["pos"].max() == 40 and len(t3["pos"]) == 18
+    # fine scores are a distribution over the tokens present at that layer
+    s = out["prunes"][1]["scores"]
+    assert len(s) == 25 and abs(s.sum() - 1) < 1e-12
+
+
+def test_in_layer_compaction_equals_end_of_layer():
+    """O-projection, RMSNorm, MLP and residual are row-wise, so removing rows right after attention gives
+    the same surviving rows as removing them at the end of the layer."""
+    m, w, weights, x = _tiny()
+    out = orc.prefill(w, weights, x, trace=True)[0]
+    t2 = out["trace"][2]
+    keep = out["prunes"][1]["keep"]
+    W2 = {k: v.astype(np.float64) for k, v in weights[2].items()}
+    early = orc.layer_finish(t2["x_in"][keep], t2["attn"][keep], W2, m)
+    np.testing.assert_allclose(early, t2["x_out"][keep], rtol=1e-12, atol=1e-13)
+
+
+def test_uniform_scores_make_fine_equal_earliest_first():
+    """With Wq = 0 every logit is 0, s_j = 1/n exactly, every candidate ties, and the tie rule makes the
+    fine prune keep the earliest candidates — the global rule."""
+    m, w, weights, x = _tiny()
+    for W in weights:
+        W["wq"] = np.zeros_like(W["wq"])
+    w2 = fi.Workload("t2", m, w.samples, [fi.Prune(2, fi.FINE, 0.5)], seed=w.seed)
+    out = orc.prefill(w2, weights, x)[0]
+    p = out["prunes"][0]
+    np.testing.assert_allclose(p["scores"], 1.0 / 41, rtol=1e-14)
+    prot = orc.protected_mask(w.samples[0], 1)
+    assert p["keep"].tolist() == orc.global_keep(prot, p["k"]).tolist()
+
+
+def test_batch_is_a_loop_over_samples():
+    m, w, weights, x = _tiny()
+    w_b = fi.Workload("tb", m, [w.samples[0], [(fi.VIDEO, 10), (fi.AUDIO, 9), (fi.TEXT, 2)]], w.prunes, seed=3)
+    xb = fi.embeddings(w_b)
+    outs = orc.prefill(w_b, weights, xb)
+    solo = orc.prefill_sample(m, weights, xb[41:], w_b.samples[1], w.prunes)
+    assert np.array_equal(outs[1]["x_out"], solo["x_out"]) and np.array_equal(outs[1]["kept_pos"], solo["kept_pos"])
+
+
+def test_input_generators_shapes():
+    for i in range(1, 6):
+        w = fi.config(i)
+        assert all(n > 0 for n in w.seqlens)
+    assert fi.config(1).seqlens == [512] and fi.config(2).seqlens == [2048]
+    assert fi.config(3).seqlens == [4096] and fi.config(4).seqlens == [16384]
+    w5 = fi.config(5)
+    assert len(w5.seqlens) == 8 and all(2048 <= n <= 6144 for n in w5.seqlens)
+    for s in w5.samples:
+        n = sum(l for _, l in s)
+        assert 0.55 <= s[0][1] / n <= 0.80 and 0.15 <= s[1][1] / n <= 0.35 and s[2][1] >= 8
+    a = np.array([1.0, 1.00390625, 1.01171875, 3.14159], dtype=np.float32)      # 1+2^-8 ties to even (down), 1+3*2^-8 ties up
+    r = fi.round_bf16(a.copy())
+    assert r[0] == 1.0 and r[1] == 1.0 and r[2] == np.float32(1.015625)
+    assert r[3] == torch.tensor(3.14159).to(torch.bfloat16).float().item()
