@@ -1,0 +1,204 @@
+/*
+ * fastav.h — C ABI of the MI355X (gfx950) FastAV pruned-prefill library.
+ *
+ * The library runs the prefill forward of a pre-norm decoder stack (RMSNorm, QKV projection, rotate-half
+ * RoPE, causal grouped-query attention, output projection, SwiGLU MLP) over a packed batch of audio-visual
+ * token sequences, and applies FastAV's two-stage token pruning on the way (paper Section 2.2, Fig. 3):
+ *
+ *   GLOBAL prune  (Section 2.2 "Global pruning"): at a middle layer, video/audio tokens in later
+ *                 positions are dropped; no scores are involved.
+ *   FINE prune    (Section 2.2 "Fine pruning", Eq. 4): s = mean over heads of softmax(Q_last K^T); the
+ *                 lowest-scoring tokens are dropped at the layer, and every later layer sees the
+ *                 survivors only.  The full attention map is never formed.
+ *
+ * Conventions for every entry point
+ *   - "dev" pointers are device (HBM) addresses on the current HIP device, "host" pointers are ordinary
+ *     host memory.  The caller owns every buffer.  Nothing here allocates or frees device memory, and
+ *     nothing synchronises: all work is enqueued on the caller's stream (a hipStream_t passed as void*,
+ *     NULL = the default stream) and host arrays may be reused as soon as the call returns.
+ *   - Every argument error is detected on the host before the first launch; the return code is the only
+ *     error channel and fastav_last_error() gives a thread-local description.  Inputs are never written.
+ *   - Matrices are row-major.  Weight matrices are stored [out_features, in_features].
+ *   - Activations/weights are in the model dtype (bf16 or fp32); scores, the residual stream handed back
+ *     in x_out and all index arrays are fp32 / int32.
+ *   - Sequences are packed: sample b owns rows cu_seqlens[b] .. cu_seqlens[b+1]-1.
+ *   - Tie rule of every selection: higher score wins; equal scores go to the lower index; NaN ranks as
+ *     -inf and -0.0 equals +0.0; kept indices are returned ascending.
+ */
+#ifndef FASTAV_H
+#define FASTAV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FASTAV_OK = 0,
+  FASTAV_EINVAL = 1,       /* bad argument (null pointer, k > n, unsorted cu_seqlens, ...) */
+  FASTAV_EUNSUPPORTED = 2, /* valid request the kernels do not cover (e.g. head_dim not 64/128) */
+  FASTAV_EWORKSPACE = 3,   /* workspace too small; see fastav_workspace_bytes */
+  FASTAV_EHIP = 4          /* a HIP launch failed; fastav_last_error() holds hipGetErrorString */
+} fastav_status_t;
+
+typedef enum { FASTAV_TEXT = 0, FASTAV_VIDEO = 1, FASTAV_AUDIO = 2 } fastav_modality_t; /* TEXT is never pruned */
+typedef enum { FASTAV_GLOBAL = 0, FASTAV_FINE = 1 } fastav_prune_kind_t;
+typedef enum { FASTAV_BF16 = 0, FASTAV_F32 = 1 } fastav_dtype_t;
+
+#define FASTAV_MAX_N_LAST 8     /* most last-query rows Eq. 4 may be averaged over */
+#define FASTAV_MAX_PRUNES 128
+#define FASTAV_MAX_GATHER_TENSORS 8
+
+/* One modality span of a sample (Section 2.1: X = [X^vis, X^aud, X^lang]).  start is relative to the
+ * sample; the spans of a sample are sorted, disjoint and cover [0, n). */
+typedef struct { int32_t start, len, modality; } fastav_span_t;
+
+/* One prune step.  layer is 0-based.  GLOBAL acts on the input of that layer; FINE uses that layer's own
+ * attention and shrinks the sequence from its output projection on.  keep_ratio = 1 - P in (0, 1].
+ * The array passed to fastav_prefill is sorted by (layer, kind); at most one of each kind per layer. */
+typedef struct { int32_t layer, kind; double keep_ratio; } fastav_prune_t;
+
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, mlp_dim;
+  float rope_base, rms_eps;
+  int32_t dtype; /* fastav_dtype_t */
+} fastav_model_t;
+
+/* Device pointers in the model dtype, borrowed for the handle's lifetime.
+ * g_attn,g_mlp [hidden]; wq [Hq*dh, hidden]; wk,wv [Hkv*dh, hidden]; wo [hidden, Hq*dh];
+ * w_gate,w_up [mlp, hidden]; w_down [hidden, mlp]. */
+typedef struct {
+  const void *g_attn, *wq, *wk, *wv, *wo, *g_mlp, *w_gate, *w_up, *w_down;
+} fastav_layer_weights_t;
+
+typedef struct fastav_ctx* fastav_handle_t;
+
+/* The packed input batch (Section 2.1). */
+typedef struct {
+  const void* x;               /* dev  [T, hidden] token embeddings, model dtype */
+  const int32_t* cu_seqlens;   /* host [batch+1], cu_seqlens[0] = 0, strictly increasing */
+  int32_t batch;
+  const fastav_span_t* spans;  /* host, all samples' spans concatenated */
+  const int32_t* span_offsets; /* host [batch+1]: sample b owns spans[span_offsets[b] .. span_offsets[b+1]) */
+} fastav_batch_t;
+
+/* Outputs of fastav_prefill.  T_final and the per-layer token counts are known on the host beforehand
+ * from fastav_schedule.  Optional members may be NULL. */
+typedef struct {
+  float* x_out;                /* dev [T_final, hidden] fp32 hidden state after the last layer */
+  int32_t* cu_seqlens_out;     /* dev [batch+1] */
+  int32_t* kept_pos_out;       /* dev [T_final] original in-sample position of every survivor */
+  void* const* kv_out;         /* optional host array [2*n_layers] of dev pointers K_0,V_0,K_1,V_1,...:
+                                  post-RoPE K and V of layer l, [T_l, Hkv, head_dim] in the model dtype, where
+                                  T_l counts the tokens that survive layer l (a FINE layer's K/V are
+                                  compacted).  Entries may be NULL. */
+  float* const* prune_scores_out;   /* optional host array [n_prunes] of dev pointers (entries may be NULL):
+                                       for a FINE prune, the Eq. 4 scores of the tokens entering it, packed */
+  int32_t* const* prune_keep_idx_out; /* optional host array [n_prunes] of dev pointers (entries may be NULL):
+                                       packed row indices (into the layout entering the prune) that survive */
+  float* const* layer_x_out;   /* optional host array [n_layers] of dev pointers (entries may be NULL):
+                                  fp32 hidden state [T_l, hidden] leaving layer l */
+} fastav_prefill_out_t;
+
+/* ---- host helpers (no GPU work) ------------------------------------------------------------------ */
+
+/* The keep-count rule: k = min(n, max(n_protected, ceil(keep_ratio*n - 1e-9))) in double precision
+ * ("tokens with the lowest P% scores are removed", Section 2.2; keep_ratio = 1 - P).  Returns -1 on a
+ * bad argument (n < 0, ratio outside (0,1], n_protected outside [0,n]). */
+int64_t fastav_keep_count(int64_t n, double keep_ratio, int64_t n_protected);
+
+/* Token counts of the whole prefill, from shapes alone (they never depend on data).
+ * tokens_in_out  [n_layers] (optional): total packed tokens that enter attention at each layer;
+ * tokens_out_out [n_layers] (optional): total packed tokens that leave each layer (= T_l of kv_out);
+ * final_lens_out [batch]    (optional): surviving tokens per sample after the last layer.
+ * Protected tokens = TEXT spans plus the last n_last positions of each sample. */
+fastav_status_t fastav_schedule(const fastav_batch_t* in, const fastav_prune_t* prunes, int32_t n_prunes,
+                                int32_t n_last, int32_t n_layers, int64_t* tokens_in_out,
+                                int64_t* tokens_out_out, int32_t* final_lens_out);
+
+const char* fastav_last_error(void);
+
+/* ---- the decoder handle --------------------------------------------------------------------------- */
+
+fastav_status_t fastav_create(const fastav_model_t* model, fastav_handle_t* out);
+void fastav_destroy(fastav_handle_t h);
+fastav_status_t fastav_set_weights(fastav_handle_t h, int32_t layer, const fastav_layer_weights_t* w);
+/* Bytes of device workspace fastav_prefill needs for at most max_total_tokens packed tokens in at most
+ * max_batch samples.  The workspace must be 256-byte aligned; its contents are scratch. */
+fastav_status_t fastav_workspace_bytes(fastav_handle_t h, int64_t max_total_tokens, int32_t max_batch, size_t* out);
+
+/* ---- the hot path ---------------------------------------------------------------------------------- */
+
+/* Pruned prefill (Fig. 3): runs every layer on the packed batch and applies the prune schedule.
+ * n_last >= 1 is the number of last query rows Eq. 4 averages (the paper uses 1).  With no prunes, or
+ * keep_ratio 1.0 everywhere, the result is the plain prefill.  All weights must have been set. */
+fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, const fastav_prune_t* prunes,
+                               int32_t n_prunes, int32_t n_last, void* workspace, size_t workspace_bytes,
+                               const fastav_prefill_out_t* out, void* stream);
+
+/* Eq. 4 on its own: scores_out[j] = mean over the Hq heads (and the last n_last rows r of the sample,
+ * row r seeing keys 0..r) of softmax_j(q_r,h . k_j,g(h) / sqrt(head_dim)), g(h) = h / (Hq/Hkv).
+ * q [T, Hq, head_dim] and k [T, Hkv, head_dim] are post-RoPE features with the given row strides (in
+ * elements); only the last n_last rows of each sample are read from q.  K is streamed once.
+ * workspace: dev, at least fastav_score_workspace_bytes(...) bytes. */
+size_t fastav_score_workspace_bytes(int32_t n_q_heads, int64_t total_tokens, int32_t batch, int32_t n_last);
+fastav_status_t fastav_score(const fastav_model_t* model, const void* q, int64_t q_row_stride, const void* k,
+                             int64_t k_row_stride, const int32_t* cu_seqlens_dev, int32_t batch,
+                             int64_t total_tokens, int32_t max_seqlen, int32_t n_last, float* scores_out,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* Top-k selection per sample plus stable compaction (Section 2.2: "tokens with the lowest P% scores are
+ * removed").  For sample b, keeps every row whose protected_mask byte is non-zero and the
+ * keep_counts[b] - (#protected) highest-scoring other rows (tie rule above); writes the kept packed row
+ * indices, ascending, to keep_idx_out[cu_seqlens_out[b] ..], writes cu_seqlens_out (prefix sums of
+ * keep_counts), and copies rows: dst[i][r] = src[i][keep_idx_out[r]] for each of the n_tensors tensors of
+ * row_bytes[i] bytes per row (src/dst/row_bytes are host arrays of dev pointers / sizes; src and dst must
+ * not overlap).  keep_counts (host, [batch]) must satisfy #protected_b <= keep_counts[b] <= n_b; the lower
+ * bound cannot be checked on the host and a violation keeps all protected rows first, in index order.
+ * scores == NULL selects by position instead (earliest rows win: the GLOBAL rule).
+ * workspace: dev, at least fastav_select_workspace_bytes(batch) bytes. */
+size_t fastav_select_workspace_bytes(int32_t batch);
+fastav_status_t fastav_select_gather(const float* scores, const uint8_t* protected_mask,
+                                     const int32_t* cu_seqlens /* host [batch+1] */,
+                                     const int32_t* keep_counts /* host [batch] */, int32_t batch,
+                                     int32_t n_tensors, const void* const* src, void* const* dst,
+                                     const int64_t* row_bytes, int32_t* keep_idx_out, int32_t* cu_seqlens_out,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- building blocks of one decoder layer (also used by fastav_prefill) --------------------------- */
+
+/* y[r,:] = x[r,:] * rsqrt(mean(x[r,:]^2) + eps) * g.  x fp32 [rows, d] (the residual stream), g and y in
+ * dtype. */
+fastav_status_t fastav_rmsnorm(const float* x, const void* g, void* y, int64_t rows, int32_t d, float eps,
+                               int32_t dtype, void* stream);
+
+/* Rotate-half RoPE in place on the first n_heads heads of each row of x [rows, row_stride] (dtype):
+ * pair (i, i + head_dim/2) of every head is rotated by pos[r] * base^(-2i/head_dim). */
+fastav_status_t fastav_rope(void* x, int64_t row_stride, const int32_t* pos, int64_t rows, int32_t n_heads,
+                            int32_t head_dim, float base, int32_t dtype, void* stream);
+
+/* Linear layers, W stored [N, K] (out, in), A [M, K] in dtype:
+ *   FASTAV_EPI_STORE   : C[M,N] (dtype)  = A W^T
+ *   FASTAV_EPI_RESADD  : R[M,N] (fp32)  += A W^T                       (residual update, C = R)
+ *   FASTAV_EPI_SWIGLU  : C[M,N] (dtype)  = silu(A W^T) * (A W2^T)      (W2 [N, K] is the "up" matrix) */
+typedef enum { FASTAV_EPI_STORE = 0, FASTAV_EPI_RESADD = 1, FASTAV_EPI_SWIGLU = 2 } fastav_epilogue_t;
+fastav_status_t fastav_linear(const void* a, const void* w, const void* w2, void* c, int64_t m, int32_t n,
+                              int32_t k, int32_t epilogue, int32_t dtype, void* stream);
+
+/* Causal grouped-query attention over a packed batch: o = softmax(q k^T / sqrt(head_dim) + causal) v.
+ * q,k,v,o are dev pointers in dtype with row strides in elements (q and o hold Hq heads, k and v Hkv).
+ * last_logits (optional, dev fp32 [Hq, T]) and last_ml (optional, dev fp32 [batch, Hq, 2]) receive, for
+ * the last query row of each sample, the scaled logits against every key of the sample and that row's
+ * (max, sum of exp) — the side output from which Eq. 4 is finalised without a second pass over K. */
+fastav_status_t fastav_attention(const fastav_model_t* model, const void* q, int64_t q_row_stride,
+                                 const void* k, const void* v, int64_t kv_row_stride, void* o,
+                                 int64_t o_row_stride, const int32_t* cu_seqlens_dev, int32_t batch,
+                                 int64_t total_tokens, int32_t max_seqlen, float* last_logits, float* last_ml,
+                                 void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTAV_H */

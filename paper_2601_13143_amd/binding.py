@@ -1,0 +1,336 @@
+"""ctypes binding of libfastav.so: argument marshalling only — every step of the path runs in the HIP
+kernels behind the C ABI declared in include/fastav.h.  PyTorch supplies device memory and streams.
+
+There is no fallback: if the shared library has not been built this module raises on import of the
+library handle (``lib()``), and nothing here computes on the CPU.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libfastav.so")
+
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, 1, 2, 3, 4
+TEXT, VIDEO, AUDIO = 0, 1, 2
+GLOBAL, FINE = 0, 1
+BF16, F32 = 0, 1
+EPI_STORE, EPI_RESADD, EPI_SWIGLU = 0, 1, 2
+MAX_N_LAST, MAX_PRUNES, MAX_GATHER_TENSORS = 8, 128, 8
+
+
+class FastavError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"fastav status {status}: {msg}")
+        self.status = status
+
+
+class Span(C.Structure):
+    _fields_ = [("start", C.c_int32), ("len", C.c_int32), ("modality", C.c_int32)]
+
+
+class Prune(C.Structure):
+    _fields_ = [("layer", C.c_int32), ("kind", C.c_int32), ("keep_ratio", C.c_double)]
+
+
+class Model(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("mlp_dim", C.c_int32), ("rope_base", C.c_float), ("rms_eps", C.c_float),
+                ("dtype", C.c_int32)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("g_attn", "wq", "wk", "wv", "wo", "g_mlp", "w_gate", "w_up", "w_down")]
+
+
+class Batch(C.Structure):
+    _fields_ = [("x", C.c_void_p), ("cu_seqlens", C.POINTER(C.c_int32)), ("batch", C.c_int32),
+                ("spans", C.POINTER(Span)), ("span_offsets", C.POINTER(C.c_int32))]
+
+
+class PrefillOut(C.Structure):
+    _fields_ = [("x_out", C.c_void_p), ("cu_seqlens_out", C.c_void_p), ("kept_pos_out", C.c_void_p),
+                ("kv_out", C.POINTER(C.c_void_p)), ("prune_scores_out", C.POINTER(C.c_void_p)),
+                ("prune_keep_idx_out", C.POINTER(C.c_void_p)), ("layer_x_out", C.POINTER(C.c_void_p))]
+
+
+_lib = None
+
+_SIGS = {
+    "fastav_last_error": (C.c_char_p, []),
+    "fastav_keep_count": (C.c_int64, [C.c_int64, C.c_double, C.c_int64]),
+    "fastav_schedule": (C.c_int, [C.POINTER(Batch), C.POINTER(Prune), C.c_int32, C.c_int32, C.c_int32,
+                                  C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]),
+    "fastav_create": (C.c_int, [C.POINTER(Model), C.POINTER(C.c_void_p)]),
+    "fastav_destroy": (None, [C.c_void_p]),
+    "fastav_set_weights": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(LayerWeights)]),
+    "fastav_workspace_bytes": (C.c_int, [C.c_void_p, C.c_int64, C.c_int32, C.POINTER(C.c_size_t)]),
+    "fastav_prefill": (C.c_int, [C.c_void_p, C.POINTER(Batch), C.POINTER(Prune), C.c_int32, C.c_int32, C.c_void_p,
+                                 C.c_size_t, C.POINTER(PrefillOut), C.c_void_p]),
+    "fastav_score_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int64, C.c_int32, C.c_int32]),
+    "fastav_score": (C.c_int, [C.POINTER(Model), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
+                               C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "fastav_select_workspace_bytes": (C.c_size_t, [C.c_int32]),
+    "fastav_select_gather": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32,
+                                       C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_int64),
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "fastav_rmsnorm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_float, C.c_int32, C.c_void_p]),
+    "fastav_rope": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_void_p]),
+    "fastav_linear": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
+                                C.c_int32, C.c_int32, C.c_void_p]),
+    "fastav_attention": (C.c_int, [C.POINTER(Model), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                   C.c_int64, C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+}
+
+
+def lib() -> C.CDLL:
+    """The loaded C-ABI library.  Raises if it has not been built (there is no CPU fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_13143_amd.build` "
+                                    "(or __graft_entry__.build()); the HIP library is the only implementation")
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def _check(st: int) -> None:
+    if st != OK:
+        raise FastavError(st, lib().fastav_last_error().decode())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError("tensors must be bfloat16 or float32")
+
+
+def make_model(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, mlp_dim, rope_base=1e4, rms_eps=1e-6, dtype=BF16) -> Model:
+    return Model(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, mlp_dim, rope_base, rms_eps, dtype)
+
+
+def _prune_array(prunes: Sequence) -> "C.Array":
+    arr = (Prune * max(1, len(prunes)))()
+    for i, p in enumerate(prunes):
+        arr[i] = Prune(int(p[0]), int(p[1]), float(p[2]))
+    return arr
+
+
+class _HostBatch:
+    """Keeps the host arrays of a fastav_batch_t alive."""
+
+    def __init__(self, x_ptr, cu_seqlens, spans, span_offsets):
+        self.cu = _i32(cu_seqlens)
+        self.spans_np = _i32(spans).reshape(-1, 3)
+        self.off = _i32(span_offsets)
+        self.spans = (Span * max(1, len(self.spans_np)))()
+        for i, (s, l, m) in enumerate(self.spans_np):
+            self.spans[i] = Span(int(s), int(l), int(m))
+        self.c = Batch(x_ptr, self.cu.ctypes.data_as(C.POINTER(C.c_int32)), len(self.cu) - 1, self.spans,
+                       self.off.ctypes.data_as(C.POINTER(C.c_int32)))
+
+
+def fastav_keep_count(n: int, keep_ratio: float, n_protected: int) -> int:
+    return int(lib().fastav_keep_count(n, keep_ratio, n_protected))
+
+
+def fastav_schedule(cu_seqlens, spans, span_offsets, prunes: Sequence, n_last: int, n_layers: int):
+    """-> (tokens_in [n_layers], tokens_out [n_layers], final_lens [batch]) as numpy arrays."""
+    hb = _HostBatch(None, cu_seqlens, spans, span_offsets)
+    tin = np.zeros(max(1, n_layers), dtype=np.int64)
+    tout = np.zeros(max(1, n_layers), dtype=np.int64)
+    fl = np.zeros(hb.c.batch if hb.c.batch > 0 else 1, dtype=np.int32)
+    _check(lib().fastav_schedule(C.byref(hb.c), _prune_array(prunes), len(prunes), n_last, n_layers,
+                                 tin.ctypes.data_as(C.POINTER(C.c_int64)), tout.ctypes.data_as(C.POINTER(C.c_int64)),
+                                 fl.ctypes.data_as(C.POINTER(C.c_int32))))
+    return tin[:n_layers], tout[:n_layers], fl
+
+
+class Decoder:
+    """Owns a fastav handle, the device weights handed to it and a reusable workspace tensor."""
+
+    def __init__(self, model: Model):
+        self.model = model
+        self._h = C.c_void_p()
+        _check(lib().fastav_create(C.byref(model), C.byref(self._h)))
+        self._weights: Dict[int, Dict[str, torch.Tensor]] = {}
+        self._ws: Optional[torch.Tensor] = None
+
+    def __del__(self):
+        if getattr(self, "_h", None) and self._h.value and _lib is not None:
+            _lib.fastav_destroy(self._h)
+            self._h = C.c_void_p()
+
+    @property
+    def torch_dtype(self):
+        return torch.bfloat16 if self.model.dtype == BF16 else torch.float32
+
+    def fastav_set_weights(self, layer: int, weights: Dict[str, torch.Tensor]) -> None:
+        """weights: name -> device tensor in the model dtype ([out, in] matrices); kept alive by the decoder."""
+        w = {k: v.contiguous() for k, v in weights.items()}
+        lw = LayerWeights(*[w[n].data_ptr() for n, _ in LayerWeights._fields_])
+        _check(lib().fastav_set_weights(self._h, layer, C.byref(lw)))
+        self._weights[layer] = w
+
+    def fastav_workspace_bytes(self, max_total_tokens: int, max_batch: int) -> int:
+        out = C.c_size_t()
+        _check(lib().fastav_workspace_bytes(self._h, max_total_tokens, max_batch, C.byref(out)))
+        return out.value
+
+    def workspace(self, total_tokens: int, batch: int) -> torch.Tensor:
+        need = self.fastav_workspace_bytes(total_tokens, batch)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = None
+            self._ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        return self._ws
+
+    def fastav_prefill(self, x: torch.Tensor, cu_seqlens, spans, span_offsets, prunes: Sequence, n_last: int = 1,
+                       want_kv: bool = False, want_trace: bool = False, want_layers: bool = False,
+                       outputs: Optional[Dict] = None) -> Dict:
+        """Runs fastav_prefill on the current stream.  ``prunes``: sequence of (layer, kind, keep_ratio).
+        Output tensors are allocated here (or reused from ``outputs``, the dict a previous call returned)."""
+        m = self.model
+        hb = _HostBatch(x.data_ptr(), cu_seqlens, spans, span_offsets)
+        B, T0 = hb.c.batch, int(hb.cu[-1])
+        if x.dtype != self.torch_dtype or not x.is_contiguous() or tuple(x.shape) != (T0, m.hidden):
+            raise ValueError("x must be a contiguous [total_tokens, hidden] tensor in the model dtype")
+        tin, tout, fl = fastav_schedule(hb.cu, hb.spans_np, hb.off, prunes, n_last, m.n_layers)
+        Tf = int(fl.sum())
+        dev = x.device
+        o = outputs if outputs is not None else {}
+        if outputs is None:
+            o["x_out"] = torch.empty((Tf, m.hidden), dtype=torch.float32, device=dev)
+            o["cu_seqlens_out"] = torch.empty(B + 1, dtype=torch.int32, device=dev)
+            o["kept_pos"] = torch.empty(Tf, dtype=torch.int32, device=dev)
+            if want_kv:
+                kd = (m.n_kv_heads, m.head_dim)
+                o["kv"] = [(torch.empty((int(tout[l]),) + kd, dtype=self.torch_dtype, device=dev),
+                            torch.empty((int(tout[l]),) + kd, dtype=self.torch_dtype, device=dev)) for l in range(m.n_layers)]
+            if want_trace:
+                # packed tokens entering prune i = survivors of the schedule truncated to its first i prunes
+                stage_tot = [int(fastav_schedule(hb.cu, hb.spans_np, hb.off, prunes[:i], n_last, m.n_layers)[2].sum())
+                             for i in range(len(prunes) + 1)]
+                o["prune_scores"] = [torch.zeros(stage_tot[i], dtype=torch.float32, device=dev) if p[1] == FINE else None
+                                     for i, p in enumerate(prunes)]
+                o["prune_keep_idx"] = [torch.empty(stage_tot[i + 1], dtype=torch.int32, device=dev) for i in range(len(prunes))]
+            if want_layers:
+                o["layer_x"] = [torch.empty((int(tout[l]), m.hidden), dtype=torch.float32, device=dev) for l in range(m.n_layers)]
+        po = PrefillOut(o["x_out"].data_ptr(), o["cu_seqlens_out"].data_ptr(), o["kept_pos"].data_ptr(), None, None, None, None)
+        keep = []
+        if "kv" in o:
+            arr = (C.c_void_p * (2 * m.n_layers))(*[t.data_ptr() for kv in o["kv"] for t in kv])
+            po.kv_out = arr; keep.append(arr)
+        if "prune_scores" in o:
+            a1 = (C.c_void_p * max(1, len(prunes)))(*[_ptr(t) for t in o["prune_scores"]])
+            a2 = (C.c_void_p * max(1, len(prunes)))(*[_ptr(t) for t in o["prune_keep_idx"]])
+            po.prune_scores_out, po.prune_keep_idx_out = a1, a2; keep += [a1, a2]
+        if "layer_x" in o:
+            a3 = (C.c_void_p * m.n_layers)(*[t.data_ptr() for t in o["layer_x"]])
+            po.layer_x_out = a3; keep.append(a3)
+        ws = self.workspace(T0, B)
+        _check(lib().fastav_prefill(self._h, C.byref(hb.c), _prune_array(prunes), len(prunes), n_last, ws.data_ptr(),
+                                    ws.numel(), C.byref(po), _stream()))
+        o["tokens_in"], o["tokens_out"], o["final_lens"] = tin, tout, fl
+        return o
+
+
+def fastav_score(model: Model, q: torch.Tensor, k: torch.Tensor, cu_seqlens_dev: torch.Tensor, max_seqlen: int,
+                 n_last: int = 1, q_row_stride: Optional[int] = None, k_row_stride: Optional[int] = None) -> torch.Tensor:
+    """q [T, Hq, dh], k [T, Hkv, dh] (or 2-D views with explicit row strides) -> fp32 scores [T]."""
+    T = q.shape[0]
+    B = cu_seqlens_dev.numel() - 1
+    qs = q_row_stride if q_row_stride is not None else q.stride(0)
+    ks = k_row_stride if k_row_stride is not None else k.stride(0)
+    out = torch.empty(T, dtype=torch.float32, device=q.device)
+    need = lib().fastav_score_workspace_bytes(model.n_q_heads, T, B, n_last)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    _check(lib().fastav_score(C.byref(model), q.data_ptr(), qs, k.data_ptr(), ks, cu_seqlens_dev.data_ptr(), B, T,
+                              max_seqlen, n_last, out.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+    return out
+
+
+def fastav_select_gather(scores: Optional[torch.Tensor], protected_mask: torch.Tensor, cu_seqlens, keep_counts,
+                         tensors: Sequence[torch.Tensor] = ()):
+    """-> (keep_idx int32 [total_keep], cu_seqlens_out int32 [B+1] (device), [gathered tensors]).
+    ``tensors`` are contiguous [T, ...] device tensors gathered along dim 0."""
+    cu = _i32(cu_seqlens)
+    kc = _i32(keep_counts)
+    B = len(cu) - 1
+    dev = protected_mask.device
+    total_keep = int(kc.sum())
+    keep_idx = torch.empty(max(total_keep, 1), dtype=torch.int32, device=dev)
+    cu_out = torch.empty(B + 1, dtype=torch.int32, device=dev)
+    dsts = [torch.empty((total_keep,) + tuple(t.shape[1:]), dtype=t.dtype, device=dev) for t in tensors]
+    nt = len(tensors)
+    src = (C.c_void_p * max(1, nt))(*[t.data_ptr() for t in tensors])
+    dst = (C.c_void_p * max(1, nt))(*[t.data_ptr() if t.numel() else None for t in dsts])
+    rb = (C.c_int64 * max(1, nt))(*[t.stride(0) * t.element_size() if t.dim() > 1 else t.element_size() for t in tensors])
+    need = lib().fastav_select_workspace_bytes(B)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    _check(lib().fastav_select_gather(_ptr(scores), protected_mask.data_ptr(), cu.ctypes.data_as(C.POINTER(C.c_int32)),
+                                      kc.ctypes.data_as(C.POINTER(C.c_int32)), B, nt, src, dst, rb, keep_idx.data_ptr(),
+                                      cu_out.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+    return keep_idx[:total_keep], cu_out, dsts
+
+
+def fastav_rmsnorm(x: torch.Tensor, g: torch.Tensor, eps: float) -> torch.Tensor:
+    y = torch.empty(x.shape, dtype=g.dtype, device=x.device)
+    _check(lib().fastav_rmsnorm(x.data_ptr(), g.data_ptr(), y.data_ptr(), x.shape[0], x.shape[1], eps, _dtype_code(g), _stream()))
+    return y
+
+
+def fastav_rope(x: torch.Tensor, pos: torch.Tensor, n_heads: int, head_dim: int, base: float) -> torch.Tensor:
+    """In place on x [rows, row_stride]; returns x."""
+    _check(lib().fastav_rope(x.data_ptr(), x.stride(0), pos.data_ptr(), x.shape[0], n_heads, head_dim, base,
+                             _dtype_code(x), _stream()))
+    return x
+
+
+def fastav_linear(a: torch.Tensor, w: torch.Tensor, epilogue: int = EPI_STORE, w2: Optional[torch.Tensor] = None,
+                  c: Optional[torch.Tensor] = None) -> torch.Tensor:
+    m, k = a.shape
+    n = w.shape[0]
+    if c is None:
+        if epilogue == EPI_RESADD:
+            raise ValueError("the residual epilogue updates c in place: pass it")
+        c = torch.empty((m, n), dtype=a.dtype, device=a.device)
+    _check(lib().fastav_linear(a.data_ptr(), w.data_ptr(), _ptr(w2), c.data_ptr(), m, n, k, epilogue, _dtype_code(a), _stream()))
+    return c
+
+
+def fastav_attention(model: Model, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens_dev: torch.Tensor,
+                     max_seqlen: int, want_last: bool = False):
+    """q [T,Hq,dh], k,v [T,Hkv,dh] (row strides taken from the tensors) -> o [T,Hq,dh] (, last_logits [Hq,T], last_ml [B,Hq,2])."""
+    T = q.shape[0]
+    B = cu_seqlens_dev.numel() - 1
+    o = torch.empty((T, model.n_q_heads, model.head_dim), dtype=q.dtype, device=q.device)
+    ll = torch.full((model.n_q_heads, T), float("-inf"), dtype=torch.float32, device=q.device) if want_last else None
+    ml = torch.zeros((B, model.n_q_heads, 2), dtype=torch.float32, device=q.device) if want_last else None
+    if k.stride(0) != v.stride(0):
+        raise ValueError("k and v must share a row stride")
+    _check(lib().fastav_attention(C.byref(model), q.data_ptr(), q.stride(0), k.data_ptr(), v.data_ptr(), k.stride(0),
+                                  o.data_ptr(), o.stride(0), cu_seqlens_dev.data_ptr(), B, T, max_seqlen, _ptr(ll), _ptr(ml), _stream()))
+    return (o, ll, ml) if want_last else o

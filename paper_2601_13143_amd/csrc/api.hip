@@ -1,0 +1,551 @@
+// C ABI of the FastAV pruned-prefill library: argument validation, the host-side token schedule, workspace
+// carving and the per-layer launch sequence.  Token counts after every prune depend only on the sequence
+// lengths and keep ratios, so the whole schedule is computed on the host up front and the stream is never
+// synchronised.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "common.hpp"
+
+namespace fastav {
+
+static thread_local char g_err[512] = "";
+
+fastav_status_t fail(fastav_status_t st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+fastav_status_t check_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(FASTAV_EHIP, "%s: %s", what, hipGetErrorString(e));
+  return FASTAV_OK;
+}
+
+fastav_status_t launch_linear_generic(const void* a, const void* w, const void* w2, void* c, int64_t ldc, int64_t m,
+                                      int n, int k, int epilogue, int dtype, hipStream_t s);
+bool mfma_linear_supported(int64_t m, int n, int k, int epilogue, int dtype);
+fastav_status_t launch_linear_mfma(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
+                                   const void* w2, void* c, int64_t ldc, int64_t m, int n, int k, int epilogue,
+                                   hipStream_t s);
+fastav_status_t launch_attention_generic(const void* q, int64_t q_stride, const void* k, const void* v,
+                                         int64_t kv_stride, void* o, int64_t o_stride, const int32_t* cu, int batch,
+                                         int64_t T, int max_seqlen, int Hq, int Hkv, int dh, float* last_logits,
+                                         float* last_ml, int dtype, hipStream_t s);
+bool mfma_attention_supported(int dh, int dtype, int64_t q_stride, int64_t kv_stride, int64_t o_stride);
+fastav_status_t launch_attention_mfma(const void* q, int64_t q_stride, const void* k, const void* v,
+                                      int64_t kv_stride, void* o, int64_t o_stride, const int32_t* cu, int batch,
+                                      int64_t T, int max_seqlen, int Hq, int Hkv, int dh, float* last_logits,
+                                      float* last_ml, hipStream_t s);
+
+// One linear layer whose weight rows may come from up to three matrices stacked along N (Q|K|V).
+static fastav_status_t linear_segments(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
+                                       const void* w2, void* c, int64_t ldc, int64_t m, int k, int epilogue, int dtype,
+                                       hipStream_t s) {
+  int n = 0;
+  for (int i = 0; i < n_seg; ++i) n += seg_rows[i];
+  if (m == 0 || n == 0) return FASTAV_OK;
+  bool ok = mfma_linear_supported(m, n, k, epilogue, dtype);
+  for (int i = 0; i < n_seg && ok; ++i) ok = mfma_linear_supported(m, seg_rows[i], k, epilogue, dtype);
+  if (ok) return launch_linear_mfma(a, w_seg, seg_rows, n_seg, w2, c, ldc, m, n, k, epilogue, s);
+  const size_t es = dtype == FASTAV_BF16 ? 2 : 4;
+  int col = 0;
+  for (int i = 0; i < n_seg; ++i) {
+    void* ci = epilogue == FASTAV_EPI_RESADD ? (void*)((float*)c + col) : (void*)((char*)c + (size_t)col * es);
+    fastav_status_t st = launch_linear_generic(a, w_seg[i], w2, ci, ldc, m, seg_rows[i], k, epilogue, dtype, s);
+    if (st != FASTAV_OK) return st;
+    col += seg_rows[i];
+  }
+  return FASTAV_OK;
+}
+
+fastav_status_t launch_linear(const void* a, const void* w, const void* w2, void* c, int64_t m, int n, int k,
+                              int epilogue, int dtype, hipStream_t s) {
+  const void* seg[1] = {w};
+  int rows[1] = {n};
+  return linear_segments(a, seg, rows, 1, w2, c, n, m, k, epilogue, dtype, s);
+}
+
+fastav_status_t launch_attention(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
+                                 void* o, int64_t o_stride, const int32_t* cu, int batch, int64_t T, int max_seqlen,
+                                 int Hq, int Hkv, int dh, float* last_logits, float* last_ml, int dtype,
+                                 hipStream_t s) {
+  if (mfma_attention_supported(dh, dtype, q_stride, kv_stride, o_stride))
+    return launch_attention_mfma(q, q_stride, k, v, kv_stride, o, o_stride, cu, batch, T, max_seqlen, Hq, Hkv, dh,
+                                 last_logits, last_ml, s);
+  return launch_attention_generic(q, q_stride, k, v, kv_stride, o, o_stride, cu, batch, T, max_seqlen, Hq, Hkv, dh,
+                                  last_logits, last_ml, dtype, s);
+}
+
+// ------------------------------------------------------------------------------------------ validation
+static int64_t keep_count(int64_t n, double r, int64_t n_prot) {
+  int64_t k = (int64_t)std::ceil(r * (double)n - 1e-9);
+  if (k < n_prot) k = n_prot;
+  if (k > n) k = n;
+  return k;
+}
+
+static fastav_status_t check_model(const fastav_model_t* m) {
+  if (!m) return fail(FASTAV_EINVAL, "model is NULL");
+  if (m->n_layers < 1 || m->hidden < 1 || m->n_q_heads < 1 || m->n_kv_heads < 1 || m->mlp_dim < 1 || m->head_dim < 1)
+    return fail(FASTAV_EINVAL, "model dimensions must be positive");
+  if (m->n_q_heads % m->n_kv_heads) return fail(FASTAV_EINVAL, "n_q_heads must be a multiple of n_kv_heads");
+  if (m->dtype != FASTAV_BF16 && m->dtype != FASTAV_F32) return fail(FASTAV_EINVAL, "dtype must be FASTAV_BF16 or FASTAV_F32");
+  if (!(m->rope_base > 1.0f) || !(m->rms_eps >= 0.0f)) return fail(FASTAV_EINVAL, "rope_base must exceed 1 and rms_eps be >= 0");
+  if (m->head_dim != 64 && m->head_dim != 128) return fail(FASTAV_EUNSUPPORTED, "head_dim must be 64 or 128");
+  if ((int64_t)m->n_q_heads * (m->head_dim + 128) * 4 > 64 * 1024)
+    return fail(FASTAV_EUNSUPPORTED, "n_q_heads*(head_dim+128)*4 bytes must fit 64 KB of LDS");
+  return FASTAV_OK;
+}
+
+static fastav_status_t check_batch(const fastav_batch_t* in, bool need_x, int64_t* T_out, int* max_len_out) {
+  if (!in) return fail(FASTAV_EINVAL, "batch descriptor is NULL");
+  if (in->batch < 1) return fail(FASTAV_EINVAL, "batch must be >= 1");
+  if (!in->cu_seqlens || !in->spans || !in->span_offsets) return fail(FASTAV_EINVAL, "cu_seqlens/spans/span_offsets is NULL");
+  if (need_x && !in->x) return fail(FASTAV_EINVAL, "x is NULL");
+  if (in->cu_seqlens[0] != 0 || in->span_offsets[0] != 0) return fail(FASTAV_EINVAL, "cu_seqlens[0] and span_offsets[0] must be 0");
+  int max_len = 0;
+  for (int b = 0; b < in->batch; ++b) {
+    const int64_t n = (int64_t)in->cu_seqlens[b + 1] - in->cu_seqlens[b];
+    if (n < 1) return fail(FASTAV_EINVAL, "cu_seqlens must be strictly increasing (sample %d)", b);
+    if (in->span_offsets[b + 1] <= in->span_offsets[b]) return fail(FASTAV_EINVAL, "sample %d has no spans", b);
+    int64_t at = 0;
+    for (int si = in->span_offsets[b]; si < in->span_offsets[b + 1]; ++si) {
+      const fastav_span_t& sp = in->spans[si];
+      if (sp.len < 1 || sp.start != at) return fail(FASTAV_EINVAL, "spans of sample %d must be sorted, disjoint and cover [0,n)", b);
+      if (sp.modality < FASTAV_TEXT || sp.modality > FASTAV_AUDIO) return fail(FASTAV_EINVAL, "bad modality in sample %d", b);
+      at += sp.len;
+    }
+    if (at != n) return fail(FASTAV_EINVAL, "spans of sample %d cover %lld of %lld tokens", b, (long long)at, (long long)n);
+    if (n > max_len) max_len = (int)n;
+  }
+  *T_out = in->cu_seqlens[in->batch];
+  *max_len_out = max_len;
+  return FASTAV_OK;
+}
+
+static fastav_status_t check_prunes(const fastav_prune_t* prunes, int n_prunes, int n_layers, int n_last) {
+  if (n_prunes < 0 || n_prunes > FASTAV_MAX_PRUNES) return fail(FASTAV_EINVAL, "n_prunes must be in [0, %d]", FASTAV_MAX_PRUNES);
+  if (n_prunes > 0 && !prunes) return fail(FASTAV_EINVAL, "prunes is NULL");
+  if (n_last < 1 || n_last > FASTAV_MAX_N_LAST) return fail(FASTAV_EINVAL, "n_last must be in [1, %d]", FASTAV_MAX_N_LAST);
+  for (int i = 0; i < n_prunes; ++i) {
+    const fastav_prune_t& p = prunes[i];
+    if (p.layer < 0 || p.layer >= n_layers) return fail(FASTAV_EINVAL, "prune %d: layer %d out of range", i, p.layer);
+    if (p.kind != FASTAV_GLOBAL && p.kind != FASTAV_FINE) return fail(FASTAV_EINVAL, "prune %d: bad kind", i);
+    if (!(p.keep_ratio > 0.0 && p.keep_ratio <= 1.0)) return fail(FASTAV_EINVAL, "prune %d: keep_ratio must be in (0,1]", i);
+    if (i > 0) {
+      const fastav_prune_t& q = prunes[i - 1];
+      if (q.layer > p.layer || (q.layer == p.layer && q.kind >= p.kind))
+        return fail(FASTAV_EINVAL, "prunes must be sorted by (layer, kind) without duplicates");
+    }
+  }
+  return FASTAV_OK;
+}
+
+// Number of tokens of sample b a prune may never remove: TEXT spans plus the last n_last positions.
+static int64_t protected_count(const fastav_batch_t* in, int b, int n_last) {
+  const int64_t n = (int64_t)in->cu_seqlens[b + 1] - in->cu_seqlens[b];
+  const int64_t tail0 = n - n_last > 0 ? n - n_last : 0;
+  int64_t cnt = 0;
+  for (int si = in->span_offsets[b]; si < in->span_offsets[b + 1]; ++si) {
+    const fastav_span_t& sp = in->spans[si];
+    const int64_t lo = sp.start, hi = (int64_t)sp.start + sp.len;
+    if (sp.modality == FASTAV_TEXT) cnt += sp.len;
+    else if (hi > tail0) cnt += hi - (lo > tail0 ? lo : tail0);
+  }
+  return cnt;
+}
+
+// lens[stage][b]: stage 0 = input, stage i+1 = after prune i.
+static void build_schedule(const fastav_batch_t* in, const fastav_prune_t* prunes, int n_prunes, int n_last,
+                           std::vector<std::vector<int32_t>>& lens) {
+  lens.assign(n_prunes + 1, std::vector<int32_t>(in->batch));
+  for (int b = 0; b < in->batch; ++b) {
+    const int64_t n_prot = protected_count(in, b, n_last);
+    int64_t cur = (int64_t)in->cu_seqlens[b + 1] - in->cu_seqlens[b];
+    lens[0][b] = (int32_t)cur;
+    for (int i = 0; i < n_prunes; ++i) {
+      cur = keep_count(cur, (double)prunes[i].keep_ratio, n_prot);
+      lens[i + 1][b] = (int32_t)cur;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------ workspace
+struct Workspace {
+  size_t resid[2], hn, qkv, attn[2], hmlp, logits, ml, partials, scores, pos[2], prot[2], keep_idx, cu, span_off,
+      spans, total;
+};
+
+static Workspace carve(const fastav_model_t& m, int64_t T, int B) {
+  Workspace w;
+  size_t at = 0;
+  auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes, 256); return o; };
+  const size_t es = m.dtype == FASTAV_BF16 ? 2 : 4;
+  const size_t qd = (size_t)m.n_q_heads * m.head_dim, kd = (size_t)m.n_kv_heads * m.head_dim;
+  w.resid[0] = take((size_t)T * m.hidden * 4);
+  w.resid[1] = take((size_t)T * m.hidden * 4);
+  w.hn = take((size_t)T * m.hidden * es);
+  w.qkv = take((size_t)T * (qd + 2 * kd) * es);
+  w.attn[0] = take((size_t)T * qd * es);
+  w.attn[1] = take((size_t)T * qd * es);
+  w.hmlp = take((size_t)T * m.mlp_dim * es);
+  w.logits = take((size_t)FASTAV_MAX_N_LAST * m.n_q_heads * T * 4);
+  w.ml = take((size_t)B * FASTAV_MAX_N_LAST * m.n_q_heads * 2 * 4);
+  w.partials = take(score_partials_bytes(m.n_q_heads, T, B, FASTAV_MAX_N_LAST));
+  w.scores = take((size_t)T * 4);
+  w.pos[0] = take((size_t)T * 4);
+  w.pos[1] = take((size_t)T * 4);
+  w.prot[0] = take((size_t)T);
+  w.prot[1] = take((size_t)T);
+  w.keep_idx = take((size_t)T * 4);
+  w.cu = take((size_t)(FASTAV_MAX_PRUNES + 1) * (B + 1) * 4);
+  w.span_off = take((size_t)(B + 1) * 4);
+  w.spans = take((size_t)T * sizeof(fastav_span_t));       // a span holds >= 1 token
+  w.total = at;
+  return w;
+}
+
+}  // namespace fastav
+
+using namespace fastav;
+
+struct fastav_ctx {
+  fastav_model_t m;
+  std::vector<fastav_layer_weights_t> w;
+  std::vector<char> has_w;
+};
+
+extern "C" {
+
+const char* fastav_last_error(void) { return g_err; }
+
+int64_t fastav_keep_count(int64_t n, double keep_ratio, int64_t n_protected) {
+  if (n < 0 || !(keep_ratio > 0.0 && keep_ratio <= 1.0) || n_protected < 0 || n_protected > n) return -1;
+  return keep_count(n, keep_ratio, n_protected);
+}
+
+fastav_status_t fastav_schedule(const fastav_batch_t* in, const fastav_prune_t* prunes, int32_t n_prunes,
+                                int32_t n_last, int32_t n_layers, int64_t* tokens_in_out, int64_t* tokens_out_out,
+                                int32_t* final_lens_out) {
+  int64_t T; int max_len;
+  fastav_status_t st = check_batch(in, false, &T, &max_len);
+  if (st != FASTAV_OK) return st;
+  if (n_layers < 1) return fail(FASTAV_EINVAL, "n_layers must be >= 1");
+  st = check_prunes(prunes, n_prunes, n_layers, n_last);
+  if (st != FASTAV_OK) return st;
+  std::vector<std::vector<int32_t>> lens;
+  build_schedule(in, prunes, n_prunes, n_last, lens);
+  std::vector<int64_t> tot(n_prunes + 1, 0);
+  for (int i = 0; i <= n_prunes; ++i) for (int b = 0; b < in->batch; ++b) tot[i] += lens[i][b];
+  int stage = 0, pi = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    if (pi < n_prunes && prunes[pi].layer == l && prunes[pi].kind == FASTAV_GLOBAL) { ++stage; ++pi; }
+    if (tokens_in_out) tokens_in_out[l] = tot[stage];
+    if (pi < n_prunes && prunes[pi].layer == l && prunes[pi].kind == FASTAV_FINE) { ++stage; ++pi; }
+    if (tokens_out_out) tokens_out_out[l] = tot[stage];
+  }
+  if (final_lens_out) for (int b = 0; b < in->batch; ++b) final_lens_out[b] = lens[n_prunes][b];
+  return FASTAV_OK;
+}
+
+fastav_status_t fastav_create(const fastav_model_t* model, fastav_handle_t* out) {
+  if (!out) return fail(FASTAV_EINVAL, "out is NULL");
+  *out = nullptr;
+  fastav_status_t st = check_model(model);
+  if (st != FASTAV_OK) return st;
+  fastav_ctx* c = new (std::nothrow) fastav_ctx();
+  if (!c) return fail(FASTAV_EINVAL, "out of host memory");
+  c->m = *model;
+  c->w.resize(model->n_layers);
+  c->has_w.assign(model->n_layers, 0);
+  *out = c;
+  return FASTAV_OK;
+}
+
+void fastav_destroy(fastav_handle_t h) { delete h; }
+
+fastav_status_t fastav_set_weights(fastav_handle_t h, int32_t layer, const fastav_layer_weights_t* w) {
+  if (!h || !w) return fail(FASTAV_EINVAL, "handle or weights is NULL");
+  if (layer < 0 || layer >= h->m.n_layers) return fail(FASTAV_EINVAL, "layer %d out of range", layer);
+  if (!w->g_attn || !w->wq || !w->wk || !w->wv || !w->wo || !w->g_mlp || !w->w_gate || !w->w_up || !w->w_down)
+    return fail(FASTAV_EINVAL, "a weight pointer of layer %d is NULL", layer);
+  const uintptr_t all = (uintptr_t)w->g_attn | (uintptr_t)w->wq | (uintptr_t)w->wk | (uintptr_t)w->wv | (uintptr_t)w->wo |
+                        (uintptr_t)w->g_mlp | (uintptr_t)w->w_gate | (uintptr_t)w->w_up | (uintptr_t)w->w_down;
+  if (all % 16) return fail(FASTAV_EINVAL, "weight pointers must be 16-byte aligned");
+  h->w[layer] = *w;
+  h->has_w[layer] = 1;
+  return FASTAV_OK;
+}
+
+fastav_status_t fastav_workspace_bytes(fastav_handle_t h, int64_t max_total_tokens, int32_t max_batch, size_t* out) {
+  if (!h || !out) return fail(FASTAV_EINVAL, "handle or out is NULL");
+  if (max_total_tokens < 1 || max_batch < 1 || max_total_tokens > 0x7FFFFFFF)
+    return fail(FASTAV_EINVAL, "max_total_tokens must be in [1, 2^31) and max_batch >= 1");
+  *out = carve(h->m, max_total_tokens, max_batch).total;
+  return FASTAV_OK;
+}
+
+#define FASTAV_TRY(expr) do { fastav_status_t st__ = (expr); if (st__ != FASTAV_OK) return st__; } while (0)
+
+fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, const fastav_prune_t* prunes,
+                               int32_t n_prunes, int32_t n_last, void* workspace, size_t workspace_bytes,
+                               const fastav_prefill_out_t* out, void* stream) {
+  if (!h) return fail(FASTAV_EINVAL, "handle is NULL");
+  const fastav_model_t& m = h->m;
+  int64_t T0; int max_len0;
+  FASTAV_TRY(check_batch(in, true, &T0, &max_len0));
+  FASTAV_TRY(check_prunes(prunes, n_prunes, m.n_layers, n_last));
+  if (!out || !out->x_out || !out->cu_seqlens_out || !out->kept_pos_out)
+    return fail(FASTAV_EINVAL, "out, x_out, cu_seqlens_out and kept_pos_out must be non-NULL");
+  if (!workspace || ((uintptr_t)workspace % 256)) return fail(FASTAV_EINVAL, "workspace must be non-NULL and 256-byte aligned");
+  if (((uintptr_t)in->x % 16) || ((uintptr_t)out->x_out % 16)) return fail(FASTAV_EINVAL, "x and x_out must be 16-byte aligned");
+  for (int l = 0; l < m.n_layers; ++l)
+    if (!h->has_w[l]) return fail(FASTAV_EINVAL, "weights of layer %d were never set", l);
+  const int B = in->batch;
+  const Workspace ws = carve(m, T0, B);
+  if (workspace_bytes < ws.total)
+    return fail(FASTAV_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, ws.total);
+  if ((size_t)in->span_offsets[B] > (size_t)T0) return fail(FASTAV_EINVAL, "more spans than tokens");
+
+  // ---- host schedule: per-stage lengths, prefix sums, totals, longest sample
+  std::vector<std::vector<int32_t>> lens;
+  build_schedule(in, prunes, n_prunes, n_last, lens);
+  const int n_stages = n_prunes + 1;
+  std::vector<int32_t> cu_host((size_t)n_stages * (B + 1));
+  std::vector<int64_t> T_stage(n_stages);
+  std::vector<int> maxlen_stage(n_stages);
+  for (int i = 0; i < n_stages; ++i) {
+    int32_t* cu = &cu_host[(size_t)i * (B + 1)];
+    cu[0] = 0;
+    int mx = 0;
+    for (int b = 0; b < B; ++b) { cu[b + 1] = cu[b] + lens[i][b]; if (lens[i][b] > mx) mx = lens[i][b]; }
+    T_stage[i] = cu[B];
+    maxlen_stage[i] = mx;
+  }
+
+  hipStream_t s = (hipStream_t)stream;
+  char* base = (char*)workspace;
+  float* resid[2] = {(float*)(base + ws.resid[0]), (float*)(base + ws.resid[1])};
+  void* hn = base + ws.hn;
+  char* qkv = base + ws.qkv;
+  void* attn[2] = {base + ws.attn[0], base + ws.attn[1]};
+  void* hmlp = base + ws.hmlp;
+  float* logits = (float*)(base + ws.logits);
+  float* ml = (float*)(base + ws.ml);
+  float* partials = (float*)(base + ws.partials);
+  float* scores_ws = (float*)(base + ws.scores);
+  int32_t* pos[2] = {(int32_t*)(base + ws.pos[0]), (int32_t*)(base + ws.pos[1])};
+  uint8_t* prot[2] = {(uint8_t*)(base + ws.prot[0]), (uint8_t*)(base + ws.prot[1])};
+  int32_t* keep_idx_ws = (int32_t*)(base + ws.keep_idx);
+  int32_t* cu_dev = (int32_t*)(base + ws.cu);
+  int32_t* span_off_dev = (int32_t*)(base + ws.span_off);
+  fastav_span_t* spans_dev = (fastav_span_t*)(base + ws.spans);
+
+  FASTAV_TRY(upload_small(cu_dev, cu_host.data(), cu_host.size() * 4, s));
+  FASTAV_TRY(upload_small(span_off_dev, in->span_offsets, (size_t)(B + 1) * 4, s));
+  FASTAV_TRY(upload_small(spans_dev, in->spans, (size_t)in->span_offsets[B] * sizeof(fastav_span_t), s));
+  FASTAV_TRY(launch_init_tokens(cu_dev, span_off_dev, spans_dev, B, T0, max_len0, n_last, pos[0], prot[0], s));
+  FASTAV_TRY(launch_to_f32(in->x, resid[0], T0 * m.hidden, m.dtype, s));
+
+  const size_t es = m.dtype == FASTAV_BF16 ? 2 : 4;
+  const int qd = m.n_q_heads * m.head_dim, kd = m.n_kv_heads * m.head_dim;
+  const int64_t qkv_stride = qd + 2 * kd;                     // elements per row of the fused Q|K|V buffer
+  int cur = 0, stage = 0, pi = 0;
+  for (int l = 0; l < m.n_layers; ++l) {
+    const fastav_layer_weights_t& W = h->w[l];
+    // ---- GLOBAL prune on the layer input: positional selection, then compaction of the residual stream
+    if (pi < n_prunes && prunes[pi].layer == l && prunes[pi].kind == FASTAV_GLOBAL) {
+      const int32_t* cu_in = cu_dev + (size_t)stage * (B + 1);
+      const int32_t* cu_nx = cu_dev + (size_t)(stage + 1) * (B + 1);
+      int32_t* kidx = (out->prune_keep_idx_out && out->prune_keep_idx_out[pi]) ? out->prune_keep_idx_out[pi] : keep_idx_ws;
+      FASTAV_TRY(launch_select(nullptr, prot[cur], cu_in, cu_nx, B, maxlen_stage[stage], kidx, s));
+      GatherTensor g[3] = {{resid[cur], resid[cur ^ 1], (int64_t)m.hidden * 4, 0},
+                           {pos[cur], pos[cur ^ 1], 4, 0},
+                           {prot[cur], prot[cur ^ 1], 1, 0}};
+      FASTAV_TRY(launch_gather(g, 3, kidx, T_stage[stage + 1], s));
+      cur ^= 1; ++stage; ++pi;
+    }
+    const int64_t Tl = T_stage[stage];
+    const int32_t* cu_l = cu_dev + (size_t)stage * (B + 1);
+    const bool fine = pi < n_prunes && prunes[pi].layer == l && prunes[pi].kind == FASTAV_FINE;
+    const bool side = fine && n_last == 1;
+
+    FASTAV_TRY(launch_rmsnorm(resid[cur], W.g_attn, hn, Tl, m.hidden, m.rms_eps, m.dtype, s));
+    {
+      const void* seg[3] = {W.wq, W.wk, W.wv};
+      int rows[3] = {qd, kd, kd};
+      FASTAV_TRY(linear_segments(hn, seg, rows, 3, nullptr, qkv, qkv_stride, Tl, m.hidden, FASTAV_EPI_STORE, m.dtype, s));
+    }
+    FASTAV_TRY(launch_rope(qkv, qkv_stride, pos[cur], Tl, m.n_q_heads + m.n_kv_heads, m.head_dim, m.rope_base, m.dtype, s));
+    const char* kptr = qkv + (size_t)qd * es;
+    const char* vptr = qkv + (size_t)(qd + kd) * es;
+    FASTAV_TRY(launch_attention(qkv, qkv_stride, kptr, vptr, qkv_stride, attn[0], qd, cu_l, B, Tl, maxlen_stage[stage],
+                                m.n_q_heads, m.n_kv_heads, m.head_dim, side ? logits : nullptr, side ? ml : nullptr,
+                                m.dtype, s));
+    void* attn_cur = attn[0];
+    void* const k_out = out->kv_out ? out->kv_out[2 * l] : nullptr;
+    void* const v_out = out->kv_out ? out->kv_out[2 * l + 1] : nullptr;
+    if (fine) {
+      // ---- FINE prune: Eq. 4 scores of the last query row(s), top-k, compaction of everything later work reads
+      float* sc = (out->prune_scores_out && out->prune_scores_out[pi]) ? out->prune_scores_out[pi] : scores_ws;
+      if (side) {
+        FASTAV_TRY(launch_score_finalize(logits, ml, nullptr, cu_l, B, Tl, maxlen_stage[stage], m.n_q_heads, 1, sc, s));
+      } else {
+        FASTAV_TRY(launch_score_logits(qkv, qkv_stride, kptr, qkv_stride, cu_l, B, Tl, maxlen_stage[stage], m.n_q_heads,
+                                       m.n_kv_heads, m.head_dim, n_last, logits, partials, m.dtype, s));
+        FASTAV_TRY(launch_score_finalize(logits, nullptr, partials, cu_l, B, Tl, maxlen_stage[stage], m.n_q_heads, n_last, sc, s));
+      }
+      const int32_t* cu_nx = cu_dev + (size_t)(stage + 1) * (B + 1);
+      int32_t* kidx = (out->prune_keep_idx_out && out->prune_keep_idx_out[pi]) ? out->prune_keep_idx_out[pi] : keep_idx_ws;
+      FASTAV_TRY(launch_select(sc, prot[cur], cu_l, cu_nx, B, maxlen_stage[stage], kidx, s));
+      GatherTensor g[6] = {{resid[cur], resid[cur ^ 1], (int64_t)m.hidden * 4, 0},
+                           {attn[0], attn[1], (int64_t)qd * (int64_t)es, 0},
+                           {pos[cur], pos[cur ^ 1], 4, 0},
+                           {prot[cur], prot[cur ^ 1], 1, 0},
+                           {kptr, k_out, k_out ? (int64_t)kd * (int64_t)es : 0, qkv_stride * (int64_t)es},
+                           {vptr, v_out, v_out ? (int64_t)kd * (int64_t)es : 0, qkv_stride * (int64_t)es}};
+      FASTAV_TRY(launch_gather(g, 6, kidx, T_stage[stage + 1], s));
+      cur ^= 1; ++stage; ++pi;
+      attn_cur = attn[1];
+    } else {
+      if (k_out) FASTAV_TRY(launch_copy_rows(kptr, qkv_stride * (int64_t)es, k_out, (int64_t)kd * (int64_t)es, Tl, nullptr, s));
+      if (v_out) FASTAV_TRY(launch_copy_rows(vptr, qkv_stride * (int64_t)es, v_out, (int64_t)kd * (int64_t)es, Tl, nullptr, s));
+    }
+    const int64_t To = T_stage[stage];
+    FASTAV_TRY(launch_linear(attn_cur, W.wo, nullptr, resid[cur], To, m.hidden, qd, FASTAV_EPI_RESADD, m.dtype, s));
+    FASTAV_TRY(launch_rmsnorm(resid[cur], W.g_mlp, hn, To, m.hidden, m.rms_eps, m.dtype, s));
+    FASTAV_TRY(launch_linear(hn, W.w_gate, W.w_up, hmlp, To, m.mlp_dim, m.hidden, FASTAV_EPI_SWIGLU, m.dtype, s));
+    FASTAV_TRY(launch_linear(hmlp, W.w_down, nullptr, resid[cur], To, m.hidden, m.mlp_dim, FASTAV_EPI_RESADD, m.dtype, s));
+    if (out->layer_x_out && out->layer_x_out[l])
+      FASTAV_TRY(launch_copy_rows(resid[cur], (int64_t)m.hidden * 4, out->layer_x_out[l], (int64_t)m.hidden * 4, To, nullptr, s));
+  }
+  const int64_t Tf = T_stage[stage];
+  FASTAV_TRY(launch_copy_rows(resid[cur], (int64_t)m.hidden * 4, out->x_out, (int64_t)m.hidden * 4, Tf, nullptr, s));
+  FASTAV_TRY(launch_copy_rows(pos[cur], 4, out->kept_pos_out, 4, Tf, nullptr, s));
+  FASTAV_TRY(launch_copy_rows(cu_dev + (size_t)stage * (B + 1), 4, out->cu_seqlens_out, 4, B + 1, nullptr, s));
+  return FASTAV_OK;
+}
+
+size_t fastav_score_workspace_bytes(int32_t n_q_heads, int64_t total_tokens, int32_t batch, int32_t n_last) {
+  if (n_q_heads < 1 || total_tokens < 0 || batch < 1 || n_last < 1) return 0;
+  return align_up((size_t)n_last * n_q_heads * total_tokens * 4, 256) +
+         align_up(score_partials_bytes(n_q_heads, total_tokens, batch, n_last), 256);
+}
+
+fastav_status_t fastav_score(const fastav_model_t* model, const void* q, int64_t q_row_stride, const void* k,
+                             int64_t k_row_stride, const int32_t* cu_seqlens_dev, int32_t batch, int64_t total_tokens,
+                             int32_t max_seqlen, int32_t n_last, float* scores_out, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  FASTAV_TRY(check_model(model));
+  if (!q || !k || !cu_seqlens_dev || !scores_out || !workspace) return fail(FASTAV_EINVAL, "a pointer argument is NULL");
+  if (batch < 1 || total_tokens < 0 || max_seqlen < 0 || max_seqlen > total_tokens) return fail(FASTAV_EINVAL, "bad batch/total_tokens/max_seqlen");
+  if (n_last < 1 || n_last > FASTAV_MAX_N_LAST) return fail(FASTAV_EINVAL, "n_last must be in [1, %d]", FASTAV_MAX_N_LAST);
+  const int64_t qd = (int64_t)model->n_q_heads * model->head_dim, kd = (int64_t)model->n_kv_heads * model->head_dim;
+  if (q_row_stride < qd || k_row_stride < kd) return fail(FASTAV_EINVAL, "row strides are smaller than a row");
+  const size_t es = model->dtype == FASTAV_BF16 ? 2 : 4;
+  if (((uintptr_t)q % 16) || ((uintptr_t)k % 16) || (q_row_stride * es) % 16 || (k_row_stride * es) % 16 || ((uintptr_t)workspace % 256))
+    return fail(FASTAV_EINVAL, "q, k and their row strides must be 16-byte aligned, workspace 256-byte aligned");
+  const size_t need = fastav_score_workspace_bytes(model->n_q_heads, total_tokens, batch, n_last);
+  if (workspace_bytes < need) return fail(FASTAV_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  float* logits = (float*)workspace;
+  float* partials = (float*)((char*)workspace + align_up((size_t)n_last * model->n_q_heads * total_tokens * 4, 256));
+  hipStream_t s = (hipStream_t)stream;
+  FASTAV_TRY(launch_score_logits(q, q_row_stride, k, k_row_stride, cu_seqlens_dev, batch, total_tokens, max_seqlen,
+                                 model->n_q_heads, model->n_kv_heads, model->head_dim, n_last, logits, partials,
+                                 model->dtype, s));
+  return launch_score_finalize(logits, nullptr, partials, cu_seqlens_dev, batch, total_tokens, max_seqlen,
+                               model->n_q_heads, n_last, scores_out, s);
+}
+
+size_t fastav_select_workspace_bytes(int32_t batch) {
+  if (batch < 1) return 0;
+  return align_up((size_t)(batch + 1) * 4, 256);
+}
+
+fastav_status_t fastav_select_gather(const float* scores, const uint8_t* protected_mask, const int32_t* cu_seqlens,
+                                     const int32_t* keep_counts, int32_t batch, int32_t n_tensors,
+                                     const void* const* src, void* const* dst, const int64_t* row_bytes,
+                                     int32_t* keep_idx_out, int32_t* cu_seqlens_out, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
+  if (!protected_mask || !cu_seqlens || !keep_counts || !keep_idx_out || !cu_seqlens_out || !workspace)
+    return fail(FASTAV_EINVAL, "a pointer argument is NULL");
+  if (batch < 1) return fail(FASTAV_EINVAL, "batch must be >= 1");
+  if (n_tensors < 0 || n_tensors > FASTAV_MAX_GATHER_TENSORS) return fail(FASTAV_EINVAL, "n_tensors must be in [0, %d]", FASTAV_MAX_GATHER_TENSORS);
+  if (n_tensors > 0 && (!src || !dst || !row_bytes)) return fail(FASTAV_EINVAL, "src/dst/row_bytes is NULL");
+  if (workspace_bytes < fastav_select_workspace_bytes(batch) || ((uintptr_t)workspace % 4))
+    return fail(FASTAV_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, fastav_select_workspace_bytes(batch));
+  if (cu_seqlens[0] != 0) return fail(FASTAV_EINVAL, "cu_seqlens[0] must be 0");
+  std::vector<int32_t> cu_out(batch + 1);
+  cu_out[0] = 0;
+  int max_len = 0;
+  for (int b = 0; b < batch; ++b) {
+    const int64_t n = (int64_t)cu_seqlens[b + 1] - cu_seqlens[b];
+    if (n < 0) return fail(FASTAV_EINVAL, "cu_seqlens must be non-decreasing");
+    if (keep_counts[b] < 0 || keep_counts[b] > n) return fail(FASTAV_EINVAL, "keep_counts[%d] = %d exceeds the sample's %lld rows", b, keep_counts[b], (long long)n);
+    cu_out[b + 1] = cu_out[b] + keep_counts[b];
+    if (n > max_len) max_len = (int)n;
+  }
+  GatherTensor g[FASTAV_MAX_GATHER_TENSORS];
+  for (int i = 0; i < n_tensors; ++i) {
+    if (row_bytes[i] < 0) return fail(FASTAV_EINVAL, "row_bytes[%d] is negative", i);
+    if (row_bytes[i] > 0 && (!src[i] || !dst[i])) return fail(FASTAV_EINVAL, "src[%d] or dst[%d] is NULL", i, i);
+    g[i] = GatherTensor{src[i], dst[i], row_bytes[i], 0};
+  }
+  hipStream_t s = (hipStream_t)stream;
+  int32_t* cu_dev = (int32_t*)workspace;
+  FASTAV_TRY(upload_small(cu_dev, cu_seqlens, (size_t)(batch + 1) * 4, s));
+  FASTAV_TRY(upload_small(cu_seqlens_out, cu_out.data(), (size_t)(batch + 1) * 4, s));
+  FASTAV_TRY(launch_select(scores, protected_mask, cu_dev, cu_seqlens_out, batch, max_len, keep_idx_out, s));
+  return launch_gather(g, n_tensors, keep_idx_out, cu_out[batch], s);
+}
+
+fastav_status_t fastav_rmsnorm(const float* x, const void* g, void* y, int64_t rows, int32_t d, float eps,
+                               int32_t dtype, void* stream) {
+  if (!x || !g || !y) return fail(FASTAV_EINVAL, "a pointer argument is NULL");
+  if (rows < 0 || d < 1 || (dtype != FASTAV_BF16 && dtype != FASTAV_F32)) return fail(FASTAV_EINVAL, "bad rows/d/dtype");
+  if ((d % 4 == 0) && ((uintptr_t)x % 16)) return fail(FASTAV_EINVAL, "x must be 16-byte aligned");
+  return launch_rmsnorm(x, g, y, rows, d, eps, dtype, (hipStream_t)stream);
+}
+
+fastav_status_t fastav_rope(void* x, int64_t row_stride, const int32_t* pos, int64_t rows, int32_t n_heads,
+                            int32_t head_dim, float base, int32_t dtype, void* stream) {
+  if (!x || !pos) return fail(FASTAV_EINVAL, "a pointer argument is NULL");
+  if (rows < 0 || n_heads < 0 || head_dim < 2 || (head_dim & 1) || head_dim > 512 || row_stride < (int64_t)n_heads * head_dim ||
+      (dtype != FASTAV_BF16 && dtype != FASTAV_F32) || !(base > 1.0f))
+    return fail(FASTAV_EINVAL, "bad rows/n_heads/head_dim/row_stride/dtype/base");
+  return launch_rope(x, row_stride, pos, rows, n_heads, head_dim, base, dtype, (hipStream_t)stream);
+}
+
+fastav_status_t fastav_linear(const void* a, const void* w, const void* w2, void* c, int64_t m, int32_t n, int32_t k,
+                              int32_t epilogue, int32_t dtype, void* stream) {
+  if (!a || !w || !c) return fail(FASTAV_EINVAL, "a pointer argument is NULL");
+  if (m < 0 || n < 1 || k < 1 || (dtype != FASTAV_BF16 && dtype != FASTAV_F32)) return fail(FASTAV_EINVAL, "bad m/n/k/dtype");
+  if (epilogue < FASTAV_EPI_STORE || epilogue > FASTAV_EPI_SWIGLU) return fail(FASTAV_EINVAL, "bad epilogue");
+  if (epilogue == FASTAV_EPI_SWIGLU && !w2) return fail(FASTAV_EINVAL, "w2 is NULL for the SwiGLU epilogue");
+  return launch_linear(a, w, w2, c, m, n, k, epilogue, dtype, (hipStream_t)stream);
+}
+
+fastav_status_t fastav_attention(const fastav_model_t* model, const void* q, int64_t q_row_stride, const void* k,
+                                 const void* v, int64_t kv_row_stride, void* o, int64_t o_row_stride,
+                                 const int32_t* cu_seqlens_dev, int32_t batch, int64_t total_tokens,
+                                 int32_t max_seqlen, float* last_logits, float* last_ml, void* stream) {
+  FASTAV_TRY(check_model(model));
+  if (!q || !k || !v || !o || !cu_seqlens_dev) return fail(FASTAV_EINVAL, "a pointer argument is NULL");
+  if ((last_logits == nullptr) != (last_ml == nullptr)) return fail(FASTAV_EINVAL, "last_logits and last_ml go together");
+  if (batch < 1 || total_tokens < 0 || max_seqlen < 0 || max_seqlen > total_tokens) return fail(FASTAV_EINVAL, "bad batch/total_tokens/max_seqlen");
+  const int64_t qd = (int64_t)model->n_q_heads * model->head_dim, kd = (int64_t)model->n_kv_heads * model->head_dim;
+  if (q_row_stride < qd || o_row_stride < qd || kv_row_stride < kd) return fail(FASTAV_EINVAL, "row strides are smaller than a row");
+  return launch_attention(q, q_row_stride, k, v, kv_row_stride, o, o_row_stride, cu_seqlens_dev, batch, total_tokens,
+                          max_seqlen, model->n_q_heads, model->n_kv_heads, model->head_dim, last_logits, last_ml,
+                          model->dtype, (hipStream_t)stream);
+}
+
+}  // extern "C"

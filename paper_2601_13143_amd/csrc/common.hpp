@@ -1,0 +1,87 @@
+// Shared declarations of the FastAV HIP library (gfx950 only): types, launch helpers and the internal
+// kernel-launch functions the C ABI in api.hip strings together.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/fastav.h"
+
+namespace fastav {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }  // RNE (v_cvt_pk_bf16_f32)
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
+
+// Records the message returned by fastav_last_error() and passes the status through.
+fastav_status_t fail(fastav_status_t st, const char* fmt, ...);
+fastav_status_t check_launch(const char* what);
+
+// ---- launchers (every pointer is a device pointer unless named host_*) ------------------------------
+
+// Copies a small host array into device memory through kernel arguments (no memcpy, no pinned memory,
+// stream-ordered, legal under graph capture).
+fastav_status_t upload_small(void* dst_dev, const void* host_src, size_t bytes, hipStream_t s);
+
+fastav_status_t launch_init_tokens(const int32_t* cu, const int32_t* span_offsets, const fastav_span_t* spans,
+                                   int batch, int64_t T, int max_seqlen, int n_last, int32_t* pos, uint8_t* prot,
+                                   hipStream_t s);
+fastav_status_t launch_to_f32(const void* x, float* y, int64_t n, int dtype, hipStream_t s);
+fastav_status_t launch_copy_rows(const void* src, int64_t src_row_bytes_stride, void* dst, int64_t row_bytes,
+                                 int64_t rows, const int32_t* idx, hipStream_t s);
+fastav_status_t launch_rmsnorm(const float* x, const void* g, void* y, int64_t rows, int d, float eps, int dtype,
+                               hipStream_t s);
+fastav_status_t launch_rope(void* x, int64_t row_stride, const int32_t* pos, int64_t rows, int n_heads, int head_dim,
+                            float base, int dtype, hipStream_t s);
+fastav_status_t launch_linear(const void* a, const void* w, const void* w2, void* c, int64_t m, int n, int k,
+                              int epilogue, int dtype, hipStream_t s);
+fastav_status_t launch_attention(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
+                                 void* o, int64_t o_stride, const int32_t* cu, int batch, int64_t T, int max_seqlen,
+                                 int Hq, int Hkv, int dh, float* last_logits, float* last_ml, int dtype,
+                                 hipStream_t s);
+
+// Eq. 4.  logits [n_last, Hq, T] fp32, ml [batch, n_last, Hq, 2] fp32.
+size_t score_partials_bytes(int Hq, int64_t T, int batch, int n_last);
+fastav_status_t launch_score_logits(const void* q, int64_t q_stride, const void* k, int64_t k_stride,
+                                    const int32_t* cu, int batch, int64_t T, int max_seqlen, int Hq, int Hkv, int dh,
+                                    int n_last, float* logits, float* partials, int dtype, hipStream_t s);
+// exactly one of ml (per-head (max, sum-exp), e.g. the attention side output) and partials is non-null
+fastav_status_t launch_score_finalize(const float* logits, const float* ml, const float* partials, const int32_t* cu,
+                                      int batch, int64_t T, int max_seqlen, int Hq, int n_last, float* scores,
+                                      hipStream_t s);
+
+// Selection + compaction.  keep_idx/cu_out as in fastav_select_gather; scores == nullptr -> positional.
+fastav_status_t launch_select(const float* scores, const uint8_t* prot, const int32_t* cu, const int32_t* cu_out,
+                              int batch, int max_seqlen, int32_t* keep_idx, hipStream_t s);
+// src_stride_bytes == 0 means rows are packed (stride = row_bytes); row_bytes == 0 skips the tensor.
+struct GatherTensor { const void* src; void* dst; int64_t row_bytes; int64_t src_stride_bytes; };
+fastav_status_t launch_gather(const GatherTensor* t, int n_tensors, const int32_t* keep_idx, int64_t n_rows,
+                              hipStream_t s);
+
+}  // namespace fastav

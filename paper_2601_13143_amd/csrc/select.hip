@@ -1,0 +1,288 @@
+// Top-k selection and compaction for the prune step ("tokens with the lowest P% scores are removed",
+// Section 2.2 of the paper; global pruning keeps the earliest positions instead).
+//
+//   k_select  one 1024-thread workgroup per sample.  The sample's order-preserving 32-bit keys live in LDS;
+//             four 8-bit MSB-first radix passes (per-wave LDS histograms, so that the narrow exponent range
+//             of softmax scores does not serialise on one counter) find the k-th largest key; ties at
+//             the threshold go to the lowest indices; two workgroup scans turn the keep flags into the
+//             ascending list of kept rows.  Integer work only, so the result is exact.
+//   k_gather  dst[r] = src[keep_idx[r]] for several tensors in one launch, 16 bytes per lane.
+#include "common.hpp"
+
+namespace fastav {
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kSelLdsKeys = 32768;          // samples up to this length keep their keys in LDS (128 KB)
+
+// fp32 -> unsigned key, larger key = better.  NaN ranks as -inf; -0.0 equals +0.0.
+__device__ __forceinline__ uint32_t score_key(float s) {
+  if (s != s) s = -INFINITY;
+  if (s == 0.0f) s = 0.0f;
+  const uint32_t u = __float_as_uint(s);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ int block_exclusive_scan(int v, int* wave_tot, int& total) {
+  // inclusive scan inside the wave
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(inc, o, kWave);
+    if (lane >= o) inc += t;
+  }
+  __syncthreads();                          // wave_tot may still be read from a previous scan
+  if (lane == 63) wave_tot[wave] = inc;
+  __syncthreads();
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    const int t = wave_tot[w];
+    if (w < wave) base += t;
+    tot += t;
+  }
+  total = tot;
+  return base + inc - v;
+}
+
+// Key of candidate j (unprotected row): by score, or by position (earlier = larger) when scores == nullptr.
+__device__ __forceinline__ uint32_t cand_key(const float* scores, int row0, int n, int j) {
+  return scores ? score_key(scores[row0 + j]) : (uint32_t)(n - j);   // n - j >= 1
+}
+
+template <bool KEYS_IN_LDS>
+__global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict__ scores,
+                                                        const uint8_t* __restrict__ prot,
+                                                        const int32_t* __restrict__ cu,
+                                                        const int32_t* __restrict__ cu_out,
+                                                        int32_t* __restrict__ keep_idx) {
+  extern __shared__ uint32_t keys[];                      // [n] when KEYS_IN_LDS; key 0 = protected (never a candidate)
+  __shared__ int hist[kSelWaves][256];
+  __shared__ int wave_tot[kSelWaves];
+  __shared__ uint32_t sh_prefix;
+  __shared__ int sh_need;
+
+  const int b = blockIdx.x;
+  const int row0 = cu[b], n = cu[b + 1] - row0;
+  const int out0 = cu_out[b], k_keep = cu_out[b + 1] - out0;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (n <= 0) return;
+
+  // ---- load keys, count protected rows
+  int my_prot = 0;
+  for (int j = tid; j < n; j += kSelThreads) {
+    const bool p = prot[row0 + j] != 0;
+    my_prot += p ? 1 : 0;
+    if (KEYS_IN_LDS) keys[j] = p ? 0u : cand_key(scores, row0, n, j);
+  }
+  int n_prot;
+  block_exclusive_scan(my_prot, wave_tot, n_prot);
+  int need = k_keep - n_prot;                             // candidates to keep
+  if (need < 0) need = 0;
+  const int n_cand = n - n_prot;
+  if (need > n_cand) need = n_cand;
+
+  // ---- radix select: largest `need` candidate keys.  After the passes: threshold key `prefix`,
+  //      `need_eq` = how many candidates equal to the threshold are kept (lowest indices first).
+  uint32_t prefix = 0, mask = 0;
+  int need_eq = need;
+  if (need > 0 && need < n_cand) {
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      for (int i = tid; i < kSelWaves * 256; i += kSelThreads) (&hist[0][0])[i] = 0;
+      __syncthreads();
+      for (int j = tid; j < n; j += kSelThreads) {
+        uint32_t key;
+        if (KEYS_IN_LDS) key = keys[j];
+        else key = prot[row0 + j] ? 0u : cand_key(scores, row0, n, j);
+        if (key != 0u && (key & mask) == prefix) atomicAdd(&hist[wave][(key >> shift) & 255u], 1);
+      }
+      __syncthreads();
+      if (wave == 0) {
+        // lane owns digits 4*lane .. 4*lane+3; walk from the top digit down until `need_eq` is covered
+        int c[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          int t = 0;
+          for (int w = 0; w < kSelWaves; ++w) t += hist[w][4 * lane + d];
+          c[d] = t;
+        }
+        const int mine = c[0] + c[1] + c[2] + c[3];
+        // suffix sum over lanes: above = total count of digits owned by higher lanes
+        int suf = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const int t = __shfl_down(suf, o, kWave);
+          if (lane + o < 64) suf += t;
+        }
+        int above = suf - mine;
+        // the lane whose range crosses need_eq finds the digit
+        if (above < need_eq && need_eq <= suf) {
+          int d = 3;
+          for (; d >= 0; --d) {
+            if (above + c[d] >= need_eq) break;
+            above += c[d];
+          }
+          sh_prefix = prefix | ((uint32_t)(4 * lane + d) << shift);
+          sh_need = need_eq - above;                     // still to take among keys with this digit
+        }
+      }
+      __syncthreads();
+      prefix = sh_prefix;
+      need_eq = sh_need;
+      mask |= 255u << shift;
+      __syncthreads();
+    }
+  } else if (need == 0) {
+    prefix = 0xFFFFFFFFu; mask = 0xFFFFFFFFu; need_eq = 0;   // no candidate passes (keys never reach 0xFFFFFFFF+)
+  } else {
+    prefix = 0; mask = 0xFFFFFFFFu; need_eq = 0;             // need == n_cand: every candidate key (> 0) passes
+  }
+  // keep candidate j  <=>  key > prefix, or key == prefix and it is among the first need_eq such rows.
+  const bool take_all = (need == n_cand), take_none = (need == 0);
+
+  // ---- flags and ordered output.  Thread t owns the contiguous rows [t*per, (t+1)*per).
+  const int per = (n + kSelThreads - 1) / kSelThreads;
+  const int j_lo = tid * per, j_hi = (j_lo + per < n) ? j_lo + per : n;
+  int eq_cnt = 0;
+  for (int j = j_lo; j < j_hi; ++j) {
+    uint32_t key;
+    if (KEYS_IN_LDS) key = keys[j];
+    else key = prot[row0 + j] ? 0u : cand_key(scores, row0, n, j);
+    eq_cnt += (key != 0u && key == prefix) ? 1 : 0;
+  }
+  int dummy;
+  int eq_before = block_exclusive_scan(eq_cnt, wave_tot, dummy);
+  int keep_cnt = 0;
+  {
+    int e = eq_before;
+    for (int j = j_lo; j < j_hi; ++j) {
+      uint32_t key;
+      if (KEYS_IN_LDS) key = keys[j];
+      else key = prot[row0 + j] ? 0u : cand_key(scores, row0, n, j);
+      bool kp;
+      if (key == 0u) kp = true;                            // protected
+      else if (take_all) kp = true;
+      else if (take_none) kp = false;
+      else if (key > prefix) kp = true;
+      else if (key == prefix) { kp = e < need_eq; ++e; }
+      else kp = false;
+      keep_cnt += kp ? 1 : 0;
+    }
+  }
+  int keep_before = block_exclusive_scan(keep_cnt, wave_tot, dummy);
+  {
+    int e = eq_before, o = keep_before;
+    for (int j = j_lo; j < j_hi; ++j) {
+      uint32_t key;
+      if (KEYS_IN_LDS) key = keys[j];
+      else key = prot[row0 + j] ? 0u : cand_key(scores, row0, n, j);
+      bool kp;
+      if (key == 0u) kp = true;
+      else if (take_all) kp = true;
+      else if (take_none) kp = false;
+      else if (key > prefix) kp = true;
+      else if (key == prefix) { kp = e < need_eq; ++e; }
+      else kp = false;
+      if (kp) {
+        if (o < k_keep) keep_idx[out0 + o] = row0 + j;     // o < k_keep always unless k_keep < #protected
+        ++o;
+      }
+    }
+  }
+}
+
+fastav_status_t launch_select(const float* scores, const uint8_t* prot, const int32_t* cu, const int32_t* cu_out,
+                              int batch, int max_seqlen, int32_t* keep_idx, hipStream_t s) {
+  if (batch == 0 || max_seqlen == 0) return FASTAV_OK;
+  if (max_seqlen <= kSelLdsKeys) {
+    const size_t shmem = (size_t)max_seqlen * sizeof(uint32_t);
+    if (shmem > 32 * 1024) {   // beyond the default dynamic-LDS limit: opt in (per device, so set on every such launch)
+      hipError_t e = hipFuncSetAttribute((const void*)k_select<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         kSelLdsKeys * (int)sizeof(uint32_t));
+      if (e != hipSuccess) return fail(FASTAV_EHIP, "select: hipFuncSetAttribute: %s", hipGetErrorString(e));
+    }
+    hipLaunchKernelGGL(k_select<true>, dim3((unsigned)batch), dim3(kSelThreads), shmem, s, scores, prot, cu, cu_out, keep_idx);
+  } else {
+    hipLaunchKernelGGL(k_select<false>, dim3((unsigned)batch), dim3(kSelThreads), 0, s, scores, prot, cu, cu_out, keep_idx);
+  }
+  return check_launch("select");
+}
+
+// ---------------------------------------------------------------------------------------- gather
+struct GatherArgs {
+  const char* src[FASTAV_MAX_GATHER_TENSORS];
+  char* dst[FASTAV_MAX_GATHER_TENSORS];
+  int64_t row_bytes[FASTAV_MAX_GATHER_TENSORS];
+  int64_t src_stride[FASTAV_MAX_GATHER_TENSORS];
+};
+
+// grid (row groups, tensor).  Rows whose size and addresses are multiples of 16 bytes move as uint4 with
+// the workgroup's lanes laid along the row; anything else moves bytewise.  idx == nullptr copies rows in
+// place order (a strided copy).
+__global__ __launch_bounds__(256) void k_gather(GatherArgs a, const int32_t* __restrict__ idx, int64_t n_rows,
+                                                int rows_per_block) {
+  const int t = blockIdx.y;
+  const int64_t rb = a.row_bytes[t];
+  const int64_t ss = a.src_stride[t];
+  const char* src = a.src[t];
+  char* dst = a.dst[t];
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+  const bool vec = ((rb | ss) % 16 == 0) && (((uintptr_t)src | (uintptr_t)dst) % 16 == 0);
+  if (vec) {
+    const int64_t v_per_row = rb / 16;
+    const int64_t total = v_per_row * rows_per_block;
+    for (int64_t i = threadIdx.x; i < total; i += 256) {
+      const int64_t r = r0 + i / v_per_row, c = i % v_per_row;
+      if (r >= n_rows) break;
+      const int64_t sr = idx ? (int64_t)idx[r] : r;
+      ((uint4*)(dst + r * rb))[c] = ((const uint4*)(src + sr * ss))[c];
+    }
+  } else {
+    const int64_t total = rb * rows_per_block;
+    for (int64_t i = threadIdx.x; i < total; i += 256) {
+      const int64_t r = r0 + i / rb, c = i % rb;
+      if (r >= n_rows) break;
+      const int64_t sr = idx ? (int64_t)idx[r] : r;
+      dst[r * rb + c] = src[sr * ss + c];
+    }
+  }
+}
+
+static fastav_status_t gather_impl(const GatherArgs& a, int n_tensors, const int32_t* keep_idx, int64_t n_rows,
+                                   hipStream_t s) {
+  if (n_rows == 0 || n_tensors == 0) return FASTAV_OK;
+  // aim at >= 4 KB of payload per workgroup, judged by the widest tensor
+  int64_t widest = 1;
+  for (int i = 0; i < n_tensors; ++i) widest = a.row_bytes[i] > widest ? a.row_bytes[i] : widest;
+  int rows_per_block = (int)(4096 / widest);
+  if (rows_per_block < 1) rows_per_block = 1;
+  if (rows_per_block > 64) rows_per_block = 64;
+  dim3 grid((unsigned)ceil_div(n_rows, rows_per_block), (unsigned)n_tensors);
+  hipLaunchKernelGGL(k_gather, grid, dim3(256), 0, s, a, keep_idx, n_rows, rows_per_block);
+  return check_launch("gather");
+}
+
+fastav_status_t launch_gather(const GatherTensor* t, int n_tensors, const int32_t* keep_idx, int64_t n_rows,
+                              hipStream_t s) {
+  if (n_tensors > FASTAV_MAX_GATHER_TENSORS) return fail(FASTAV_EINVAL, "gather: too many tensors");
+  GatherArgs a;
+  int m = 0;
+  for (int i = 0; i < n_tensors; ++i) {
+    if (t[i].row_bytes == 0) continue;
+    a.src[m] = (const char*)t[i].src; a.dst[m] = (char*)t[i].dst;
+    a.row_bytes[m] = t[i].row_bytes; a.src_stride[m] = t[i].src_stride_bytes ? t[i].src_stride_bytes : t[i].row_bytes; ++m;
+  }
+  for (int i = m; i < FASTAV_MAX_GATHER_TENSORS; ++i) { a.src[i] = nullptr; a.dst[i] = nullptr; a.row_bytes[i] = 0; a.src_stride[i] = 0; }
+  return gather_impl(a, m, keep_idx, n_rows, s);
+}
+
+fastav_status_t launch_copy_rows(const void* src, int64_t src_row_bytes_stride, void* dst, int64_t row_bytes,
+                                 int64_t rows, const int32_t* idx, hipStream_t s) {
+  GatherArgs a;
+  for (int i = 0; i < FASTAV_MAX_GATHER_TENSORS; ++i) { a.src[i] = nullptr; a.dst[i] = nullptr; a.row_bytes[i] = 0; a.src_stride[i] = 0; }
+  a.src[0] = (const char*)src; a.dst[0] = (char*)dst; a.row_bytes[0] = row_bytes; a.src_stride[0] = src_row_bytes_stride;
+  return gather_impl(a, 1, idx, rows, s);
+}
+
+}  // namespace fastav

@@ -1,0 +1,375 @@
+"""GPU parity: every stage of the HIP path against the CPU oracle, element by element, through the C ABI.
+
+Integer / index work (selection, compaction) must match bit for bit; floating-point stages stay within the
+tolerances in gpu_util (bf16: max-abs 2e-2, relative L2 1e-2 on O(1)-scale outputs).  End-to-end kept sets
+may differ only on tokens whose oracle score lies within 1e-3 of the k-th score."""
+import numpy as np
+import pytest
+import torch
+
+import fastav_inputs as fi
+from oracle import fastav_oracle as orc
+import paper_2601_13143_amd as fa
+from gpu_util import (TIE_BAND, assert_close, dev, host, make_decoder, model_struct, prune_tuples, rel_l2)
+
+pytestmark = pytest.mark.gpu
+
+
+def _cu(lens):
+    return np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+
+
+# ------------------------------------------------------------------------------------ select + gather
+def _select_case(lens, score_kind, seed, prot_frac=0.1, ratio=0.6, positional=False):
+    rng = np.random.default_rng(seed)
+    cu = _cu(lens)
+    T = int(cu[-1])
+    kind = score_kind or "softmax"
+    scores = np.concatenate([fi.random_scores(n, seed + i, kind) if n else np.zeros(0, np.float32) for i, n in enumerate(lens)])
+    prot = (rng.random(T) < prot_frac)
+    for b in range(len(lens)):
+        if lens[b] > 0:
+            prot[cu[b + 1] - 1] = True
+    kc, want = [], []
+    for b, n in enumerate(lens):
+        p = prot[cu[b]:cu[b + 1]]
+        k = orc.keep_count(n, ratio, int(p.sum())) if n else 0
+        kc.append(k)
+        keep = orc.global_keep(p, k) if positional else orc.select_keep(scores[cu[b]:cu[b + 1]], p, k)
+        want.append(keep + cu[b])
+    want = np.concatenate(want) if want else np.zeros(0, np.int64)
+    x = rng.standard_normal((T, 24)).astype(np.float32)           # 96-byte rows (16-byte path)
+    ids = np.arange(T, dtype=np.int32)                            # 4-byte rows
+    by = rng.integers(0, 255, (T, 3)).astype(np.uint8)            # 3-byte rows (bytewise path)
+    s_dev = None if positional else torch.from_numpy(scores).cuda()
+    keep_idx, cu_out, (gx, gi, gb) = fa.fastav_select_gather(
+        s_dev, torch.from_numpy(prot.astype(np.uint8)).cuda(), cu, kc,
+        [torch.from_numpy(x).cuda(), torch.from_numpy(ids).cuda(), torch.from_numpy(by).cuda()])
+    torch.cuda.synchronize()
+    got = keep_idx.cpu().numpy()
+    assert np.array_equal(got, want), f"kept indices differ: {np.sum(got != want)} of {len(want)}"
+    assert np.array_equal(cu_out.cpu().numpy(), _cu(kc))
+    assert np.array_equal(gx.cpu().numpy(), x[want]) and np.array_equal(gi.cpu().numpy(), ids[want])
+    assert np.array_equal(gb.cpu().numpy(), by[want])
+
+
+@pytest.mark.parametrize("kind", ["softmax", "ties", "equal", "mixed"])
+def test_select_gather_single_samples(kind):
+    for n in (1, 2, 63, 64, 65, 1000, 1025, 4096, 5000):
+        _select_case([n], kind, 11 + n)
+
+
+def test_select_gather_ragged_batch_and_edges():
+    _select_case([2048, 6144, 3000, 1, 77, 4095, 2049, 5120], "softmax", 5)
+    _select_case([300, 1, 1, 900], "ties", 6, prot_frac=0.5, ratio=0.3)
+    _select_case([500, 700], "softmax", 7, ratio=1.0)              # keep everything
+    _select_case([500, 700], "softmax", 8, prot_frac=0.0, ratio=0.001)   # keep only the forced last row
+    _select_case([500, 700], "equal", 9, prot_frac=1.0, ratio=0.5)  # everything protected
+    _select_case([128, 0, 64], "softmax", 10)                      # an empty sample in the batch
+
+
+def test_select_gather_long_samples():
+    _select_case([16384], "softmax", 21, ratio=0.7)
+    _select_case([32768, 33000], "ties", 22, ratio=0.5)            # second sample exceeds the LDS-resident limit
+    _select_case([70001], "softmax", 23, ratio=0.35)
+
+
+def test_select_positional_is_the_global_rule():
+    _select_case([4096, 1000, 37], None, 31, prot_frac=0.05, ratio=0.6, positional=True)
+    _select_case([16384], None, 32, prot_frac=0.05, ratio=0.5, positional=True)
+
+
+# ------------------------------------------------------------------------------------ Eq. 4 scores
+@pytest.mark.parametrize("dtype,Hq,Hkv,dh", [("bf16", 32, 8, 128), ("bf16", 28, 4, 128), ("bf16", 6, 3, 64), ("bf16", 8, 8, 128),
+                                            ("f32", 4, 2, 64), ("f32", 8, 2, 128), ("bf16", 16, 2, 64)])
+@pytest.mark.parametrize("n_last", [1, 3])
+def test_score_matches_oracle(dtype, Hq, Hkv, dh, n_last):
+    lens = [300, 129, 2, 1, 517]
+    rng = np.random.default_rng(Hq * 100 + dh + n_last)
+    T = sum(lens)
+    q = rng.standard_normal((T, Hq, dh)).astype(np.float32) * 1.3
+    k = rng.standard_normal((T, Hkv, dh)).astype(np.float32) * 1.3
+    if dtype == "bf16":
+        fi.round_bf16(q); fi.round_bf16(k)
+    m = fa.make_model(1, 64, Hq, Hkv, dh, 64, dtype=fa.BF16 if dtype == "bf16" else fa.F32)
+    cu = _cu(lens)
+    got = host(fa.fastav_score(m, dev(q, dtype), dev(k, dtype), torch.from_numpy(cu).cuda(), max(lens), n_last))
+    for b, n in enumerate(lens):
+        want = orc.last_query_scores(q[cu[b]:cu[b + 1]].astype(np.float64), k[cu[b]:cu[b + 1]].astype(np.float64), n_last)
+        g = got[cu[b]:cu[b + 1]]
+        assert abs(g.sum() - 1.0) < 1e-4
+        # scores are O(1/n): compare after scaling by n; inputs are identical so fp32 accumulation is the only error
+        assert np.max(np.abs(g - want)) * n <= 1e-3 and rel_l2(g, want) <= 1e-4, (b, np.max(np.abs(g - want)) * n, rel_l2(g, want))
+
+
+def test_score_strided_views_of_a_fused_qkv_buffer():
+    Hq, Hkv, dh, n = 8, 2, 128, 700
+    rng = np.random.default_rng(3)
+    qkv = fi.round_bf16(rng.standard_normal((n, (Hq + 2 * Hkv) * dh)).astype(np.float32))
+    t = dev(qkv, "bf16")
+    m = fa.make_model(1, 64, Hq, Hkv, dh, 64)
+    got = host(fa.fastav_score(m, t, t[:, Hq * dh:], torch.tensor([0, n], dtype=torch.int32).cuda(), n, 1,
+                               q_row_stride=t.stride(0), k_row_stride=t.stride(0)))
+    q = qkv[:, :Hq * dh].reshape(n, Hq, dh).astype(np.float64)
+    k = qkv[:, Hq * dh:(Hq + Hkv) * dh].reshape(n, Hkv, dh).astype(np.float64)
+    want = orc.last_query_scores(q, k, 1)
+    assert np.max(np.abs(got - want)) * n <= 1e-3
+
+
+# ------------------------------------------------------------------------------------ row-wise ops
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("rows,d", [(1, 256), (77, 4096), (33, 3584), (5, 250)])
+def test_rmsnorm(dtype, rows, d):
+    rng = np.random.default_rng(rows + d)
+    x = (rng.standard_normal((rows, d)) * 3 + 0.5).astype(np.float32)
+    g = (1 + 0.02 * rng.standard_normal(d)).astype(np.float32)
+    if dtype == "bf16":
+        fi.round_bf16(g)
+    got = host(fa.fastav_rmsnorm(torch.from_numpy(x).cuda(), dev(g, dtype), 1e-6))
+    assert_close(got, orc.rmsnorm(x.astype(np.float64), g.astype(np.float64), 1e-6), dtype, what="rmsnorm")
+
+
+@pytest.mark.parametrize("dtype,dh,base", [("bf16", 128, 1e4), ("bf16", 128, 1e6), ("f32", 64, 1e4), ("bf16", 64, 1e4)])
+def test_rope_with_original_positions(dtype, dh, base):
+    rng = np.random.default_rng(dh)
+    n, H, extra = 50, 5, 2 * dh                                     # rows wider than the rotated heads (V part untouched)
+    x = rng.standard_normal((n, H * dh + extra)).astype(np.float32)
+    if dtype == "bf16":
+        fi.round_bf16(x)
+    pos = np.sort(rng.choice(16384, n, replace=False)).astype(np.int32)
+    pos[0] = 0; pos[-1] = 16383
+    t = dev(x, dtype)
+    fa.fastav_rope(t, torch.from_numpy(pos).cuda(), H, dh, base)
+    got = host(t)
+    want = orc.rope(x[:, :H * dh].reshape(n, H, dh).astype(np.float64), pos, base).reshape(n, H * dh)
+    assert_close(got[:, :H * dh], want, dtype, what="rope")
+    assert np.array_equal(got[:, H * dh:], x[:, H * dh:].astype(np.float64))
+
+
+# ------------------------------------------------------------------------------------ linear layers
+LINEAR_SHAPES = [("f32", 100, 688, 256), ("f32", 37, 256, 688), ("bf16", 100, 200, 72),
+                 ("bf16", 300, 1024, 512), ("bf16", 1205, 512, 1024), ("bf16", 257, 6144, 4096), ("bf16", 129, 3584, 1024)]
+
+
+@pytest.mark.parametrize("dtype,M,N,K", LINEAR_SHAPES)
+@pytest.mark.parametrize("epi", [fa.EPI_STORE, fa.EPI_RESADD, fa.EPI_SWIGLU])
+def test_linear(dtype, M, N, K, epi):
+    rng = np.random.default_rng(M + N + K + epi)
+    a = rng.standard_normal((M, K)).astype(np.float32)
+    w = (rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32)
+    w2 = (rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32)
+    if dtype == "bf16":
+        fi.round_bf16(a); fi.round_bf16(w); fi.round_bf16(w2)
+    a64, w64, w264 = a.astype(np.float64), w.astype(np.float64), w2.astype(np.float64)
+    if epi == fa.EPI_STORE:
+        got = host(fa.fastav_linear(dev(a, dtype), dev(w, dtype)))
+        want = a64 @ w64.T
+    elif epi == fa.EPI_RESADD:
+        r = rng.standard_normal((M, N)).astype(np.float32)
+        c = torch.from_numpy(r.copy()).cuda()
+        fa.fastav_linear(dev(a, dtype), dev(w, dtype), fa.EPI_RESADD, c=c)
+        got, want = host(c), r.astype(np.float64) + a64 @ w64.T
+    else:
+        got = host(fa.fastav_linear(dev(a, dtype), dev(w, dtype), fa.EPI_SWIGLU, w2=dev(w2, dtype)))
+        want = orc.silu(a64 @ w64.T) * (a64 @ w264.T)
+    assert_close(got, want, dtype, what=f"linear epi={epi}")
+
+
+# ------------------------------------------------------------------------------------ attention (+ side output)
+@pytest.mark.parametrize("dtype,Hq,Hkv,dh,lens", [("f32", 4, 2, 64, [130, 1, 77]), ("bf16", 8, 2, 128, [300, 129, 64]),
+                                                 ("bf16", 4, 4, 64, [200, 65]), ("bf16", 32, 8, 128, [700]),
+                                                 ("bf16", 28, 4, 128, [257, 500])])
+def test_attention_and_last_row_side_output(dtype, Hq, Hkv, dh, lens):
+    rng = np.random.default_rng(Hq + dh + len(lens))
+    T = sum(lens)
+    qkv = rng.standard_normal((T, (Hq + 2 * Hkv) * dh)).astype(np.float32)
+    qkv[:, :(Hq + Hkv) * dh] *= 1.3
+    if dtype == "bf16":
+        fi.round_bf16(qkv)
+    t = dev(qkv, dtype)
+    q = t.as_strided((T, Hq, dh), (t.stride(0), dh, 1))
+    k = t.as_strided((T, Hkv, dh), (t.stride(0), dh, 1), Hq * dh)
+    v = t.as_strided((T, Hkv, dh), (t.stride(0), dh, 1), (Hq + Hkv) * dh)
+    m = fa.make_model(1, 64, Hq, Hkv, dh, 64, dtype=fa.BF16 if dtype == "bf16" else fa.F32)
+    cu = _cu(lens)
+    cu_dev = torch.from_numpy(cu).cuda()
+    o, ll, ml = fa.fastav_attention(m, q, k, v, cu_dev, max(lens), want_last=True)
+    o2 = fa.fastav_attention(m, q, k, v, cu_dev, max(lens))
+    assert torch.equal(o, o2)                                     # the side output does not change the result
+    got, ll, ml = host(o), host(ll), host(ml)
+    q64 = qkv[:, :Hq * dh].reshape(T, Hq, dh).astype(np.float64)
+    k64 = qkv[:, Hq * dh:(Hq + Hkv) * dh].reshape(T, Hkv, dh).astype(np.float64)
+    v64 = qkv[:, (Hq + Hkv) * dh:].reshape(T, Hkv, dh).astype(np.float64)
+    G = Hq // Hkv
+    for b, n in enumerate(lens):
+        sl = slice(cu[b], cu[b + 1])
+        want = orc.causal_gqa_attention(q64[sl], k64[sl], v64[sl])
+        assert_close(got[sl], want, dtype, what=f"attention sample {b}")
+        # side output: scaled logits of the last row and its (max, sum exp)
+        for h in range(Hq):
+            z = (k64[sl, h // G] @ q64[cu[b + 1] - 1, h]) / np.sqrt(dh)
+            assert np.max(np.abs(ll[h, sl] - z)) <= 1e-3 * max(1.0, np.abs(z).max())
+            assert abs(ml[b, h, 0] - z.max()) <= 1e-3 * max(1.0, abs(z.max()))
+            assert abs(ml[b, h, 1] - np.exp(z - ml[b, h, 0]).sum()) <= 2e-3 * np.exp(z - z.max()).sum()
+
+
+# ------------------------------------------------------------------------------------ prefill end to end
+def _oracle_and_gpu(w: fi.Workload, weights, x, want_kv=True):
+    dec = make_decoder(w.model, weights)
+    spans, offs = fi.span_table(w)
+    out = dec.fastav_prefill(dev(x, w.model.dtype), fi.cu_seqlens(w), spans, offs, prune_tuples(w), w.n_last,
+                             want_kv=want_kv, want_trace=True, want_layers=True)
+    torch.cuda.synchronize()
+    ref = orc.prefill(w, weights, x)
+    return out, ref
+
+
+def _check_prefill(w: fi.Workload, out, ref, x_scale_from_ref=True):
+    """Kept sets (tie band), surviving positions, hidden states on the common survivors, K/V."""
+    dtype = w.model.dtype
+    cu0 = fi.cu_seqlens(w)
+    B = len(w.samples)
+    got_pos = out["kept_pos"].cpu().numpy()
+    got_cu = out["cu_seqlens_out"].cpu().numpy()
+    assert got_cu[-1] == len(got_pos) == out["x_out"].shape[0]
+    x_out = host(out["x_out"])
+    stats = {"flipped": 0}
+    # per prune: compare kept sets in terms of ORIGINAL positions
+    for b in range(B):
+        r = ref[b]
+        n_prunes = len(r["prunes"])
+        for i, pr in enumerate(r["prunes"]):
+            want_pos = set(pr["pos_in"][pr["keep"]].tolist())
+            # GPU kept rows of prune i, mapped to original positions through the previous prunes
+            idx = out["prune_keep_idx"][i].cpu().numpy()
+            stage_lens_in = [pr_["n_in"] for pr_ in [rr["prunes"][i] for rr in ref]]
+            cu_in = _cu(stage_lens_in)
+            mine = idx[(idx >= cu_in[b]) & (idx < cu_in[b + 1])] - cu_in[b]
+            # original positions entering prune i on the GPU
+            pos_in = np.arange(cu0[b + 1] - cu0[b])
+            for j in range(i):
+                idx_j = out["prune_keep_idx"][j].cpu().numpy()
+                cu_j = _cu([rr["prunes"][j]["n_in"] for rr in ref])
+                sel = idx_j[(idx_j >= cu_j[b]) & (idx_j < cu_j[b + 1])] - cu_j[b]
+                pos_in = pos_in[sel]
+            got_set = set(pos_in[mine].tolist())
+            assert len(got_set) == pr["k"]
+            diff = got_set ^ want_pos
+            if diff:
+                assert pr["kind"] == fi.FINE, "a global prune is positional and must match exactly"
+                s = pr["scores"]
+                prot0 = orc.protected_mask(w.samples[b], w.n_last)
+                cand_kept = [j for j in pr["keep"] if not prot0[pr["pos_in"][j]]]
+                kth = min(s[j] for j in cand_kept) if cand_kept else 0.0
+                pos_to_local = {int(p): j for j, p in enumerate(pr["pos_in"])}
+                for p in diff:
+                    assert p in pos_to_local, "GPU kept a token the oracle had already dropped outside the tie band"
+                    assert abs(s[pos_to_local[p]] - kth) <= TIE_BAND, (b, i, p, s[pos_to_local[p]], kth)
+                stats["flipped"] += len(diff) // 2
+            if pr["kind"] == fi.FINE and out["prune_scores"][i] is not None and not stats["flipped"]:
+                g = host(out["prune_scores"][i])[cu_in[b]:cu_in[b + 1]]
+                n = len(g)
+                lim = 2e-2 if dtype == "bf16" else 1e-4
+                assert np.max(np.abs(g - pr["scores"])) * n <= lim * max(1.0, pr["scores"].max() * n), \
+                    (np.max(np.abs(g - pr["scores"])) * n, pr["scores"].max() * n)
+        # final hidden state on the common survivors
+        mine_pos = got_pos[got_cu[b]:got_cu[b + 1]]
+        assert (np.diff(mine_pos) > 0).all()
+        common, gi, ri = np.intersect1d(mine_pos, r["kept_pos"], return_indices=True)
+        assert len(common) >= len(mine_pos) - stats["flipped"]
+        gx, rx = x_out[got_cu[b]:got_cu[b + 1]][gi], r["x_out"][ri]
+        scale = float(np.sqrt(np.mean(rx ** 2)))
+        stats[f"x_rel_l2_{b}"] = rel_l2(gx, rx)
+        stats[f"x_max_abs_over_rms_{b}"] = float(np.max(np.abs(gx - rx))) / scale
+    return stats
+
+
+def test_prefill_cfg1_tiny_fp32():
+    w = fi.config(1)
+    weights = [fi.layer_weights(w.model, l, w.weight_seed) for l in range(w.model.n_layers)]
+    x = fi.embeddings(w)
+    out, ref = _oracle_and_gpu(w, weights, x)
+    st = _check_prefill(w, out, ref)
+    assert st["flipped"] == 0
+    assert st["x_rel_l2_0"] <= 2e-5 and st["x_max_abs_over_rms_0"] <= 2e-4, st
+    assert out["x_out"].shape[0] == 128 and out["tokens_in"].tolist() == [512, 512, 256, 256]
+    # K/V caches: layer 3's are compacted to the survivors
+    for l, (k, v) in enumerate(out["kv"]):
+        rk, rv = ref[0]["kv"][l]
+        assert_close(host(k), rk, "f32", what=f"K layer {l}")
+        assert_close(host(v), rv, "f32", what=f"V layer {l}")
+    # per-layer hidden states
+    r_trace = orc.prefill(w, weights, x, trace=True)[0]["trace"]
+    for l in range(3):
+        assert rel_l2(host(out["layer_x"][l]), r_trace[l]["x_out"]) <= 2e-5
+
+
+def _small_bf16():
+    m = fi.Model(3, 512, 8, 2, 128, 1024, 1.0e4, 1e-6, "bf16")
+    w = fi.Workload("small_bf16", m, [[(fi.VIDEO, 288), (fi.AUDIO, 150), (fi.TEXT, 30)], [(fi.VIDEO, 144), (fi.AUDIO, 97), (fi.TEXT, 9)]],
+                    [fi.Prune(1, fi.GLOBAL, 0.6), fi.Prune(1, fi.FINE, 0.7), fi.Prune(2, fi.FINE, 0.7)], seed=41)
+    weights = [fi.layer_weights(m, l, 7) for l in range(m.n_layers)]
+    return w, weights, fi.embeddings(w)
+
+
+def test_prefill_small_bf16_ragged_batch():
+    w, weights, x = _small_bf16()
+    out, ref = _oracle_and_gpu(w, weights, x)
+    st = _check_prefill(w, out, ref)
+    for b in range(2):
+        assert st[f"x_rel_l2_{b}"] <= 1e-2 and st[f"x_max_abs_over_rms_{b}"] <= 5e-2, st
+
+
+def test_prefill_keep_ratio_one_is_the_unpruned_forward():
+    w, weights, x = _small_bf16()
+    dec = make_decoder(w.model, weights)
+    spans, offs = fi.span_table(w)
+    xd = dev(x, "bf16")
+    plain = dec.fastav_prefill(xd, fi.cu_seqlens(w), spans, offs, [], 1)
+    x_plain = plain["x_out"].clone()
+    ones = dec.fastav_prefill(xd, fi.cu_seqlens(w), spans, offs, [(p.layer, p.kind, 1.0) for p in w.prunes], 1)
+    torch.cuda.synchronize()
+    assert torch.equal(x_plain, ones["x_out"])
+    assert np.array_equal(ones["kept_pos"].cpu().numpy(), np.concatenate([np.arange(n) for n in w.seqlens]))
+    assert np.array_equal(ones["cu_seqlens_out"].cpu().numpy(), fi.cu_seqlens(w))
+
+
+def test_prefill_batched_equals_per_sample():
+    w, weights, x = _small_bf16()
+    dec = make_decoder(w.model, weights)
+    spans, offs = fi.span_table(w)
+    both = dec.fastav_prefill(dev(x, "bf16"), fi.cu_seqlens(w), spans, offs, prune_tuples(w), 1)
+    xb, posb, cub = both["x_out"].clone(), both["kept_pos"].clone(), both["cu_seqlens_out"].cpu().numpy()
+    row = 0
+    for b, s in enumerate(w.samples):
+        n = sum(l for _, l in s)
+        wb = fi.Workload("one", w.model, [s], w.prunes)
+        sp, of = fi.span_table(wb)
+        one = dec.fastav_prefill(dev(x[row:row + n], "bf16"), [0, n], sp, of, prune_tuples(w), 1)
+        torch.cuda.synchronize()
+        assert torch.equal(one["kept_pos"], posb[cub[b]:cub[b + 1]])
+        assert torch.equal(one["x_out"], xb[cub[b]:cub[b + 1]])
+        row += n
+
+
+def test_prefill_n_last_greater_than_one():
+    w, weights, x = _small_bf16()
+    w.n_last = 3
+    out, ref = _oracle_and_gpu(w, weights, x, want_kv=False)
+    st = _check_prefill(w, out, ref)
+    for b in range(2):
+        assert st[f"x_rel_l2_{b}"] <= 1e-2, st
+
+
+def test_prefill_cfg2_7b_single_layer():
+    w = fi.config(2)
+    weights = [fi.layer_weights(w.model, 0, w.weight_seed)]
+    x = fi.embeddings(w)
+    out, ref = _oracle_and_gpu(w, weights, x)
+    st = _check_prefill(w, out, ref)
+    assert out["x_out"].shape[0] == 1229
+    assert st["x_rel_l2_0"] <= 1e-2 and st["x_max_abs_over_rms_0"] <= 5e-2, st
+    rk, rv = ref[0]["kv"][0]
+    common, gi, ri = np.intersect1d(out["kept_pos"].cpu().numpy(), ref[0]["kept_pos"], return_indices=True)
+    assert_close(host(out["kv"][0][0])[gi], rk[ri], "bf16", scale=float(np.sqrt(np.mean(rk ** 2))), what="K")
+    assert_close(host(out["kv"][0][1])[gi], rv[ri], "bf16", scale=float(np.sqrt(np.mean(rv ** 2))), what="V")
