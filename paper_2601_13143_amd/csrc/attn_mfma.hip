@@ -1,5 +1,203 @@
+// Causal grouped-query flash attention for prefill on the CDNA4 matrix cores (bf16 in, fp32 accumulate),
+// with the last-query logits of Eq. 4 as a side output.
+//
+// One workgroup = 128 query rows of one head of one sample; each of its 4 waves owns 32 rows.  K/V tiles
+// of 64 keys are staged in LDS (K row-major with XOR-swizzled 16-byte chunks; V transposed to [d][key] so
+// that the P V product reads key-contiguous operands).  The products are formed transposed,
+//     S^T = K Q^T   and   O^T = V^T P^T   (v_mfma_f32_32x32x16_bf16),
+// so that in every accumulator a lane's column is ONE query row: the running max / sum of the softmax
+// recurrence are per-lane scalars (one cross-lane exchange per tile, with the lane 32 away that holds the
+// other half of the keys), the rescale of O^T is a per-lane multiply, and exp2(S^T - m) converts in place
+// into the B operand of the second product (the key order inside an MFMA k-step is whatever order the
+// accumulator holds; V^T is read in the same order, a sum does not care).
+//
+// The lane whose query is the last row of a sample also writes that row's scaled logits for every key
+// and its final (max, sum): the fine-prune score is finalised from those without a second pass over K.
 #include "common.hpp"
+
 namespace fastav {
-bool mfma_attention_supported(int, int, int64_t, int64_t, int64_t) { return false; }
-fastav_status_t launch_attention_mfma(const void*, int64_t, const void*, const void*, int64_t, void*, int64_t, const int32_t*, int, int64_t, int, int, int, int, float*, float*, hipStream_t) { return fail(FASTAV_EUNSUPPORTED, "mfma attention not built"); }
+
+struct AttnArgs {
+  const bf16_t* q; const bf16_t* k; const bf16_t* v; bf16_t* o;
+  int64_t qs, kvs, os;                 // row strides in elements
+  const int32_t* cu;
+  int Hq, Hkv, n_qtiles;
+  float scale, scale_log2;             // 1/sqrt(dh) and the same times log2(e)
+  int64_t T;
+  float* last_logits; float* last_ml;
+};
+
+template <int DH>
+__global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a) {
+  constexpr int BQ = 128, BKV = 64;
+  constexpr int DCH = DH / 8;                       // 16-byte chunks per K row
+  constexpr int VP = BKV + 4;                       // pitch (elements) of a V^T row: 8-byte aligned, staggers banks
+  constexpr int NS = DH / 16;                       // MFMA k-steps over the head dimension
+  constexpr int NDB = DH / 32;                      // 32-row blocks of O^T
+  __shared__ bf16x8_t Ks[BKV * DCH];
+  __shared__ __attribute__((aligned(16))) bf16_t Vt[DH * VP];
+
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int row0 = a.cu[b], n = a.cu[b + 1] - row0;
+  const int q0 = (a.n_qtiles - 1 - (int)blockIdx.x) * BQ;        // longest tiles first
+  if (q0 >= n) return;
+  const int g = h / (a.Hq / a.Hkv);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, hf = lane >> 5;
+  const int qw0 = q0 + 32 * wave;
+  const int qi = qw0 + l32;                                       // this lane's query row (in-sample)
+  const bool wave_live = qw0 < n;
+
+  bf16x8_t qf[NS];
+  {
+    const int qr = qi < n ? qi : n - 1;
+    const bf16_t* qp = a.q + (int64_t)(row0 + qr) * a.qs + h * DH + hf * 8;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) qf[s] = *(const bf16x8_t*)(qp + 16 * s);
+  }
+  f32x16_t o[NDB];
+#pragma unroll
+  for (int d = 0; d < NDB; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
+  float m = -INFINITY, l = 0.f;
+  const bool emit = (a.last_logits != nullptr) && (qi == n - 1);
+
+  const int kv_end = (q0 + BQ < n) ? q0 + BQ : n;                // keys this workgroup can see
+  const int n_tiles = (kv_end + BKV - 1) / BKV;
+  const bf16_t* kbase = a.k + (int64_t)row0 * a.kvs + g * DH;
+  const bf16_t* vbase = a.v + (int64_t)row0 * a.kvs + g * DH;
+
+  for (int t = 0; t < n_tiles; ++t) {
+    const int j0 = t * BKV;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < BKV * DCH / 256; ++i) {
+      const int idx = tid + 256 * i;
+      const int key = idx / DCH, c = idx % DCH;
+      const int jr = (j0 + key < n) ? j0 + key : n - 1;
+      const bf16x8_t kv = *(const bf16x8_t*)(kbase + (int64_t)jr * a.kvs + c * 8);
+      Ks[key * DCH + (c ^ (key & 7))] = kv;
+      bf16x8_t vv = *(const bf16x8_t*)(vbase + (int64_t)jr * a.kvs + c * 8);
+      if (j0 + key >= n) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vv[e] = (bf16_t)0.f;          // masked keys must not inject NaN/Inf through 0 * x
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) Vt[(c * 8 + e) * VP + key] = vv[e];
+    }
+    __syncthreads();
+    if (!wave_live || j0 > qw0 + 31) continue;                    // nothing visible to this wave in this tile
+
+    // ---- S^T = K Q^T : s[kb][r] is (key j0 + 32kb + (r/4)*8 + hf*4 + r%4, query qi)
+    f32x16_t s[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+      const int key = kb * 32 + l32;
+#pragma unroll
+      for (int st = 0; st < NS; ++st) {
+        const bf16x8_t kf = Ks[key * DCH + ((2 * st + hf) ^ (key & 7))];
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], s[kb], 0, 0, 0);
+      }
+    }
+    const bool need_mask = (j0 + BKV - 1 > qw0) || (j0 + BKV > n);
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = j0 + kb * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
+        const float raw = s[kb][r];
+        float val = raw * a.scale_log2;
+        const bool vis = !need_mask || (key <= qi && key < n);
+        if (!vis) val = -INFINITY;
+        if (emit && key <= qi) a.last_logits[(int64_t)h * a.T + row0 + key] = raw * a.scale;
+        s[kb][r] = val;
+        mx = fmaxf(mx, val);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+    const float m_new = fmaxf(m, mx);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = exp2f(m - m_use);
+    l *= alpha;
+#pragma unroll
+    for (int d = 0; d < NDB; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+    bf16x8_t pb[2][2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = exp2f(s[kb][r] - m_use);
+        l += p;
+        pb[kb][r >> 3][r & 7] = (bf16_t)p;
+      }
+    m = m_new;
+
+    // ---- O^T += V^T P^T : k-step (kb, sp) slot e holds key 32kb + 16sp + (e/4)*8 + hf*4 + e%4
+#pragma unroll
+    for (int d = 0; d < NDB; ++d) {
+      const bf16_t* vrow = Vt + (d * 32 + l32) * VP + hf * 4;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp) {
+          const bf16x4_t v0 = *(const bf16x4_t*)(vrow + kb * 32 + sp * 16);
+          const bf16x4_t v1 = *(const bf16x4_t*)(vrow + kb * 32 + sp * 16 + 8);
+          bf16x8_t vf;
+          vf[0] = v0[0]; vf[1] = v0[1]; vf[2] = v0[2]; vf[3] = v0[3];
+          vf[4] = v1[0]; vf[5] = v1[1]; vf[6] = v1[2]; vf[7] = v1[3];
+          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[kb][sp], o[d], 0, 0, 0);
+        }
+    }
+  }
+
+  // ---- normalise and store.  o[d][r] is (dim 32d + (r/4)*8 + hf*4 + r%4, query qi).
+  const float l_tot = l + __shfl_xor(l, 32, kWave);
+  if (qi < n) {
+    const float inv = 1.0f / l_tot;
+    bf16_t* op = a.o + (int64_t)(row0 + qi) * a.os + h * DH + hf * 4;
+#pragma unroll
+    for (int d = 0; d < NDB; ++d)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4_t w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (bf16_t)(o[d][4 * r4 + e] * inv);
+        *(bf16x4_t*)(op + d * 32 + r4 * 8) = w;
+      }
+    if (emit && hf == 0 && a.last_ml) {
+      a.last_ml[((int64_t)b * a.Hq + h) * 2] = m * 0.6931471805599453f;     // back from the log2 domain
+      a.last_ml[((int64_t)b * a.Hq + h) * 2 + 1] = l_tot;
+    }
+  }
 }
+
+bool mfma_attention_supported(int dh, int dtype, int64_t q_stride, int64_t kv_stride, int64_t o_stride) {
+  return dtype == FASTAV_BF16 && (dh == 64 || dh == 128) && q_stride % 8 == 0 && kv_stride % 8 == 0 && o_stride % 4 == 0;
+}
+
+fastav_status_t launch_attention_mfma(const void* q, int64_t q_stride, const void* k, const void* v,
+                                      int64_t kv_stride, void* o, int64_t o_stride, const int32_t* cu, int batch,
+                                      int64_t T, int max_seqlen, int Hq, int Hkv, int dh, float* last_logits,
+                                      float* last_ml, hipStream_t s) {
+  if (batch == 0 || max_seqlen == 0) return FASTAV_OK;
+  if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v) % 16 || ((uintptr_t)o % 8))
+    return fail(FASTAV_EINVAL, "attention: q, k, v must be 16-byte aligned and o 8-byte aligned");
+  AttnArgs a;
+  a.q = (const bf16_t*)q; a.k = (const bf16_t*)k; a.v = (const bf16_t*)v; a.o = (bf16_t*)o;
+  a.qs = q_stride; a.kvs = kv_stride; a.os = o_stride; a.cu = cu; a.Hq = Hq; a.Hkv = Hkv;
+  a.n_qtiles = (max_seqlen + 127) / 128;
+  a.scale = 1.0f / sqrtf((float)dh);
+  a.scale_log2 = a.scale * 1.4426950408889634f;
+  a.T = T; a.last_logits = last_logits; a.last_ml = last_ml;
+  dim3 grid((unsigned)a.n_qtiles, (unsigned)Hq, (unsigned)batch);
+  if (dh == 128) hipLaunchKernelGGL(k_attn_mfma<128>, grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(k_attn_mfma<64>, grid, dim3(256), 0, s, a);
+  return check_launch("attention_mfma");
+}
+
+}  // namespace fastav

@@ -148,7 +148,8 @@ def test_rope_with_original_positions(dtype, dh, base):
 
 # ------------------------------------------------------------------------------------ linear layers
 LINEAR_SHAPES = [("f32", 100, 688, 256), ("f32", 37, 256, 688), ("bf16", 100, 200, 72),
-                 ("bf16", 300, 1024, 512), ("bf16", 1205, 512, 1024), ("bf16", 257, 6144, 4096), ("bf16", 129, 3584, 1024)]
+                 ("bf16", 300, 1024, 512), ("bf16", 1205, 512, 1024), ("bf16", 257, 6144, 4096), ("bf16", 129, 3584, 1024),
+                 ("bf16", 2100, 6144, 256), ("bf16", 4000, 2048, 192)]
 
 
 @pytest.mark.parametrize("dtype,M,N,K", LINEAR_SHAPES)
@@ -233,19 +234,18 @@ def _check_prefill(w: fi.Workload, out, ref, x_scale_from_ref=True):
     got_cu = out["cu_seqlens_out"].cpu().numpy()
     assert got_cu[-1] == len(got_pos) == out["x_out"].shape[0]
     x_out = host(out["x_out"])
-    stats = {"flipped": 0}
+    stats = {"flipped": 0, "flips_per_prune": []}
     # per prune: compare kept sets in terms of ORIGINAL positions
     for b in range(B):
         r = ref[b]
-        n_prunes = len(r["prunes"])
+        prot0 = orc.protected_mask(w.samples[b], w.n_last)
+        inherited = set()                      # positions that already differed at an earlier prune
         for i, pr in enumerate(r["prunes"]):
             want_pos = set(pr["pos_in"][pr["keep"]].tolist())
             # GPU kept rows of prune i, mapped to original positions through the previous prunes
             idx = out["prune_keep_idx"][i].cpu().numpy()
-            stage_lens_in = [pr_["n_in"] for pr_ in [rr["prunes"][i] for rr in ref]]
-            cu_in = _cu(stage_lens_in)
+            cu_in = _cu([rr["prunes"][i]["n_in"] for rr in ref])
             mine = idx[(idx >= cu_in[b]) & (idx < cu_in[b + 1])] - cu_in[b]
-            # original positions entering prune i on the GPU
             pos_in = np.arange(cu0[b + 1] - cu0[b])
             for j in range(i):
                 idx_j = out["prune_keep_idx"][j].cpu().numpy()
@@ -253,20 +253,25 @@ def _check_prefill(w: fi.Workload, out, ref, x_scale_from_ref=True):
                 sel = idx_j[(idx_j >= cu_j[b]) & (idx_j < cu_j[b + 1])] - cu_j[b]
                 pos_in = pos_in[sel]
             got_set = set(pos_in[mine].tolist())
-            assert len(got_set) == pr["k"]
-            diff = got_set ^ want_pos
+            assert len(got_set) == pr["k"] and (np.diff(mine) > 0).all()
+            assert set(np.nonzero(prot0)[0].tolist()) <= got_set, "a protected token was pruned"
+            diff = (got_set ^ want_pos) - inherited
             if diff:
                 assert pr["kind"] == fi.FINE, "a global prune is positional and must match exactly"
-                s = pr["scores"]
-                prot0 = orc.protected_mask(w.samples[b], w.n_last)
+                s_ref = pr["scores"]
                 cand_kept = [j for j in pr["keep"] if not prot0[pr["pos_in"][j]]]
-                kth = min(s[j] for j in cand_kept) if cand_kept else 0.0
+                kth = min(s_ref[j] for j in cand_kept) if cand_kept else 0.0
                 pos_to_local = {int(p): j for j, p in enumerate(pr["pos_in"])}
                 for p in diff:
-                    assert p in pos_to_local, "GPU kept a token the oracle had already dropped outside the tie band"
-                    assert abs(s[pos_to_local[p]] - kth) <= TIE_BAND, (b, i, p, s[pos_to_local[p]], kth)
-                stats["flipped"] += len(diff) // 2
-            if pr["kind"] == fi.FINE and out["prune_scores"][i] is not None and not stats["flipped"]:
+                    # a token the oracle no longer holds can only be the partner of an earlier flip
+                    assert p in pos_to_local, (b, i, p, "differs, yet was never within a tie band")
+                    assert abs(s_ref[pos_to_local[p]] - kth) <= TIE_BAND, (b, i, p, s_ref[pos_to_local[p]], kth)
+                # beyond the literal band: bf16 noise may only flip a small fraction of the kept set
+                assert len(diff) <= max(4, int(0.03 * pr["k"])), (b, i, len(diff), pr["k"])
+            stats["flips_per_prune"].append((b, i, len(diff) // 2))
+            stats["flipped"] += (len(diff) + 1) // 2
+            inherited |= (got_set ^ want_pos)
+            if pr["kind"] == fi.FINE and out["prune_scores"][i] is not None and not inherited:
                 g = host(out["prune_scores"][i])[cu_in[b]:cu_in[b + 1]]
                 n = len(g)
                 lim = 2e-2 if dtype == "bf16" else 1e-4
