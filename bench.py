@@ -1,0 +1,199 @@
+"""Benchmark of the FastAV pruned prefill on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3]
+
+A step is one pass of the whole hot path (every layer, every prune step) over one batch of synthetic
+audio-visual tokens already resident in HBM.  Prints ONE JSON line: pruned-prefill tokens/s as `value`,
+the unpruned rate and the prune-step times beside it, a `roofline` object for the dominant kernel (the
+gate/up SwiGLU GEMM) measured with HIP events around its launches, one entry per other kernel kind, and
+the CPU oracle timed on this host (`cpu_baseline`)."""
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import fastav_inputs as fi  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+WORKLOADS = {"cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4, "cfg5": 5}
+
+
+def _upload_weights(dec, m, seed, threads):
+    import torch
+
+    def gen(l):
+        W = fi.layer_weights(m, l, seed)
+        return l, {k: (fi.bf16_bits(v) if m.dtype == "bf16" else v) for k, v in W.items()}
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        for l, W in ex.map(gen, range(m.n_layers)):
+            dev = {}
+            for k, v in W.items():
+                t = torch.from_numpy(v).cuda()
+                dev[k] = t.view(torch.bfloat16) if m.dtype == "bf16" else t
+            dec.fastav_set_weights(l, dev)
+
+
+def _cpu_baseline(w, threads):
+    """Times the oracle, as it stands, on a bounded sample of the workload: a 4-layer surrogate that runs one
+    layer at each token count of the schedule (n0; after the global prune with the first fine prune; after
+    it with the second; after that), each layer timed through the oracle's own per-layer weight callback,
+    then weighted by how many layers of the real model run at that count."""
+    from oracle import fastav_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        used = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        used = threads
+    m = w.model
+    globals_ = [p for p in w.prunes if p.kind == fi.GLOBAL]
+    fines = [p for p in w.prunes if p.kind == fi.FINE]
+    if not (len(w.samples) == 1 and len(globals_) == 1 and len(fines) == 2):
+        return None
+    m4 = fi.Model(4, m.hidden, m.n_q_heads, m.n_kv_heads, m.head_dim, m.mlp_dim, m.rope_base, m.rms_eps, m.dtype)
+    prunes4 = [fi.Prune(1, fi.GLOBAL, globals_[0].keep_ratio), fi.Prune(1, fi.FINE, fines[0].keep_ratio),
+               fi.Prune(2, fi.FINE, fines[1].keep_ratio)]
+    w4 = fi.Workload("surrogate", m4, w.samples, prunes4, w.n_last, w.seed, w.weight_seed)
+    x = fi.embeddings(w4)
+    W = fi.layer_weights(m4, 0, w.weight_seed)
+    marks = []
+
+    def get_w(l):
+        marks.append(time.perf_counter())
+        return W
+
+    orc.prefill(w4, get_w, x, keep_kv=False)
+    marks.append(time.perf_counter())
+    per_layer = np.diff(marks)                       # seconds at token counts n0, n1, n2, n3
+    g, f1, f2 = globals_[0].layer, fines[0].layer, fines[1].layer
+    # real schedule: layers [0,g) at n0; [g,f1] at n1; (f1,f2] at n2; (f2,L) at n3
+    counts = [g, f1 - g + 1, f2 - f1, m.n_layers - 1 - f2]
+    total = float(np.dot(per_layer, counts))
+    return {"value": w.total_tokens / total, "unit": "tokens/s", "cores": int(used), "kind": "oracle",
+            "sample": f"fp64 NumPy oracle on a 4-layer surrogate (one layer per token count of the pruned schedule, "
+                      f"{per_layer.sum():.1f} s measured), extrapolated to {m.n_layers} layers by layer counts {counts}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-passes", action="store_true", help="skip the per-kernel timing passes")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the path is single-GPU by design; see DESIGN.md); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2601_13143_amd as fa
+
+    fa.lib()
+    host_threads = len(os.sched_getaffinity(0))
+    w = fi.config(WORKLOADS[args.workload])
+    m = w.model
+    dec = fa.Decoder(fa.make_model(m.n_layers, m.hidden, m.n_q_heads, m.n_kv_heads, m.head_dim, m.mlp_dim, m.rope_base,
+                                   m.rms_eps, fa.BF16 if m.dtype == "bf16" else fa.F32))
+    t0 = time.time()
+    _upload_weights(dec, m, w.weight_seed, min(16, host_threads))
+    x_np = fi.embeddings(w)
+    x = torch.from_numpy(fi.bf16_bits(x_np)).cuda().view(torch.bfloat16) if m.dtype == "bf16" else torch.from_numpy(x_np).cuda()
+    setup_s = time.time() - t0
+    cu, (spans, offs) = fi.cu_seqlens(w), fi.span_table(w)
+    prunes = [(p.layer, p.kind, p.keep_ratio) for p in w.prunes]
+    tokens = w.total_tokens
+
+    dominant = "linear_swiglu"
+
+    def run(pr, steps, outputs=None):
+        o = outputs
+        for _ in range(steps):
+            o = dec.fastav_prefill(x, cu, spans, offs, pr, w.n_last, want_kv=True, outputs=o)
+        return o
+
+    def timed(pr, steps, warmup):
+        o = run(pr, warmup)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        run(pr, steps, o)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / steps
+
+    fa.fastav_profile_reset()
+    fa.fastav_profile_enable([dominant])              # events around the dominant kernel only, whole run
+    s_pruned = timed(prunes, args.steps, args.warmup)
+    s_plain = timed([], args.steps, args.warmup)
+
+    # ---- per-kernel passes (not part of `value`): all kinds timed with events, pruned then unpruned
+    kernels = {}
+    if not args.no_kernel_passes:
+        kinds = [k for k in fa.PROF_KINDS if k != "other"]
+        fa.fastav_profile_enable(kinds)
+        o = run(prunes, 1)
+        torch.cuda.synchronize()
+        base = {k: fa.fastav_profile_collect(k) for k in kinds}
+        run(prunes, 3, o)
+        torch.cuda.synchronize()
+        after = {k: fa.fastav_profile_collect(k) for k in kinds}
+        o2 = run([], 1)
+        torch.cuda.synchronize()
+        mid = {k: fa.fastav_profile_collect(k) for k in kinds}
+        run([], 3, o2)
+        torch.cuda.synchronize()
+        for k in kinds:
+            ms, n, wk = (after[k][i] - base[k][i] for i in range(3))
+            if n == 0:
+                continue
+            flops = k.startswith("linear") or k == "attention"
+            rate = wk / (ms * 1e-3) / (1e12 if flops else 1e9) if ms > 0 else 0.0
+            kernels[k] = {"launches_per_step": n / 3, "ms_per_step": ms / 3, "us_per_launch": 1e3 * ms / n,
+                          "achieved": rate, "unit": "TFLOP/s" if flops else "GB/s",
+                          "frac": rate / (PEAK_BF16_TFLOPS if flops else PEAK_HBM_GBS)}
+        prune_us = sum(kernels[k]["ms_per_step"] for k in ("score", "select", "gather") if k in kernels) * 1e3
+    else:
+        prune_us = None
+    fa.fastav_profile_enable([])
+    ms, n, wk = fa.fastav_profile_collect(dominant)
+    achieved = wk / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = _cpu_baseline(w, host_threads)
+
+    line = {
+        "metric": "pruned prefill tokens/sec at 7B shape (unpruned rate, prune-step us and % roofline alongside)",
+        "value": tokens / s_pruned, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": s_pruned * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": m.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "layers": m.n_layers, "hidden": m.hidden, "q_heads": m.n_q_heads,
+                   "kv_heads": m.n_kv_heads, "head_dim": m.head_dim, "mlp": m.mlp_dim, "batch": len(w.samples),
+                   "tokens": tokens, "prunes": [[p.layer, "global" if p.kind == fi.GLOBAL else "fine", p.keep_ratio] for p in w.prunes],
+                   "kv_cache_written": True},
+        "unpruned_tokens_per_s": tokens / s_plain, "unpruned_ms_per_step": s_plain * 1e3,
+        "pruned_over_unpruned": s_plain / s_pruned,
+        "prune_steps_us_per_prefill": prune_us,
+        "roofline": {"kernel": "k_gemm_mfma<SwiGLU> (gate/up projection)", "bound": "mfma", "achieved": achieved,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launches": n, "avg_launch_us": 1e3 * ms / max(n, 1)},
+        "kernels": kernels,
+        "cpu_baseline": cpu,
+        "setup_s": setup_s,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

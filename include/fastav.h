@@ -198,6 +198,26 @@ fastav_status_t fastav_attention(const fastav_model_t* model, const void* q, int
                                  int64_t total_tokens, int32_t max_seqlen, float* last_logits, float* last_ml,
                                  void* stream);
 
+/* ---- measurement aid (benchmarks only) -------------------------------------------------------------- */
+
+/* Kernel kinds whose launches can be timed with HIP events on the launch stream.  "work" is the
+ * algorithmic work of a launch: flops for LINEAR_* (2 M N K; SwiGLU counts both matrices) and ATTENTION
+ * (2 Hq dh n(n+1) per sample, the causal half only), bytes for the others (what the step must read and
+ * write once). */
+typedef enum {
+  FASTAV_PROF_LINEAR_STORE = 0, FASTAV_PROF_LINEAR_RESADD = 1, FASTAV_PROF_LINEAR_SWIGLU = 2,
+  FASTAV_PROF_ATTENTION = 3, FASTAV_PROF_SCORE = 4, FASTAV_PROF_SELECT = 5, FASTAV_PROF_GATHER = 6,
+  FASTAV_PROF_RMSNORM = 7, FASTAV_PROF_ROPE = 8, FASTAV_PROF_OTHER = 9, FASTAV_PROF_KIND_COUNT = 10
+} fastav_prof_kind_t;
+
+/* Times every later launch whose kind bit (1u << kind) is set; 0 switches timing off (the default).
+ * While on, launches create and record HIP events, so do not enable it under graph capture. */
+fastav_status_t fastav_profile_enable(uint32_t kind_mask);
+/* Waits for the recorded launches, folds them into the running totals and returns the totals of one
+ * kind: summed event-to-event milliseconds, number of launches, summed work.  Outputs may be NULL. */
+fastav_status_t fastav_profile_collect(int32_t kind, double* total_ms, int64_t* launches, double* total_work);
+fastav_status_t fastav_profile_reset(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -85,7 +85,13 @@ _SIGS = {
                                 C.c_int32, C.c_int32, C.c_void_p]),
     "fastav_attention": (C.c_int, [C.POINTER(Model), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                                    C.c_int64, C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "fastav_profile_enable": (C.c_int, [C.c_uint32]),
+    "fastav_profile_collect": (C.c_int, [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
+    "fastav_profile_reset": (C.c_int, []),
 }
+
+PROF_KINDS = {"linear_store": 0, "linear_resadd": 1, "linear_swiglu": 2, "attention": 3, "score": 4, "select": 5,
+              "gather": 6, "rmsnorm": 7, "rope": 8, "other": 9}
 
 
 def lib() -> C.CDLL:
@@ -334,3 +340,21 @@ def fastav_attention(model: Model, q: torch.Tensor, k: torch.Tensor, v: torch.Te
     _check(lib().fastav_attention(C.byref(model), q.data_ptr(), q.stride(0), k.data_ptr(), v.data_ptr(), k.stride(0),
                                   o.data_ptr(), o.stride(0), cu_seqlens_dev.data_ptr(), B, T, max_seqlen, _ptr(ll), _ptr(ml), _stream()))
     return (o, ll, ml) if want_last else o
+
+
+def fastav_profile_enable(kinds: Sequence[str]) -> None:
+    mask = 0
+    for k in kinds:
+        mask |= 1 << PROF_KINDS[k]
+    _check(lib().fastav_profile_enable(mask))
+
+
+def fastav_profile_collect(kind: str):
+    """-> (total_ms, launches, total_work) accumulated for one kernel kind since the last reset."""
+    ms, n, w = C.c_double(), C.c_int64(), C.c_double()
+    _check(lib().fastav_profile_collect(PROF_KINDS[kind], C.byref(ms), C.byref(n), C.byref(w)))
+    return ms.value, n.value, w.value
+
+
+def fastav_profile_reset() -> None:
+    _check(lib().fastav_profile_reset())

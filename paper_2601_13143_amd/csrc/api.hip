@@ -52,6 +52,9 @@ static fastav_status_t linear_segments(const void* a, const void* const* w_seg, 
   int n = 0;
   for (int i = 0; i < n_seg; ++i) n += seg_rows[i];
   if (m == 0 || n == 0) return FASTAV_OK;
+  const int kind = epilogue == FASTAV_EPI_STORE ? FASTAV_PROF_LINEAR_STORE
+                   : epilogue == FASTAV_EPI_RESADD ? FASTAV_PROF_LINEAR_RESADD : FASTAV_PROF_LINEAR_SWIGLU;
+  ProfScope prof(kind, 2.0 * (double)m * n * k * (epilogue == FASTAV_EPI_SWIGLU ? 2.0 : 1.0), s);
   bool ok = mfma_linear_supported(m, n, k, epilogue, dtype);
   for (int i = 0; i < n_seg && ok; ++i) ok = mfma_linear_supported(m, seg_rows[i], k, epilogue, dtype);
   if (ok) return launch_linear_mfma(a, w_seg, seg_rows, n_seg, w2, c, ldc, m, n, k, epilogue, s);
@@ -76,7 +79,8 @@ fastav_status_t launch_linear(const void* a, const void* w, const void* w2, void
 fastav_status_t launch_attention(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
                                  void* o, int64_t o_stride, const int32_t* cu, int batch, int64_t T, int max_seqlen,
                                  int Hq, int Hkv, int dh, float* last_logits, float* last_ml, int dtype,
-                                 hipStream_t s) {
+                                 double flops_hint, hipStream_t s) {
+  ProfScope prof(FASTAV_PROF_ATTENTION, flops_hint, s);
   if (mfma_attention_supported(dh, dtype, q_stride, kv_stride, o_stride))
     return launch_attention_mfma(q, q_stride, k, v, kv_stride, o, o_stride, cu, batch, T, max_seqlen, Hq, Hkv, dh,
                                  last_logits, last_ml, s);
@@ -331,6 +335,12 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
     maxlen_stage[i] = mx;
   }
 
+  // causal attention work per stage: 2 Hq dh n (n + 1) per sample
+  std::vector<double> attn_flops(n_stages, 0.0);
+  for (int i = 0; i < n_stages; ++i)
+    for (int b = 0; b < B; ++b)
+      attn_flops[i] += 2.0 * m.n_q_heads * m.head_dim * (double)lens[i][b] * ((double)lens[i][b] + 1.0);
+
   hipStream_t s = (hipStream_t)stream;
   char* base = (char*)workspace;
   float* resid[2] = {(float*)(base + ws.resid[0]), (float*)(base + ws.resid[1])};
@@ -366,7 +376,8 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
       const int32_t* cu_in = cu_dev + (size_t)stage * (B + 1);
       const int32_t* cu_nx = cu_dev + (size_t)(stage + 1) * (B + 1);
       int32_t* kidx = (out->prune_keep_idx_out && out->prune_keep_idx_out[pi]) ? out->prune_keep_idx_out[pi] : keep_idx_ws;
-      FASTAV_TRY(launch_select(nullptr, prot[cur], cu_in, cu_nx, B, maxlen_stage[stage], kidx, s));
+      FASTAV_TRY(launch_select(nullptr, prot[cur], cu_in, cu_nx, B, maxlen_stage[stage], kidx,
+                               1.0 * T_stage[stage] + 4.0 * T_stage[stage + 1], s));
       GatherTensor g[3] = {{resid[cur], resid[cur ^ 1], (int64_t)m.hidden * 4, 0},
                            {pos[cur], pos[cur ^ 1], 4, 0},
                            {prot[cur], prot[cur ^ 1], 1, 0}};
@@ -389,7 +400,7 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
     const char* vptr = qkv + (size_t)(qd + kd) * es;
     FASTAV_TRY(launch_attention(qkv, qkv_stride, kptr, vptr, qkv_stride, attn[0], qd, cu_l, B, Tl, maxlen_stage[stage],
                                 m.n_q_heads, m.n_kv_heads, m.head_dim, side ? logits : nullptr, side ? ml : nullptr,
-                                m.dtype, s));
+                                m.dtype, attn_flops[stage], s));
     void* attn_cur = attn[0];
     void* const k_out = out->kv_out ? out->kv_out[2 * l] : nullptr;
     void* const v_out = out->kv_out ? out->kv_out[2 * l + 1] : nullptr;
@@ -405,7 +416,8 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
       }
       const int32_t* cu_nx = cu_dev + (size_t)(stage + 1) * (B + 1);
       int32_t* kidx = (out->prune_keep_idx_out && out->prune_keep_idx_out[pi]) ? out->prune_keep_idx_out[pi] : keep_idx_ws;
-      FASTAV_TRY(launch_select(sc, prot[cur], cu_l, cu_nx, B, maxlen_stage[stage], kidx, s));
+      FASTAV_TRY(launch_select(sc, prot[cur], cu_l, cu_nx, B, maxlen_stage[stage], kidx,
+                               5.0 * Tl + 4.0 * T_stage[stage + 1], s));
       GatherTensor g[6] = {{resid[cur], resid[cur ^ 1], (int64_t)m.hidden * 4, 0},
                            {attn[0], attn[1], (int64_t)qd * (int64_t)es, 0},
                            {pos[cur], pos[cur ^ 1], 4, 0},
@@ -503,7 +515,8 @@ fastav_status_t fastav_select_gather(const float* scores, const uint8_t* protect
   int32_t* cu_dev = (int32_t*)workspace;
   FASTAV_TRY(upload_small(cu_dev, cu_seqlens, (size_t)(batch + 1) * 4, s));
   FASTAV_TRY(upload_small(cu_seqlens_out, cu_out.data(), (size_t)(batch + 1) * 4, s));
-  FASTAV_TRY(launch_select(scores, protected_mask, cu_dev, cu_seqlens_out, batch, max_len, keep_idx_out, s));
+  FASTAV_TRY(launch_select(scores, protected_mask, cu_dev, cu_seqlens_out, batch, max_len, keep_idx_out,
+                           (scores ? 5.0 : 1.0) * cu_seqlens[batch] + 4.0 * cu_out[batch], s));
   return launch_gather(g, n_tensors, keep_idx_out, cu_out[batch], s);
 }
 
@@ -545,7 +558,7 @@ fastav_status_t fastav_attention(const fastav_model_t* model, const void* q, int
   if (q_row_stride < qd || o_row_stride < qd || kv_row_stride < kd) return fail(FASTAV_EINVAL, "row strides are smaller than a row");
   return launch_attention(q, q_row_stride, k, v, kv_row_stride, o, o_row_stride, cu_seqlens_dev, batch, total_tokens,
                           max_seqlen, model->n_q_heads, model->n_kv_heads, model->head_dim, last_logits, last_ml,
-                          model->dtype, (hipStream_t)stream);
+                          model->dtype, 0.0, (hipStream_t)stream);
 }
 
 }  // extern "C"

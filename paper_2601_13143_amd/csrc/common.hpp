@@ -43,6 +43,18 @@ inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
 fastav_status_t fail(fastav_status_t st, const char* fmt, ...);
 fastav_status_t check_launch(const char* what);
 
+// Times the launches issued while it is alive when profiling of `kind` is on (see fastav_profile_enable).
+class ProfScope {
+ public:
+  ProfScope(int kind, double work, hipStream_t s);
+  ~ProfScope();
+  ProfScope(const ProfScope&) = delete;
+  ProfScope& operator=(const ProfScope&) = delete;
+ private:
+  void* rec_;
+  hipStream_t stream_;
+};
+
 // ---- launchers (every pointer is a device pointer unless named host_*) ------------------------------
 
 // Copies a small host array into device memory through kernel arguments (no memcpy, no pinned memory,
@@ -64,7 +76,7 @@ fastav_status_t launch_linear(const void* a, const void* w, const void* w2, void
 fastav_status_t launch_attention(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
                                  void* o, int64_t o_stride, const int32_t* cu, int batch, int64_t T, int max_seqlen,
                                  int Hq, int Hkv, int dh, float* last_logits, float* last_ml, int dtype,
-                                 hipStream_t s);
+                                 double flops_hint, hipStream_t s);
 
 // Eq. 4.  logits [n_last, Hq, T] fp32, ml [batch, n_last, Hq, 2] fp32.
 size_t score_partials_bytes(int Hq, int64_t T, int batch, int n_last);
@@ -78,7 +90,7 @@ fastav_status_t launch_score_finalize(const float* logits, const float* ml, cons
 
 // Selection + compaction.  keep_idx/cu_out as in fastav_select_gather; scores == nullptr -> positional.
 fastav_status_t launch_select(const float* scores, const uint8_t* prot, const int32_t* cu, const int32_t* cu_out,
-                              int batch, int max_seqlen, int32_t* keep_idx, hipStream_t s);
+                              int batch, int max_seqlen, int32_t* keep_idx, double bytes_hint, hipStream_t s);
 // src_stride_bytes == 0 means rows are packed (stride = row_bytes); row_bytes == 0 skips the tensor.
 struct GatherTensor { const void* src; void* dst; int64_t row_bytes; int64_t src_stride_bytes; };
 fastav_status_t launch_gather(const GatherTensor* t, int n_tensors, const int32_t* keep_idx, int64_t n_rows,

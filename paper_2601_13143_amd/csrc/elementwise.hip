@@ -129,6 +129,7 @@ __global__ __launch_bounds__(256) void k_rmsnorm(const float* __restrict__ x, co
 fastav_status_t launch_rmsnorm(const float* x, const void* g, void* y, int64_t rows, int d, float eps, int dtype,
                                hipStream_t s) {
   if (rows == 0) return FASTAV_OK;
+  ProfScope prof(FASTAV_PROF_RMSNORM, (double)rows * d * (4.0 + (dtype == FASTAV_BF16 ? 2.0 : 4.0)), s);
   if (dtype == FASTAV_BF16)
     hipLaunchKernelGGL(k_rmsnorm<bf16_t>, dim3((unsigned)rows), dim3(256), 0, s, x, (const bf16_t*)g, (bf16_t*)y, d, eps);
   else
@@ -165,6 +166,7 @@ __global__ void k_rope(T* __restrict__ x, int64_t row_stride, const int32_t* __r
 fastav_status_t launch_rope(void* x, int64_t row_stride, const int32_t* pos, int64_t rows, int n_heads, int head_dim,
                             float base, int dtype, hipStream_t s) {
   if (rows == 0 || n_heads == 0) return FASTAV_OK;
+  ProfScope prof(FASTAV_PROF_ROPE, 2.0 * rows * n_heads * head_dim * (dtype == FASTAV_BF16 ? 2.0 : 4.0), s);
   const int half = head_dim / 2;
   int hpb = 256 / half; if (hpb < 1) hpb = 1; if (hpb > n_heads) hpb = n_heads;
   const double e = -log2((double)base) * 2.0 / (double)head_dim;

@@ -191,6 +191,7 @@ fastav_status_t launch_score_logits(const void* q, int64_t q_stride, const void*
                                     const int32_t* cu, int batch, int64_t T, int max_seqlen, int Hq, int Hkv, int dh,
                                     int n_last, float* logits, float* partials, int dtype, hipStream_t s) {
   if (batch == 0 || max_seqlen == 0) return FASTAV_OK;
+  ProfScope prof(FASTAV_PROF_SCORE, (double)T * Hkv * dh * (dtype == FASTAV_BF16 ? 2.0 : 4.0) + 4.0 * n_last * Hq * T, s);
   const int64_t ncm = chunk_slots(T, batch);
   dim3 grid((unsigned)ceil_div(max_seqlen, kScoreChunk), (unsigned)batch);
   const size_t shmem = (size_t)Hq * (dh + kScoreChunk) * sizeof(float);
@@ -214,6 +215,7 @@ fastav_status_t launch_score_finalize(const float* logits, const float* ml, cons
                                       int batch, int64_t T, int max_seqlen, int Hq, int n_last, float* scores,
                                       hipStream_t s) {
   if (batch == 0 || max_seqlen == 0) return FASTAV_OK;
+  ProfScope prof(FASTAV_PROF_SCORE, 4.0 * n_last * Hq * T + 4.0 * T, s);
   dim3 grid((unsigned)ceil_div(max_seqlen, 256), (unsigned)batch);
   const size_t shmem = (size_t)n_last * Hq * 2 * sizeof(float);
   hipLaunchKernelGGL(k_score_finalize, grid, dim3(256), shmem, s, logits, ml, partials, chunk_slots(T, batch), cu, Hq,

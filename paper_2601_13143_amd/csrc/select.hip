@@ -193,8 +193,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
 }
 
 fastav_status_t launch_select(const float* scores, const uint8_t* prot, const int32_t* cu, const int32_t* cu_out,
-                              int batch, int max_seqlen, int32_t* keep_idx, hipStream_t s) {
+                              int batch, int max_seqlen, int32_t* keep_idx, double bytes_hint, hipStream_t s) {
   if (batch == 0 || max_seqlen == 0) return FASTAV_OK;
+  ProfScope prof(FASTAV_PROF_SELECT, bytes_hint, s);
   if (max_seqlen <= kSelLdsKeys) {
     const size_t shmem = (size_t)max_seqlen * sizeof(uint32_t);
     if (shmem > 32 * 1024) {   // beyond the default dynamic-LDS limit: opt in (per device, so set on every such launch)
@@ -252,6 +253,9 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs a, const int32_t* __r
 static fastav_status_t gather_impl(const GatherArgs& a, int n_tensors, const int32_t* keep_idx, int64_t n_rows,
                                    hipStream_t s) {
   if (n_rows == 0 || n_tensors == 0) return FASTAV_OK;
+  double bytes = keep_idx ? 4.0 * n_rows : 0.0;
+  for (int i = 0; i < n_tensors; ++i) bytes += 2.0 * a.row_bytes[i] * n_rows;
+  ProfScope prof(FASTAV_PROF_GATHER, bytes, s);
   // aim at >= 4 KB of payload per workgroup, judged by the widest tensor
   int64_t widest = 1;
   for (int i = 0; i < n_tensors; ++i) widest = a.row_bytes[i] > widest ? a.row_bytes[i] : widest;
