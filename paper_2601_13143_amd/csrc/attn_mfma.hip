@@ -2,17 +2,23 @@
 // with the last-query logits of Eq. 4 as a side output.
 //
 // One workgroup = 128 query rows of one head of one sample; each of its 4 waves owns 32 rows.  K/V tiles
-// of 64 keys are staged in LDS (K row-major with XOR-swizzled 16-byte chunks; V transposed to [d][key] so
-// that the P V product reads key-contiguous operands).  The products are formed transposed,
+// of 64 keys are fetched with 16-byte loads into registers one tile ahead of the math and parked in one
+// of two LDS stages, both row-major [key][d]: K with its 16-byte chunks XOR-swizzled by the key (the MFMA
+// operand read is 32 keys x one chunk), V with its 32-byte granules XOR-swizzled by key mod 4 (the
+// transposing LDS read below touches 4 keys x 32 bytes per 16 lanes).  The products are formed transposed,
 //     S^T = K Q^T   and   O^T = V^T P^T   (v_mfma_f32_32x32x16_bf16),
 // so that in every accumulator a lane's column is ONE query row: the running max / sum of the softmax
-// recurrence are per-lane scalars (one cross-lane exchange per tile, with the lane 32 away that holds the
-// other half of the keys), the rescale of O^T is a per-lane multiply, and exp2(S^T - m) converts in place
-// into the B operand of the second product (the key order inside an MFMA k-step is whatever order the
-// accumulator holds; V^T is read in the same order, a sum does not care).
+// recurrence are per-lane scalars (one exchange per tile with the lane 32 away, which holds the other half
+// of the keys), the rescale of O^T is a per-lane multiply, and exp2(S^T - m) converts in place into the B
+// operand of the second product.  V^T operands come straight out of the row-major V tile through
+// ds_read_b64_tr_b16: per 16 lanes it reads 4 keys x 16 dims and hands lane i the 4 keys of dim i.  The
+// key order inside an MFMA k-step is the order the S^T accumulator holds them in; a sum does not care.
 //
 // The lane whose query is the last row of a sample also writes that row's scaled logits for every key
 // and its final (max, sum): the fine-prune score is finalised from those without a second pass over K.
+//
+// Workgroup ids are re-dealt so that each XCD owns a contiguous run of (head, tile) pairs: the query heads
+// that share a KV head then share an L2.  Inside a head the longest (last) query tiles run first.
 #include "common.hpp"
 
 namespace fastav {
@@ -21,25 +27,34 @@ struct AttnArgs {
   const bf16_t* q; const bf16_t* k; const bf16_t* v; bf16_t* o;
   int64_t qs, kvs, os;                 // row strides in elements
   const int32_t* cu;
-  int Hq, Hkv, n_qtiles;
+  int Hq, Hkv, n_qtiles, n_blocks;
   float scale, scale_log2;             // 1/sqrt(dh) and the same times log2(e)
   int64_t T;
   float* last_logits; float* last_ml;
 };
 
+typedef __attribute__((address_space(3))) bf16x4_t* lds_bf16x4_ptr;
+
 template <int DH>
-__global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a) {
+__global__ __launch_bounds__(256, 2) void k_attn_mfma(AttnArgs a) {
   constexpr int BQ = 128, BKV = 64;
-  constexpr int DCH = DH / 8;                       // 16-byte chunks per K row
-  constexpr int VP = BKV + 4;                       // pitch (elements) of a V^T row: 8-byte aligned, staggers banks
+  constexpr int DCH = DH / 8;                       // 16-byte chunks per row
   constexpr int NS = DH / 16;                       // MFMA k-steps over the head dimension
   constexpr int NDB = DH / 32;                      // 32-row blocks of O^T
-  __shared__ bf16x8_t Ks[BKV * DCH];
-  __shared__ __attribute__((aligned(16))) bf16_t Vt[DH * VP];
+  constexpr int NLD = BKV * DCH / 256;              // 16-byte chunks per thread per tile (K and V each)
+  __shared__ bf16x8_t Ks[2][BKV * DCH];
+  __shared__ bf16x8_t Vs[2][BKV * DCH];
 
-  const int b = blockIdx.z, h = blockIdx.y;
+  int v = blockIdx.x;
+  {
+    const int per = a.n_blocks / 8, rem = a.n_blocks % 8, xcd = v % 8, idx = v / 8;
+    v = xcd * per + (xcd < rem ? xcd : rem) + idx;
+  }
+  const int qt = a.n_qtiles - 1 - v % a.n_qtiles;                 // longest tiles first
+  const int h = (v / a.n_qtiles) % a.Hq;
+  const int b = v / (a.n_qtiles * a.Hq);
   const int row0 = a.cu[b], n = a.cu[b + 1] - row0;
-  const int q0 = (a.n_qtiles - 1 - (int)blockIdx.x) * BQ;        // longest tiles first
+  const int q0 = qt * BQ;
   if (q0 >= n) return;
   const int g = h / (a.Hq / a.Hkv);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -62,97 +77,148 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a) {
     for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
   float m = -INFINITY, l = 0.f;
   const bool emit = (a.last_logits != nullptr) && (qi == n - 1);
+  const bool emit_wave = __ballot(emit) != 0;                    // wave-uniform: some lane owns the sample's last row
 
   const int kv_end = (q0 + BQ < n) ? q0 + BQ : n;                // keys this workgroup can see
   const int n_tiles = (kv_end + BKV - 1) / BKV;
   const bf16_t* kbase = a.k + (int64_t)row0 * a.kvs + g * DH;
   const bf16_t* vbase = a.v + (int64_t)row0 * a.kvs + g * DH;
 
-  for (int t = 0; t < n_tiles; ++t) {
-    const int j0 = t * BKV;
-    __syncthreads();
+  // this thread's share of a tile: chunks idx = tid + 256 i -> (key, c)
+  bf16x8_t kreg[NLD], vreg[NLD];
+  auto fetch = [&](int j0) {
 #pragma unroll
-    for (int i = 0; i < BKV * DCH / 256; ++i) {
+    for (int i = 0; i < NLD; ++i) {
       const int idx = tid + 256 * i;
       const int key = idx / DCH, c = idx % DCH;
-      const int jr = (j0 + key < n) ? j0 + key : n - 1;
-      const bf16x8_t kv = *(const bf16x8_t*)(kbase + (int64_t)jr * a.kvs + c * 8);
-      Ks[key * DCH + (c ^ (key & 7))] = kv;
+      const bool ok = j0 + key < n;
+      const int jr = ok ? j0 + key : n - 1;
+      kreg[i] = *(const bf16x8_t*)(kbase + (int64_t)jr * a.kvs + c * 8);
       bf16x8_t vv = *(const bf16x8_t*)(vbase + (int64_t)jr * a.kvs + c * 8);
-      if (j0 + key >= n) {
+      if (!ok) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) vv[e] = (bf16_t)0.f;          // masked keys must not inject NaN/Inf through 0 * x
       }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) Vt[(c * 8 + e) * VP + key] = vv[e];
+      vreg[i] = vv;
     }
-    __syncthreads();
-    if (!wave_live || j0 > qw0 + 31) continue;                    // nothing visible to this wave in this tile
-
-    // ---- S^T = K Q^T : s[kb][r] is (key j0 + 32kb + (r/4)*8 + hf*4 + r%4, query qi)
-    f32x16_t s[2];
+  };
+  auto park = [&](int st) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-      const int key = kb * 32 + l32;
-#pragma unroll
-      for (int st = 0; st < NS; ++st) {
-        const bf16x8_t kf = Ks[key * DCH + ((2 * st + hf) ^ (key & 7))];
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], s[kb], 0, 0, 0);
-      }
+    for (int i = 0; i < NLD; ++i) {
+      const int idx = tid + 256 * i;
+      const int key = idx / DCH, c = idx % DCH;
+      Ks[st][key * DCH + (c ^ (key & 7))] = kreg[i];
+      Vs[st][key * DCH + (c ^ ((key & 3) << 1))] = vreg[i];
     }
-    const bool need_mask = (j0 + BKV - 1 > qw0) || (j0 + BKV > n);
-    float mx = -INFINITY;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = j0 + kb * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
-        const float raw = s[kb][r];
-        float val = raw * a.scale_log2;
-        const bool vis = !need_mask || (key <= qi && key < n);
-        if (!vis) val = -INFINITY;
-        if (emit && key <= qi) a.last_logits[(int64_t)h * a.T + row0 + key] = raw * a.scale;
-        s[kb][r] = val;
-        mx = fmaxf(mx, val);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-    const float m_new = fmaxf(m, mx);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = exp2f(m - m_use);
-    l *= alpha;
-#pragma unroll
-    for (int d = 0; d < NDB; ++d)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
-    bf16x8_t pb[2][2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = exp2f(s[kb][r] - m_use);
-        l += p;
-        pb[kb][r >> 3][r & 7] = (bf16_t)p;
-      }
-    m = m_new;
+  };
+  fetch(0);
+  park(0);
+  __syncthreads();
 
-    // ---- O^T += V^T P^T : k-step (kb, sp) slot e holds key 32kb + 16sp + (e/4)*8 + hf*4 + e%4
+  // byte offset inside a V tile of this lane's transposing read for (d-block 0, key 0): the read for
+  // (db, key base kb) adds db*64 bytes (4 chunks, swizzle-invariant since it only flips chunk bits 1..2
+  // and db moves bits 2..3 ... handled below by recomputing the chunk) and kb rows.
+  const int tr_krow = (lane & 15) >> 2;                          // which of the 4 keys this lane addresses
+  const int tr_c0 = ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);   // chunk inside the 32-dim block
+  const int tr_e = (lane & 1) * 4;                               // element inside the chunk
+
+  for (int t = 0; t < n_tiles; ++t) {
+    const int j0 = t * BKV;
+    const int st = t & 1;
+    if (t + 1 < n_tiles) fetch(j0 + BKV);
+
+    if (wave_live && j0 <= qw0 + 31) {                            // else nothing visible to this wave in this tile
+      // ---- S^T = K Q^T : s[kb][r] is (key j0 + 32kb + (r/4)*8 + hf*4 + r%4, query qi)
+      f32x16_t s[2];
 #pragma unroll
-    for (int d = 0; d < NDB; ++d) {
-      const bf16_t* vrow = Vt + (d * 32 + l32) * VP + hf * 4;
+      for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+      }
+#pragma unroll
+      for (int sI = 0; sI < NS; ++sI) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          const int key = kb * 32 + l32;
+          const bf16x8_t kf = Ks[st][key * DCH + ((2 * sI + hf) ^ (key & 7))];
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[sI], s[kb], 0, 0, 0);
+        }
+      }
+      if (emit_wave) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = j0 + kb * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
+            if (emit && key <= qi) a.last_logits[(int64_t)h * a.T + row0 + key] = s[kb][r] * a.scale;
+          }
+      }
+      float mx = -INFINITY;
+      if ((j0 + BKV - 1 > qw0) || (j0 + BKV > n)) {                // diagonal or ragged tile: mask (wave-uniform test)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = j0 + kb * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
+            float val = s[kb][r] * a.scale_log2;
+            if (!(key <= qi && key < n)) val = -INFINITY;
+            s[kb][r] = val;
+            mx = fmaxf(mx, val);
+          }
+      } else {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float val = s[kb][r] * a.scale_log2;
+            s[kb][r] = val;
+            mx = fmaxf(mx, val);
+          }
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+      const float m_new = fmaxf(m, mx);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+      l *= alpha;
+#pragma unroll
+      for (int d = 0; d < NDB; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+      bf16x8_t pb[2][2];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float p = __builtin_amdgcn_exp2f(s[kb][r] - m_use);
+          l += p;
+          pb[kb][r >> 3][r & 7] = (bf16_t)p;
+        }
+      m = m_new;
+
+      // ---- O^T += V^T P^T : k-step (kb, sp), slot e holds key 32kb + 16sp + (e/4)*8 + hf*4 + e%4
+      const bf16_t* vtile = (const bf16_t*)Vs[st];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int sp = 0; sp < 2; ++sp) {
-          const bf16x4_t v0 = *(const bf16x4_t*)(vrow + kb * 32 + sp * 16);
-          const bf16x4_t v1 = *(const bf16x4_t*)(vrow + kb * 32 + sp * 16 + 8);
-          bf16x8_t vf;
-          vf[0] = v0[0]; vf[1] = v0[1]; vf[2] = v0[2]; vf[3] = v0[3];
-          vf[4] = v1[0]; vf[5] = v1[1]; vf[6] = v1[2]; vf[7] = v1[3];
-          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[kb][sp], o[d], 0, 0, 0);
+#pragma unroll
+          for (int d = 0; d < NDB; ++d) {
+            bf16x8_t vf;
+#pragma unroll
+            for (int r2 = 0; r2 < 2; ++r2) {
+              const int key = kb * 32 + sp * 16 + r2 * 8 + hf * 4 + tr_krow;      // key & 3 == tr_krow
+              const int c = (d * 4 + tr_c0) ^ (tr_krow << 1);
+              const bf16x4_t got = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                  (lds_bf16x4_ptr)(vtile + key * DH + c * 8 + tr_e));
+              vf[4 * r2 + 0] = got[0]; vf[4 * r2 + 1] = got[1]; vf[4 * r2 + 2] = got[2]; vf[4 * r2 + 3] = got[3];
+            }
+            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[kb][sp], o[d], 0, 0, 0);
+          }
         }
     }
+
+    if (t + 1 < n_tiles) park(st ^ 1);
+    __syncthreads();
   }
 
   // ---- normalise and store.  o[d][r] is (dim 32d + (r/4)*8 + hf*4 + r%4, query qi).
@@ -191,12 +257,14 @@ fastav_status_t launch_attention_mfma(const void* q, int64_t q_stride, const voi
   a.q = (const bf16_t*)q; a.k = (const bf16_t*)k; a.v = (const bf16_t*)v; a.o = (bf16_t*)o;
   a.qs = q_stride; a.kvs = kv_stride; a.os = o_stride; a.cu = cu; a.Hq = Hq; a.Hkv = Hkv;
   a.n_qtiles = (max_seqlen + 127) / 128;
+  const int64_t blocks = (int64_t)a.n_qtiles * Hq * batch;
+  if (blocks > 0x7FFFFFFF) return fail(FASTAV_EUNSUPPORTED, "attention: too many workgroups");
+  a.n_blocks = (int)blocks;
   a.scale = 1.0f / sqrtf((float)dh);
   a.scale_log2 = a.scale * 1.4426950408889634f;
   a.T = T; a.last_logits = last_logits; a.last_ml = last_ml;
-  dim3 grid((unsigned)a.n_qtiles, (unsigned)Hq, (unsigned)batch);
-  if (dh == 128) hipLaunchKernelGGL(k_attn_mfma<128>, grid, dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(k_attn_mfma<64>, grid, dim3(256), 0, s, a);
+  if (dh == 128) hipLaunchKernelGGL(k_attn_mfma<128>, dim3((unsigned)blocks), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(k_attn_mfma<64>, dim3((unsigned)blocks), dim3(256), 0, s, a);
   return check_launch("attention_mfma");
 }
 
