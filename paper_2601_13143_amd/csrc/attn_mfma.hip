@@ -3,9 +3,9 @@
 //
 // One workgroup = 128 query rows of one head of one sample; each of its 4 waves owns 32 rows.  K/V tiles
 // of 64 keys are fetched with 16-byte loads into registers one tile ahead of the math and parked in one
-// of two LDS stages, both row-major [key][d]: K with its 16-byte chunks XOR-swizzled by the key (the MFMA
-// operand read is 32 keys x one chunk), V with its 32-byte granules XOR-swizzled by key mod 4 (the
-// transposing LDS read below touches 4 keys x 32 bytes per 16 lanes).  The products are formed transposed,
+// of two LDS stages, both row-major [key][d] and XOR-swizzled so that the operand reads spread over all 64
+// LDS banks (K: 32 keys x one 16-byte chunk per MFMA operand; V: 4 keys x 32 bytes per 16 lanes of the
+// transposing read below).  The products are formed transposed,
 //     S^T = K Q^T   and   O^T = V^T P^T   (v_mfma_f32_32x32x16_bf16),
 // so that in every accumulator a lane's column is ONE query row: the running max / sum of the softmax
 // recurrence are per-lane scalars (one exchange per tile with the lane 32 away, which holds the other half
@@ -42,6 +42,13 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(AttnArgs a) {
   constexpr int NS = DH / 16;                       // MFMA k-steps over the head dimension
   constexpr int NDB = DH / 32;                      // 32-row blocks of O^T
   constexpr int NLD = BKV * DCH / 256;              // 16-byte chunks per thread per tile (K and V each)
+  // Swizzles (64 LDS banks of 4 bytes; a 16-byte access is served 16 lanes at a time, an 8-byte access 32):
+  //   K: 16 consecutive keys reading the same logical chunk must hit 16 distinct 16-byte slots of the 256-byte
+  //      bank window -> XOR the chunk with the key (rows of 256 B) or with key/2 (rows of 128 B).
+  //   V: a transposing read touches, per 32 lanes, 4 keys x two 32-byte granules -> XOR the granule so the
+  //      eight pieces fall in eight distinct 32-byte slots.
+  auto kswz = [](int key, int c) { return DH == 128 ? (c ^ (key & 15)) : (c ^ ((key >> 1) & 7)); };
+  auto vswz = [](int key, int c) { return DH == 128 ? (c ^ ((key & 3) << 2)) : (c ^ ((key & 2) << 1)); };
   __shared__ bf16x8_t Ks[2][BKV * DCH];
   __shared__ bf16x8_t Vs[2][BKV * DCH];
 
@@ -107,17 +114,15 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(AttnArgs a) {
     for (int i = 0; i < NLD; ++i) {
       const int idx = tid + 256 * i;
       const int key = idx / DCH, c = idx % DCH;
-      Ks[st][key * DCH + (c ^ (key & 7))] = kreg[i];
-      Vs[st][key * DCH + (c ^ ((key & 3) << 1))] = vreg[i];
+      Ks[st][key * DCH + kswz(key, c)] = kreg[i];
+      Vs[st][key * DCH + vswz(key, c)] = vreg[i];
     }
   };
   fetch(0);
   park(0);
   __syncthreads();
 
-  // byte offset inside a V tile of this lane's transposing read for (d-block 0, key 0): the read for
-  // (db, key base kb) adds db*64 bytes (4 chunks, swizzle-invariant since it only flips chunk bits 1..2
-  // and db moves bits 2..3 ... handled below by recomputing the chunk) and kb rows.
+  // this lane's part of a transposing V read: 16 lanes cover 4 keys x 16 dims (two chunks)
   const int tr_krow = (lane & 15) >> 2;                          // which of the 4 keys this lane addresses
   const int tr_c0 = ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);   // chunk inside the 32-dim block
   const int tr_e = (lane & 1) * 4;                               // element inside the chunk
@@ -140,7 +145,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(AttnArgs a) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
           const int key = kb * 32 + l32;
-          const bf16x8_t kf = Ks[st][key * DCH + ((2 * sI + hf) ^ (key & 7))];
+          const bf16x8_t kf = Ks[st][key * DCH + kswz(key, 2 * sI + hf)];
           s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[sI], s[kb], 0, 0, 0);
         }
       }
@@ -207,7 +212,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(AttnArgs a) {
 #pragma unroll
             for (int r2 = 0; r2 < 2; ++r2) {
               const int key = kb * 32 + sp * 16 + r2 * 8 + hf * 4 + tr_krow;      // key & 3 == tr_krow
-              const int c = (d * 4 + tr_c0) ^ (tr_krow << 1);
+              const int c = vswz(tr_krow, d * 4 + tr_c0);
               const bf16x4_t got = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
                   (lds_bf16x4_ptr)(vtile + key * DH + c * 8 + tr_e));
               vf[4 * r2 + 0] = got[0]; vf[4 * r2 + 1] = got[1]; vf[4 * r2 + 2] = got[2]; vf[4 * r2 + 3] = got[3];
