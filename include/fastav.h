@@ -184,8 +184,13 @@ fastav_status_t fastav_rope(void* x, int64_t row_stride, const int32_t* pos, int
  *   FASTAV_EPI_RESADD  : R[M,N] (fp32)  += A W^T                       (residual update, C = R)
  *   FASTAV_EPI_SWIGLU  : C[M,N] (dtype)  = silu(A W^T) * (A W2^T)      (W2 [N, K] is the "up" matrix) */
 typedef enum { FASTAV_EPI_STORE = 0, FASTAV_EPI_RESADD = 1, FASTAV_EPI_SWIGLU = 2 } fastav_epilogue_t;
+/* workspace (optional, dev, 256-byte aligned, fastav_linear_workspace_bytes() bytes): lets a residual update
+ * with few output tiles split K across more compute units; the partial tiles are summed in a fixed order, so
+ * results do not depend on scheduling.  NULL is allowed (no splitting). */
+size_t fastav_linear_workspace_bytes(void);
 fastav_status_t fastav_linear(const void* a, const void* w, const void* w2, void* c, int64_t m, int32_t n,
-                              int32_t k, int32_t epilogue, int32_t dtype, void* stream);
+                              int32_t k, int32_t epilogue, int32_t dtype, void* workspace, size_t workspace_bytes,
+                              void* stream);
 
 /* Causal grouped-query attention over a packed batch: o = softmax(q k^T / sqrt(head_dim) + causal) v.
  * q,k,v,o are dev pointers in dtype with row strides in elements (q and o hold Hq heads, k and v Hkv).

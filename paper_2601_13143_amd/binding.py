@@ -81,8 +81,9 @@ _SIGS = {
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "fastav_rmsnorm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_float, C.c_int32, C.c_void_p]),
     "fastav_rope": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_void_p]),
+    "fastav_linear_workspace_bytes": (C.c_size_t, []),
     "fastav_linear": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
-                                C.c_int32, C.c_int32, C.c_void_p]),
+                                C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
     "fastav_attention": (C.c_int, [C.POINTER(Model), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                                    C.c_int64, C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "fastav_profile_enable": (C.c_int, [C.c_uint32]),
@@ -315,15 +316,25 @@ def fastav_rope(x: torch.Tensor, pos: torch.Tensor, n_heads: int, head_dim: int,
     return x
 
 
+_linear_ws: Dict = {}
+
+
 def fastav_linear(a: torch.Tensor, w: torch.Tensor, epilogue: int = EPI_STORE, w2: Optional[torch.Tensor] = None,
-                  c: Optional[torch.Tensor] = None) -> torch.Tensor:
+                  c: Optional[torch.Tensor] = None, use_workspace: bool = True) -> torch.Tensor:
     m, k = a.shape
     n = w.shape[0]
     if c is None:
         if epilogue == EPI_RESADD:
             raise ValueError("the residual epilogue updates c in place: pass it")
         c = torch.empty((m, n), dtype=a.dtype, device=a.device)
-    _check(lib().fastav_linear(a.data_ptr(), w.data_ptr(), _ptr(w2), c.data_ptr(), m, n, k, epilogue, _dtype_code(a), _stream()))
+    ws = None
+    if use_workspace and epilogue == EPI_RESADD and a.dtype == torch.bfloat16:
+        key = a.device.index
+        if key not in _linear_ws:
+            _linear_ws[key] = torch.empty(lib().fastav_linear_workspace_bytes(), dtype=torch.uint8, device=a.device)
+        ws = _linear_ws[key]
+    _check(lib().fastav_linear(a.data_ptr(), w.data_ptr(), _ptr(w2), c.data_ptr(), m, n, k, epilogue, _dtype_code(a),
+                               _ptr(ws), ws.numel() if ws is not None else 0, _stream()))
     return c
 
 

@@ -34,7 +34,8 @@ fastav_status_t launch_linear_generic(const void* a, const void* w, const void* 
 bool mfma_linear_supported(int64_t m, int n, int k, int epilogue, int dtype);
 fastav_status_t launch_linear_mfma(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
                                    const void* w2, void* c, int64_t ldc, int64_t m, int n, int k, int epilogue,
-                                   hipStream_t s);
+                                   void* scratch, size_t scratch_bytes, hipStream_t s);
+size_t mfma_linear_scratch_bytes();
 fastav_status_t launch_attention_generic(const void* q, int64_t q_stride, const void* k, const void* v,
                                          int64_t kv_stride, void* o, int64_t o_stride, const int32_t* cu, int batch,
                                          int64_t T, int max_seqlen, int Hq, int Hkv, int dh, float* last_logits,
@@ -48,7 +49,7 @@ fastav_status_t launch_attention_mfma(const void* q, int64_t q_stride, const voi
 // One linear layer whose weight rows may come from up to three matrices stacked along N (Q|K|V).
 static fastav_status_t linear_segments(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
                                        const void* w2, void* c, int64_t ldc, int64_t m, int k, int epilogue, int dtype,
-                                       hipStream_t s) {
+                                       void* scratch, size_t scratch_bytes, hipStream_t s) {
   int n = 0;
   for (int i = 0; i < n_seg; ++i) n += seg_rows[i];
   if (m == 0 || n == 0) return FASTAV_OK;
@@ -57,7 +58,7 @@ static fastav_status_t linear_segments(const void* a, const void* const* w_seg, 
   ProfScope prof(kind, 2.0 * (double)m * n * k * (epilogue == FASTAV_EPI_SWIGLU ? 2.0 : 1.0), s);
   bool ok = mfma_linear_supported(m, n, k, epilogue, dtype);
   for (int i = 0; i < n_seg && ok; ++i) ok = mfma_linear_supported(m, seg_rows[i], k, epilogue, dtype);
-  if (ok) return launch_linear_mfma(a, w_seg, seg_rows, n_seg, w2, c, ldc, m, n, k, epilogue, s);
+  if (ok) return launch_linear_mfma(a, w_seg, seg_rows, n_seg, w2, c, ldc, m, n, k, epilogue, scratch, scratch_bytes, s);
   const size_t es = dtype == FASTAV_BF16 ? 2 : 4;
   int col = 0;
   for (int i = 0; i < n_seg; ++i) {
@@ -70,10 +71,10 @@ static fastav_status_t linear_segments(const void* a, const void* const* w_seg, 
 }
 
 fastav_status_t launch_linear(const void* a, const void* w, const void* w2, void* c, int64_t m, int n, int k,
-                              int epilogue, int dtype, hipStream_t s) {
+                              int epilogue, int dtype, void* scratch, size_t scratch_bytes, hipStream_t s) {
   const void* seg[1] = {w};
   int rows[1] = {n};
-  return linear_segments(a, seg, rows, 1, w2, c, n, m, k, epilogue, dtype, s);
+  return linear_segments(a, seg, rows, 1, w2, c, n, m, k, epilogue, dtype, scratch, scratch_bytes, s);
 }
 
 fastav_status_t launch_attention(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
@@ -185,7 +186,7 @@ static void build_schedule(const fastav_batch_t* in, const fastav_prune_t* prune
 // ------------------------------------------------------------------------------------------ workspace
 struct Workspace {
   size_t resid[2], hn, qkv, attn[2], hmlp, logits, ml, partials, scores, pos[2], prot[2], keep_idx, cu, span_off,
-      spans, total;
+      spans, gemm_scratch, gemm_scratch_bytes, total;
 };
 
 static Workspace carve(const fastav_model_t& m, int64_t T, int B) {
@@ -213,6 +214,8 @@ static Workspace carve(const fastav_model_t& m, int64_t T, int B) {
   w.cu = take((size_t)(FASTAV_MAX_PRUNES + 1) * (B + 1) * 4);
   w.span_off = take((size_t)(B + 1) * 4);
   w.spans = take((size_t)T * sizeof(fastav_span_t));       // a span holds >= 1 token
+  w.gemm_scratch_bytes = m.dtype == FASTAV_BF16 ? mfma_linear_scratch_bytes() : 0;   // split-K partial tiles
+  w.gemm_scratch = take(w.gemm_scratch_bytes);
   w.total = at;
   return w;
 }
@@ -358,6 +361,7 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
   int32_t* cu_dev = (int32_t*)(base + ws.cu);
   int32_t* span_off_dev = (int32_t*)(base + ws.span_off);
   fastav_span_t* spans_dev = (fastav_span_t*)(base + ws.spans);
+  void* gscr = ws.gemm_scratch_bytes ? (void*)(base + ws.gemm_scratch) : nullptr;
 
   FASTAV_TRY(upload_small(cu_dev, cu_host.data(), cu_host.size() * 4, s));
   FASTAV_TRY(upload_small(span_off_dev, in->span_offsets, (size_t)(B + 1) * 4, s));
@@ -393,7 +397,7 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
     {
       const void* seg[3] = {W.wq, W.wk, W.wv};
       int rows[3] = {qd, kd, kd};
-      FASTAV_TRY(linear_segments(hn, seg, rows, 3, nullptr, qkv, qkv_stride, Tl, m.hidden, FASTAV_EPI_STORE, m.dtype, s));
+      FASTAV_TRY(linear_segments(hn, seg, rows, 3, nullptr, qkv, qkv_stride, Tl, m.hidden, FASTAV_EPI_STORE, m.dtype, nullptr, 0, s));
     }
     FASTAV_TRY(launch_rope(qkv, qkv_stride, pos[cur], Tl, m.n_q_heads + m.n_kv_heads, m.head_dim, m.rope_base, m.dtype, s));
     const char* kptr = qkv + (size_t)qd * es;
@@ -432,10 +436,10 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
       if (v_out) FASTAV_TRY(launch_copy_rows(vptr, qkv_stride * (int64_t)es, v_out, (int64_t)kd * (int64_t)es, Tl, nullptr, s));
     }
     const int64_t To = T_stage[stage];
-    FASTAV_TRY(launch_linear(attn_cur, W.wo, nullptr, resid[cur], To, m.hidden, qd, FASTAV_EPI_RESADD, m.dtype, s));
+    FASTAV_TRY(launch_linear(attn_cur, W.wo, nullptr, resid[cur], To, m.hidden, qd, FASTAV_EPI_RESADD, m.dtype, gscr, ws.gemm_scratch_bytes, s));
     FASTAV_TRY(launch_rmsnorm(resid[cur], W.g_mlp, hn, To, m.hidden, m.rms_eps, m.dtype, s));
-    FASTAV_TRY(launch_linear(hn, W.w_gate, W.w_up, hmlp, To, m.mlp_dim, m.hidden, FASTAV_EPI_SWIGLU, m.dtype, s));
-    FASTAV_TRY(launch_linear(hmlp, W.w_down, nullptr, resid[cur], To, m.hidden, m.mlp_dim, FASTAV_EPI_RESADD, m.dtype, s));
+    FASTAV_TRY(launch_linear(hn, W.w_gate, W.w_up, hmlp, To, m.mlp_dim, m.hidden, FASTAV_EPI_SWIGLU, m.dtype, nullptr, 0, s));
+    FASTAV_TRY(launch_linear(hmlp, W.w_down, nullptr, resid[cur], To, m.hidden, m.mlp_dim, FASTAV_EPI_RESADD, m.dtype, gscr, ws.gemm_scratch_bytes, s));
     if (out->layer_x_out && out->layer_x_out[l])
       FASTAV_TRY(launch_copy_rows(resid[cur], (int64_t)m.hidden * 4, out->layer_x_out[l], (int64_t)m.hidden * 4, To, nullptr, s));
   }
@@ -537,13 +541,16 @@ fastav_status_t fastav_rope(void* x, int64_t row_stride, const int32_t* pos, int
   return launch_rope(x, row_stride, pos, rows, n_heads, head_dim, base, dtype, (hipStream_t)stream);
 }
 
+size_t fastav_linear_workspace_bytes(void) { return mfma_linear_scratch_bytes(); }
+
 fastav_status_t fastav_linear(const void* a, const void* w, const void* w2, void* c, int64_t m, int32_t n, int32_t k,
-                              int32_t epilogue, int32_t dtype, void* stream) {
+                              int32_t epilogue, int32_t dtype, void* workspace, size_t workspace_bytes, void* stream) {
+  if (workspace && ((uintptr_t)workspace % 256)) return fail(FASTAV_EINVAL, "workspace must be 256-byte aligned");
   if (!a || !w || !c) return fail(FASTAV_EINVAL, "a pointer argument is NULL");
   if (m < 0 || n < 1 || k < 1 || (dtype != FASTAV_BF16 && dtype != FASTAV_F32)) return fail(FASTAV_EINVAL, "bad m/n/k/dtype");
   if (epilogue < FASTAV_EPI_STORE || epilogue > FASTAV_EPI_SWIGLU) return fail(FASTAV_EINVAL, "bad epilogue");
   if (epilogue == FASTAV_EPI_SWIGLU && !w2) return fail(FASTAV_EINVAL, "w2 is NULL for the SwiGLU epilogue");
-  return launch_linear(a, w, w2, c, m, n, k, epilogue, dtype, (hipStream_t)stream);
+  return launch_linear(a, w, w2, c, m, n, k, epilogue, dtype, workspace, workspace ? workspace_bytes : 0, (hipStream_t)stream);
 }
 
 fastav_status_t fastav_attention(const fastav_model_t* model, const void* q, int64_t q_row_stride, const void* k,

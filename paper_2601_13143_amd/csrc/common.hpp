@@ -71,8 +71,9 @@ fastav_status_t launch_rmsnorm(const float* x, const void* g, void* y, int64_t r
                                hipStream_t s);
 fastav_status_t launch_rope(void* x, int64_t row_stride, const int32_t* pos, int64_t rows, int n_heads, int head_dim,
                             float base, int dtype, hipStream_t s);
+// scratch (optional): device memory for split-K partial tiles; without it small-M residual GEMMs are not split
 fastav_status_t launch_linear(const void* a, const void* w, const void* w2, void* c, int64_t m, int n, int k,
-                              int epilogue, int dtype, hipStream_t s);
+                              int epilogue, int dtype, void* scratch, size_t scratch_bytes, hipStream_t s);
 fastav_status_t launch_attention(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
                                  void* o, int64_t o_stride, const int32_t* cu, int batch, int64_t T, int max_seqlen,
                                  int Hq, int Hkv, int dh, float* last_logits, float* last_ml, int dtype,

@@ -1,14 +1,20 @@
 // bf16 linear layers on the CDNA4 matrix cores: C = A W^T with A [M, K] and W [N, K] both K-contiguous,
 // fp32 accumulation in v_mfma_f32_32x32x16_bf16.
 //
-// Tiling: one workgroup (2 x 4 waves for the 256 x 256 tile, so that two waves share each SIMD and one's
-// MFMAs cover the other's LDS and barrier waits; 2 x 2 waves for 128 x 128) owns a BM x BN output tile
-// and walks K in steps of 64.  Each
-// K-step's A and B panels are fetched from HBM/L2 with 16-byte loads into registers while the previous
-// step is being multiplied, then parked in one of two LDS stages (row = 64 bf16 = 128 bytes, 16-byte
-// chunks XOR-swizzled with half the row index so that both the row-major stores and the MFMA operand reads
-// (32 rows x one chunk) spread over all 64 banks).  A wave multiplies its (BM/WM) x (BN/WN) sub-tile as
-// 32 x 32 MFMA blocks.
+// One workgroup owns a BM x BN output tile; its WM x WN waves each multiply a (BM/WM) x (BN/WN) sub-tile as
+// 32 x 32 MFMA blocks.  K is walked in stages of 32.  The operands of a stage travel HBM/L2 -> LDS with
+// asynchronous 16-byte copies (global_load_lds_dwordx4: no VGPR staging, no ds_write) into a ring of four
+// LDS stages, three stages ahead of the math.  The copies are issued one at a time between groups of MFMAs:
+// the memory pipeline takes 64 B/clk per CU, and a burst of copies would queue up in front of the issuing
+// waves' matrix instructions.  The last k-slice of a stage is multiplied after the barrier that publishes
+// the next stage, while that stage's first operand reads are already in flight.
+//
+// LDS layout: a stage holds BM + BN rows of 32 bf16 = 64 bytes (4 chunks of 16).  The LDS has 64 four-byte
+// banks and serves a 16-byte-per-lane read 16 lanes at a time, so the 16 rows an MFMA operand read touches
+// (same logical chunk) must fall in 16 distinct 16-byte slots of the 256-byte bank window: four rows share
+// a window, hence chunk ^ (row/4 & 3).  A copy instruction lands lane l at base + 16 l, i.e. it fills 16
+// consecutive rows; the swizzle is applied on the global side (a lane fetches the chunk that belongs in
+// its slot).
 //
 // B rows may come from several matrices: Q|K|V stacked along N (segments), or gate/up for the SwiGLU
 // epilogue, where 32-row blocks of the B tile alternate gate, up, gate, up ... so that a lane holds
@@ -32,43 +38,39 @@ struct GemmArgs {
   int64_t ldc;
   int M, N, K;             // N = output columns
   int tiles_m, tiles_n;
-  int pf_dist;             // K-steps ahead that lines are pulled into L2 (0 = off)
+  int n_off;               // first output column of this launch (a launch may cover a range of tile columns)
+  int splits;              // split-K: blockIdx.y picks a K range and writes an fp32 partial tile to `partial`
+  float* partial;          // [splits][M][N] fp32 (split-K only)
 };
 
-// LDS tile rows are 128 bytes (8 chunks of 16).  The LDS has 64 four-byte banks and serves a 16-byte-per-lane
-// access 16 lanes at a time, so 16 consecutive rows reading the same logical chunk must land in 16 different
-// 16-byte slots of the 256-byte bank window: two rows share a window, hence the XOR with row/2.
-__device__ __forceinline__ int swz(int row, int chunk) { return row * 8 + (chunk ^ ((row >> 1) & 7)); }   // in 16-byte units
+constexpr int kEpiPartial = 100;   // internal epilogue: plain fp32 store of a split-K partial
 
-// Asynchronous 16-byte global -> LDS copy (no VGPR staging, no ds_write): lane l's data lands at
-// lds_base + 16 l, so a wave fills 8 consecutive 128-byte tile rows per instruction; the XOR swizzle is
-// applied on the global side (each lane fetches the chunk that belongs in its slot).  Completion is
-// tracked by vmcnt; the caller waits with dma_wait() before the barrier that publishes the stage.
+// Asynchronous 16-byte global -> LDS copy; lane l's data lands at lds_byte_addr + 16 l.  Completion is
+// tracked by vmcnt (copies complete in issue order).
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_byte_addr) {
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_byte_addr) : "memory");
 }
-__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
-// Same path with a 4-byte payload aimed at a scratch corner of LDS: used only to pull a cache line into L2
-// a few K-steps before the real copy needs it (no VGPR is written, so nothing has to stay reserved).
-__device__ __forceinline__ void l2_touch(const void* gptr, uint32_t lds_scratch_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" : : "v"(gptr), "s"(lds_scratch_addr) : "memory");
+template <int N> __device__ __forceinline__ void dma_wait_keep() {   // until at most N copies are in flight
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
-// All copies of this K-step have landed; the one younger instruction (the L2 touch) may still be in flight.
-__device__ __forceinline__ void dma_wait_keep1() { asm volatile("s_waitcnt vmcnt(1)" : : : "memory"); }
 
-template <int BM, int BN, int WM, int WN, int EPI, bool DMA, int SCHED = 0>
+__device__ __forceinline__ int swz4(int row, int chunk) { return row * 4 + (chunk ^ ((row >> 2) & 3)); }   // 16-byte units
+
+template <int BM, int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_mfma(GemmArgs g) {
-  constexpr int BK = 64;
-  constexpr int NT = WM * WN * 64;                     // threads
+  constexpr int NW = WM * WN;                          // waves
   constexpr int WTM = BM / WM, WTN = BN / WN;          // wave tile
   constexpr int TM = WTM / 32, TN = WTN / 32;          // 32x32 blocks per wave
-  constexpr int RPP = NT / 8;                          // rows covered by one load pass of the workgroup
-  constexpr int A_CH = BM / RPP, B_CH = BN / RPP;      // 16-byte chunks per thread per K-step
-  static_assert(RPP % 32 == 0 && TN % 2 == 0, "tile shape");
+  constexpr int NST = 4;                               // LDS stages of 32 k
+  constexpr int A_D = BM / (16 * NW), B_D = BN / (16 * NW);   // copy instructions per wave and stage
+  constexpr int D = A_D + B_D;
+  constexpr int NMF = TM * TN;                         // MFMAs per k-slice
+  constexpr int GRP = NMF / (D / 2);                   // MFMAs between two copies
   constexpr int OUT_BN = (EPI == FASTAV_EPI_SWIGLU) ? BN / 2 : BN;
+  static_assert(A_D >= 1 && B_D >= 1 && D % 2 == 0 && NMF % (D / 2) == 0 && TN % 2 == 0, "tile shape");
   extern __shared__ bf16x8_t lds[];
-  bf16x8_t* As = lds;                                     // [2][BM*8]
-  bf16x8_t* Bs = lds + 2 * BM * 8;                        // [2][BN*8]
+  bf16x8_t* A4 = lds;                                  // [NST][BM*4]
+  bf16x8_t* B4 = lds + NST * BM * 4;                   // [NST][BN*4]
 
   // ---- tile assignment
   const int nblk = g.tiles_m * g.tiles_n;
@@ -79,23 +81,18 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_mfma(GemmArgs g) {
   }
   const int tile_m = pid % g.tiles_m, tile_n = pid / g.tiles_m;
   const int m0 = tile_m * BM;
-  const int n0 = tile_n * OUT_BN;
+  const int n0 = g.n_off + tile_n * OUT_BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   const int wm = wave / WN, wn = wave % WN;
   const int K = g.K;
+  // stages of 32 k owned by this workgroup (all of them unless split-K)
+  const int kt_all = K / 32;
+  const int kt0 = (int)((int64_t)kt_all * blockIdx.y / g.splits);
+  const int KT = (int)((int64_t)kt_all * (blockIdx.y + 1) / g.splits) - kt0;
 
-  f32x16_t acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-  const int KT = K / BK;
-  const int frow = lane & 31, fch = lane >> 5;         // operand fragment: row in block, which 8-wide k chunk
-
-  // B-tile row -> source row pointer (segments for Q|K|V; gate/up interleaved per 32 rows for SwiGLU)
+  // B-tile row -> source row (segments for Q|K|V; gate/up interleaved per 32 rows for SwiGLU)
   const bf16_t* wbase = g.W[0];
   int seg_start = 0;
   if (EPI != FASTAV_EPI_SWIGLU) {
@@ -106,326 +103,97 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_mfma(GemmArgs g) {
     if (EPI == FASTAV_EPI_SWIGLU) {
       const int blk = brow >> 5;
       const bf16_t* wsel = (blk & 1) ? g.W2 : g.W[0];
-      return wsel + (int64_t)(n0 + (blk >> 1) * 32 + (brow & 31)) * K;
+      return wsel + (int64_t)(n0 + (blk >> 1) * 32 + (brow & 31)) * K + kt0 * 32;
     }
-    return wbase + (int64_t)(n0 - seg_start + brow) * K;
+    return wbase + (int64_t)(n0 - seg_start + brow) * K + kt0 * 32;
   };
   auto a_row_ptr = [&](int arow) -> const bf16_t* {
     int row = m0 + arow;
     row = row < g.M ? row : g.M - 1;                    // clamp: stay inside A, the epilogue masks the row
-    return g.A + (int64_t)row * K;
+    return g.A + (int64_t)row * K + kt0 * 32;
   };
 
-  // One K-step (4 MFMA k-slices of 16) on LDS stage st.  Operand fragments are double-buffered in
-  // registers: the reads of slice kk+1 are issued before the MFMAs of slice kk, so LDS latency hides
-  // behind matrix work instead of stalling it.
-  auto mma_stage = [&](int st) {
-    const bf16x8_t* Asb = As + st * BM * 8;
-    const bf16x8_t* Bsb = Bs + st * BN * 8;
-    bf16x8_t af[2][TM], bfr[2][TN];
-    auto frags = [&](int buf, int kk) {
+  // ---- this wave's copies: instruction i covers tile rows [(i*NW + wave)*16, +16)
+  const int drow = lane >> 2, dpos = lane & 3;          // row inside the 16-row group, 16-byte slot inside the row
+  const bf16_t* a_src[A_D];
+  const bf16_t* b_src[B_D];
+  uint32_t a_dst[A_D], b_dst[B_D];                      // LDS byte address of the 16-row group in stage 0
+  const uint32_t a_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)A4;
+  const uint32_t b_base = a_base + (uint32_t)NST * BM * 64u;
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[buf][i] = Asb[swz(wm * WTM + i * 32 + frow, kk * 2 + fch)];
-#pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[buf][j] = Bsb[swz(wn * WTN + j * 32 + frow, kk * 2 + fch)];
-    };
-    frags(0, 0);
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      if (kk + 1 < 4) frags((kk + 1) & 1, kk + 1);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
-    }
-  };
-
-  if constexpr (DMA) {
-    // wave `wave` owns tile rows [wave*8 + 8*NW*i, +8) of A and of B for i = 0 .. *_DI-1
-    constexpr int NW = WM * WN;
-    constexpr int A_DI = BM / (8 * NW), B_DI = BN / (8 * NW);
-    const int drow = lane >> 3, dpos = lane & 7;       // row inside the 8-row group, 16-byte slot inside the row
-    const bf16_t* a_src[A_DI];
-    const bf16_t* b_src[B_DI];
-    uint32_t a_dst[A_DI], b_dst[B_DI];                 // LDS byte address of the 8-row group in stage 0
-    const uint32_t as_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)As;
-    const uint32_t bs_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)Bs;
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-#pragma unroll
-    for (int i = 0; i < A_DI; ++i) {
-      const int r0 = (i * NW + wave_u) * 8, row = r0 + drow;
-      a_src[i] = a_row_ptr(row) + ((dpos ^ ((row >> 1) & 7)) * 8);
-      a_dst[i] = as_base + (uint32_t)r0 * 128u;
-    }
-#pragma unroll
-    for (int i = 0; i < B_DI; ++i) {
-      const int r0 = (i * NW + wave_u) * 8, row = r0 + drow;
-      b_src[i] = b_row_ptr(row) + ((dpos ^ ((row >> 1) & 7)) * 8);
-      b_dst[i] = bs_base + (uint32_t)r0 * 128u;
-    }
-    auto issue = [&](int kt, int st) {
-      const int koff = kt * BK;
-#pragma unroll
-      for (int i = 0; i < A_DI; ++i) dma16(a_src[i] + koff, a_dst[i] + (uint32_t)st * (BM * 128u));
-#pragma unroll
-      for (int i = 0; i < B_DI; ++i) dma16(b_src[i] + koff, b_dst[i] + (uint32_t)st * (BN * 128u));
-    };
-    issue(0, 0);
-    dma_wait();
-    __syncthreads();
-    if constexpr (SCHED == 0) {
-      for (int kt = 0; kt < KT; ++kt) {
-        const int st = kt & 1;
-        if (kt + 1 < KT) issue(kt + 1, st ^ 1);        // stage st^1 was last read before the previous barrier
-        mma_stage(st);
-        dma_wait();
-        __syncthreads();
-      }
-    } else {
-      // Software-pipelined across the barrier: the last k-slice of a stage is multiplied AFTER the barrier
-      // that publishes the next stage, while the next stage's first operand reads are already in flight.
-      bf16x8_t af[2][TM], bfr[2][TN];
-      auto frags = [&](int buf, int st, int kk) {
-        const bf16x8_t* Asb = As + st * BM * 8;
-        const bf16x8_t* Bsb = Bs + st * BN * 8;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) af[buf][i] = Asb[swz(wm * WTM + i * 32 + frow, kk * 2 + fch)];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) bfr[buf][j] = Bsb[swz(wn * WTN + j * 32 + frow, kk * 2 + fch)];
-        if constexpr (SCHED == 2) __builtin_amdgcn_sched_barrier(0);
-      };
-      auto mfmas = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
-        if constexpr (SCHED == 2) __builtin_amdgcn_sched_barrier(0);
-        if constexpr (SCHED == 3 || SCHED == 4 || SCHED == 5 || SCHED == 6) {
-          // interleave: one LDS read between MFMAs
-#pragma unroll
-          for (int q = 0; q < TM + TN; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-          }
-          __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
-        }
-      };
-      if constexpr (SCHED == 4) {
-        // As above, and the next tile's copies are spread over the K-step (one A and one B instruction per
-        // k-slice) instead of being issued in one burst that backs up the memory pipeline.
-        static_assert(A_DI == 4 && B_DI == 4, "spread schedule assumes 4 + 4 copies per wave and K-step");
-        // Past the last tile the copy is re-aimed at the last tile (into a stage nobody reads any more):
-        // keeping the loop body branch-free matters more than the two redundant copies per workgroup.
-        auto dma_part = [&](int kt_next, int part) {
-          const int koff = (kt_next < KT ? kt_next : KT - 1) * BK, stn = kt_next & 1;
-          dma16(a_src[part] + koff, a_dst[part] + (uint32_t)stn * (BM * 128u));
-          dma16(b_src[part] + koff, b_dst[part] + (uint32_t)stn * (BN * 128u));
-        };
-        dma_part(1, 0);
-        frags(0, 0, 0);
-        for (int kt = 0; kt < KT; ++kt) {
-          const int st = kt & 1;
-          frags(1, st, 1); dma_part(kt + 1, 1); mfmas(0);
-          frags(0, st, 2); dma_part(kt + 1, 2); mfmas(1);
-          frags(1, st, 3); dma_part(kt + 1, 3); mfmas(0);
-          dma_wait();
-          __syncthreads();
-          frags(0, st ^ 1, 0);                          // (after the last tile: a harmless read of the idle stage)
-          dma_part(kt + 2, 0);                          // stage st is free again after the barrier
-          mfmas(1);
-        }
-        dma_wait();
-      } else if constexpr (SCHED == 6 || SCHED == 7) {
-        constexpr bool SPREAD = (SCHED == 7);
-        // Four LDS stages of 32 k each (same 128 KB): copies run three stages ahead of the math, so a stage
-        // has three stage-times to arrive instead of one.  Rows are 64 bytes here (4 chunks): four rows
-        // share a 256-byte bank window, hence the XOR with row/4.
-        constexpr int NST = 4;
-        constexpr int A_D = BM / (16 * NW), B_D = BN / (16 * NW);
-        static_assert(A_D >= 1 && B_D >= 1, "tile too small for the 4-stage copy pattern");
-        bf16x8_t* A4 = lds;                              // [NST][BM*4]
-        bf16x8_t* B4 = lds + NST * BM * 4;               // [NST][BN*4]
-        auto swz4 = [](int row, int chunk) { return row * 4 + (chunk ^ ((row >> 2) & 3)); };
-        const int drow4 = lane >> 2, dpos4 = lane & 3;
-        const bf16_t* a4_src[A_D];
-        const bf16_t* b4_src[B_D];
-        uint32_t a4_dst[A_D], b4_dst[B_D];
-#pragma unroll
-        for (int i = 0; i < A_D; ++i) {
-          const int r0 = (i * NW + wave_u) * 16, row = r0 + drow4;
-          a4_src[i] = a_row_ptr(row) + ((dpos4 ^ ((row >> 2) & 3)) * 8);
-          a4_dst[i] = as_base + (uint32_t)r0 * 64u;
-        }
-        const uint32_t b4_base = as_base + (uint32_t)NST * BM * 64u;
-#pragma unroll
-        for (int i = 0; i < B_D; ++i) {
-          const int r0 = (i * NW + wave_u) * 16, row = r0 + drow4;
-          b4_src[i] = b_row_ptr(row) + ((dpos4 ^ ((row >> 2) & 3)) * 8);
-          b4_dst[i] = b4_base + (uint32_t)r0 * 64u;
-        }
-        const int KT4 = K / 32;
-        auto issue4 = [&](int t) {
-          const int koff = (t < KT4 ? t : KT4 - 1) * 32;   // past the end: a redundant copy into an idle slot
-          const uint32_t slot = (uint32_t)(t & 3);
-#pragma unroll
-          for (int i = 0; i < A_D; ++i) dma16(a4_src[i] + koff, a4_dst[i] + slot * (BM * 64u));
-#pragma unroll
-          for (int i = 0; i < B_D; ++i) dma16(b4_src[i] + koff, b4_dst[i] + slot * (BN * 64u));
-        };
-        auto frags4 = [&](int buf, int slot, int kk) {
-          const bf16x8_t* Asb = A4 + slot * BM * 4;
-          const bf16x8_t* Bsb = B4 + slot * BN * 4;
-#pragma unroll
-          for (int i = 0; i < TM; ++i) af[buf][i] = Asb[swz4(wm * WTM + i * 32 + frow, kk * 2 + fch)];
-#pragma unroll
-          for (int j = 0; j < TN; ++j) bfr[buf][j] = Bsb[swz4(wn * WTN + j * 32 + frow, kk * 2 + fch)];
-        };
-        // waits until at most 2 stages' worth of this wave's copies are still in flight
-        auto wait_keep2 = [&]() {
-          static_assert(A_D + B_D == 4, "the vmcnt immediate below is 2 * (A_D + B_D)");
-          asm volatile("s_waitcnt vmcnt(8)" : : : "memory");
-        };
-        issue4(0); issue4(1); issue4(2);
-        wait_keep2();
-        __syncthreads();
-        frags4(0, 0, 0);
-        if constexpr (SPREAD) {
-          // One copy instruction at a time, fenced between halves of a k-slice's MFMAs: a burst of copies
-          // at the top of a stage would sit in the memory pipeline's input queue (64 B/clk) and hold up the
-          // issuing waves' matrix instructions behind it.
-          static_assert(A_D == 2 && B_D == 2 && TM % 2 == 0, "spread schedule: 2 + 2 copies per wave and stage");
-          auto mfma_half = [&](int buf, int half) {
-#pragma unroll
-            for (int i = half * (TM / 2); i < (half + 1) * (TM / 2); ++i)
-#pragma unroll
-              for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
-          };
-          auto dma_one = [&](int t, bool is_b, int i) {
-            const int koff = (t < KT4 ? t : KT4 - 1) * 32;
-            const uint32_t slot = (uint32_t)(t & 3);
-            __builtin_amdgcn_sched_barrier(0);
-            if (is_b) dma16(b4_src[i] + koff, b4_dst[i] + slot * (BN * 64u));
-            else dma16(a4_src[i] + koff, a4_dst[i] + slot * (BM * 64u));
-            __builtin_amdgcn_sched_barrier(0);
-          };
-          for (int t = 0; t < KT4; ++t) {
-            frags4(1, t & 3, 1);
-            mfma_half(0, 0); dma_one(t + 3, false, 0);
-            mfma_half(0, 1); dma_one(t + 3, true, 0);
-            asm volatile("s_waitcnt vmcnt(6)" : : : "memory");   // stage t+1 landed; stage t+2 and two copies of t+3 may fly
-            __syncthreads();
-            frags4(0, (t + 1) & 3, 0);
-            mfma_half(1, 0); dma_one(t + 3, false, 1);
-            mfma_half(1, 1); dma_one(t + 3, true, 1);
-          }
-        } else {
-          for (int t = 0; t < KT4; ++t) {
-            issue4(t + 3);                               // its slot held stage t-1, free since the last barrier
-            frags4(1, t & 3, 1); mfmas(0);
-            wait_keep2();                                // stage t+1 has landed (this wave's share)
-            __syncthreads();
-            frags4(0, (t + 1) & 3, 0);
-            mfmas(1);
-          }
-        }
-        dma_wait();
-      } else if constexpr (SCHED == 5) {
-        // SCHED 3 plus an L2 warm-up: each wave touches 64 cache lines (one per lane) of the tile pf_dist
-        // K-steps ahead, so that the real copies one K-step ahead hit L2 instead of paying DRAM latency.
-        static_assert(NW == 8 && BM == 256 && BN == 256, "the touch pattern assumes 8 waves on a 256 x 256 tile");
-        const uint32_t scratch = bs_base + 2u * BN * 128u;               // 256 bytes past the B stages
-        const int prow = (wave_u & 3) * 64 + lane;
-        const bf16_t* pf_src = (wave_u < 4) ? a_row_ptr(prow) : b_row_ptr(prow);
-        const int pd = g.pf_dist;
-        frags(0, 0, 0);
-        for (int kt = 0; kt < KT; ++kt) {
-          const int st = kt & 1;
-          if (kt + 1 < KT) issue(kt + 1, st ^ 1);
-          { const int kp = kt + pd; l2_touch(pf_src + (kp < KT ? kp : KT - 1) * BK, scratch); }
-          frags(1, st, 1); mfmas(0);
-          frags(0, st, 2); mfmas(1);
-          frags(1, st, 3); mfmas(0);
-          dma_wait_keep1();
-          __syncthreads();
-          if (kt + 1 < KT) frags(0, st ^ 1, 0);
-          mfmas(1);
-        }
-        dma_wait();
-      } else if constexpr (SCHED >= 100) {
-        // measurement-only ablations (results are wrong): 101 no copies, 102 no barrier, 103 no operand reads
-        frags(0, 0, 0);
-        frags(1, 0, 1);
-        for (int kt = 0; kt < KT; ++kt) {
-          const int st = kt & 1;
-          if (SCHED != 101 && kt + 1 < KT) issue(kt + 1, st ^ 1);
-          if (SCHED != 103) frags(1, st, 1);
-          mfmas(0);
-          if (SCHED != 103) frags(0, st, 2);
-          mfmas(1);
-          if (SCHED != 103) frags(1, st, 3);
-          mfmas(0);
-          if (SCHED != 102) { dma_wait(); __syncthreads(); }
-          if (SCHED != 103 && kt + 1 < KT) frags(0, st ^ 1, 0);
-          mfmas(1);
-        }
-        dma_wait();
-      } else {
-        frags(0, 0, 0);
-        for (int kt = 0; kt < KT; ++kt) {
-          const int st = kt & 1;
-          if (kt + 1 < KT) issue(kt + 1, st ^ 1);
-          frags(1, st, 1); mfmas(0);
-          frags(0, st, 2); mfmas(1);
-          frags(1, st, 3); mfmas(0);
-          dma_wait();
-          __syncthreads();
-          if (kt + 1 < KT) frags(0, st ^ 1, 0);
-          mfmas(1);
-        }
-      }
-    }
-  } else {
-    const int lr = tid >> 3, lc = tid & 7;             // this thread's row in a load pass and chunk
-    const bf16_t* a_src[A_CH];
-    const bf16_t* b_src[B_CH];
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) a_src[i] = a_row_ptr(lr + RPP * i) + lc * 8;
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) b_src[i] = b_row_ptr(lr + RPP * i) + lc * 8;
-    bf16x8_t a_reg[A_CH], b_reg[B_CH];
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) a_reg[i] = *(const bf16x8_t*)(a_src[i]);
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) b_reg[i] = *(const bf16x8_t*)(b_src[i]);
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) As[swz(lr + RPP * i, lc)] = a_reg[i];
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) Bs[swz(lr + RPP * i, lc)] = b_reg[i];
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-      const int st = kt & 1;
-      if (kt + 1 < KT) {
-        const int koff = (kt + 1) * BK;
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i) a_reg[i] = *(const bf16x8_t*)(a_src[i] + koff);
-#pragma unroll
-        for (int i = 0; i < B_CH; ++i) b_reg[i] = *(const bf16x8_t*)(b_src[i] + koff);
-      }
-      mma_stage(st);
-      if (kt + 1 < KT) {
-        bf16x8_t* Asn = As + (st ^ 1) * BM * 8;
-        bf16x8_t* Bsn = Bs + (st ^ 1) * BN * 8;
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i) Asn[swz(lr + RPP * i, lc)] = a_reg[i];
-#pragma unroll
-        for (int i = 0; i < B_CH; ++i) Bsn[swz(lr + RPP * i, lc)] = b_reg[i];
-      }
-      __syncthreads();
-    }
+  for (int i = 0; i < A_D; ++i) {
+    const int r0 = (i * NW + wave_u) * 16, row = r0 + drow;
+    a_src[i] = a_row_ptr(row) + ((dpos ^ ((row >> 2) & 3)) * 8);
+    a_dst[i] = a_base + (uint32_t)r0 * 64u;
   }
+#pragma unroll
+  for (int i = 0; i < B_D; ++i) {
+    const int r0 = (i * NW + wave_u) * 16, row = r0 + drow;
+    b_src[i] = b_row_ptr(row) + ((dpos ^ ((row >> 2) & 3)) * 8);
+    b_dst[i] = b_base + (uint32_t)r0 * 64u;
+  }
+  // copy number c (0 .. D-1: A's first) of stage t.  Past the last stage the copy is re-aimed at the last
+  // stage (into a ring slot nobody reads any more): a branch-free loop body matters more than the few
+  // redundant copies per workgroup.
+  auto dma_one = [&](int t, int c) {
+    const int koff = (t < KT ? t : KT - 1) * 32;
+    const uint32_t slot = (uint32_t)(t & (NST - 1));
+    if (c < A_D) dma16(a_src[c < A_D ? c : 0] + koff, a_dst[c < A_D ? c : 0] + slot * (BM * 64u));
+    else dma16(b_src[c >= A_D ? c - A_D : 0] + koff, b_dst[c >= A_D ? c - A_D : 0] + slot * (BN * 64u));
+  };
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int frow = lane & 31, fch = lane >> 5;          // operand fragment: row in block, which 8-wide k chunk
+  bf16x8_t af[2][TM], bfr[2][TN];                       // operand fragments of two k-slices
+  auto frags = [&](int buf, int slot, int kk) {
+    const bf16x8_t* Asb = A4 + slot * BM * 4;
+    const bf16x8_t* Bsb = B4 + slot * BN * 4;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) af[buf][i] = Asb[swz4(wm * WTM + i * 32 + frow, kk * 2 + fch)];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bfr[buf][j] = Bsb[swz4(wn * WTN + j * 32 + frow, kk * 2 + fch)];
+  };
+  // One k-slice: NMF MFMAs in D/2 groups, one copy of stage t_copy fenced in after each group.
+  auto slice = [&](int buf, int t_copy, int c0) {
+#pragma unroll
+    for (int grp = 0; grp < D / 2; ++grp) {
+#pragma unroll
+      for (int q = grp * GRP; q < (grp + 1) * GRP; ++q) {
+        const int i = q / TN, j = q % TN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      dma_one(t_copy, c0 + grp);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  // ---- prologue: three stages in flight, the first one landed and published
+#pragma unroll
+  for (int t = 0; t < 3; ++t)
+#pragma unroll
+    for (int c = 0; c < D; ++c) dma_one(t, c);
+  dma_wait_keep<2 * D>();
+  __syncthreads();
+  frags(0, 0, 0);
+
+  for (int t = 0; t < KT; ++t) {
+    // the ring slot of stage t+3 held stage t-1, which nobody reads after the previous barrier
+    frags(1, t & (NST - 1), 1);
+    slice(0, t + 3, 0);
+    dma_wait_keep<D + D / 2>();                          // stage t+1 has landed (this wave's share)
+    __syncthreads();
+    frags(0, (t + 1) & (NST - 1), 0);                    // (after the last stage: a harmless read of an idle slot)
+    slice(1, t + 3, D / 2);
+  }
+  dma_wait_keep<0>();
 
   // ---- epilogue.  Accumulator register r of a 32x32 block: column = lane % 32,
   //      row = (r / 4) * 8 + (lane / 32) * 4 + r % 4.
@@ -457,6 +225,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_mfma(GemmArgs g) {
           const int row = m0 + wm * WTM + i * 32 + (r >> 2) * 8 + erow0 + (r & 3);
           if (row < g.M) {
             if (EPI == FASTAV_EPI_STORE) ((bf16_t*)g.C)[(int64_t)row * g.ldc + col] = (bf16_t)acc[i][j][r];
+            else if (EPI == kEpiPartial) g.partial[((int64_t)blockIdx.y * g.M + row) * g.N + col] = acc[i][j][r];
             else ((float*)g.C)[(int64_t)row * g.ldc + col] += acc[i][j][r];
           }
         }
@@ -466,48 +235,100 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_mfma(GemmArgs g) {
 
 bool mfma_linear_supported(int64_t m, int n, int k, int epilogue, int dtype) {
   if (dtype != FASTAV_BF16 || m < 1 || m > 0x7FFFFFFF) return false;
-  if (k % 64 != 0 || k < 64) return false;
+  if (k % 64 != 0 || k < 128) return false;            // >= 4 stages of 32
   return epilogue == FASTAV_EPI_SWIGLU ? (n % 64 == 0) : (n % 128 == 0);
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, bool DMA, int SCHED = 0>
-static fastav_status_t launch_cfg(GemmArgs& g, hipStream_t s) {
+// R[m][n] += sum over splits of partial[s][m][n], splits added in index order (deterministic).
+__global__ __launch_bounds__(256) void k_splitk_reduce(float* __restrict__ R, int64_t ldc, const float* __restrict__ partial,
+                                                       int M, int N, int splits) {
+  const int64_t n4 = N / 4;
+  const int64_t total = (int64_t)M * n4;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t row = i / n4, c4 = i % n4;
+    f32x4_t acc = *(const f32x4_t*)(R + row * ldc + c4 * 4);
+    for (int s = 0; s < splits; ++s) {
+      const f32x4_t p = *(const f32x4_t*)(partial + ((int64_t)s * M + row) * N + c4 * 4);
+      acc[0] += p[0]; acc[1] += p[1]; acc[2] += p[2]; acc[3] += p[3];
+    }
+    *(f32x4_t*)(R + row * ldc + c4 * 4) = acc;
+  }
+}
+
+// Launches tile columns [col0, col0 + ncols) (in units of the tile's output width) of the GEMM.
+template <int BM, int BN, int WM, int WN, int EPI>
+static fastav_status_t launch_cfg(GemmArgs g, int col0, int ncols, int splits, hipStream_t s) {
   constexpr int OUT_BN = (EPI == FASTAV_EPI_SWIGLU) ? BN / 2 : BN;
   g.tiles_m = (g.M + BM - 1) / BM;
-  g.tiles_n = g.N / OUT_BN;
-  const size_t shmem = (size_t)2 * (BM + BN) * 8 * sizeof(bf16x8_t) + (SCHED == 5 ? 256 : 0);
+  g.tiles_n = ncols;
+  g.n_off = col0 * OUT_BN;
+  g.splits = splits;
+  const size_t shmem = (size_t)4 * (BM + BN) * 4 * sizeof(bf16x8_t);
   if (shmem > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WM, WN, EPI, DMA, SCHED>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    hipError_t e = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WM, WN, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     if (e != hipSuccess) return fail(FASTAV_EHIP, "gemm: hipFuncSetAttribute: %s", hipGetErrorString(e));
   }
-  hipLaunchKernelGGL((k_gemm_mfma<BM, BN, WM, WN, EPI, DMA, SCHED>), dim3((unsigned)(g.tiles_m * g.tiles_n)), dim3(WM * WN * 64), shmem, s, g);
+  hipLaunchKernelGGL((k_gemm_mfma<BM, BN, WM, WN, EPI>), dim3((unsigned)(g.tiles_m * g.tiles_n), (unsigned)splits),
+                     dim3(WM * WN * 64), shmem, s, g);
   return check_launch("gemm_mfma");
 }
 
+constexpr int kCUs = 256;
+constexpr size_t kSplitKScratchBytes = (size_t)2 * kCUs * 256 * 256 * sizeof(float);   // <= 512 partial tiles
+
+size_t mfma_linear_scratch_bytes() { return kSplitKScratchBytes; }
+
 template <int EPI>
-static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, hipStream_t s) {
-  // 256x256 tiles when they still fill the 256 CUs, else 128x128
-  const int64_t tiles_big = (int64_t)((g.M + 255) / 256) * (g.N / (EPI == FASTAV_EPI_SWIGLU ? 128 : 256));
-  if (big_ok && tiles_big >= 192) {
-    static const int variant = getenv("FASTAV_GEMM_VARIANT") ? atoi(getenv("FASTAV_GEMM_VARIANT")) : 0;
-    if (variant == 1) return launch_cfg<256, 256, 2, 4, EPI, true, 1>(g, s);
-    if (variant == 2) return launch_cfg<256, 256, 2, 4, EPI, true, 2>(g, s);
-    if (variant == 3) return launch_cfg<256, 256, 2, 4, EPI, true, 3>(g, s);
-    if (variant == 4) return launch_cfg<256, 256, 2, 4, EPI, true, 4>(g, s);
-    if (variant == 5) { g.pf_dist = getenv("FASTAV_GEMM_PD") ? atoi(getenv("FASTAV_GEMM_PD")) : 3; return launch_cfg<256, 256, 2, 4, EPI, true, 5>(g, s); }
-    if (variant == 6) return launch_cfg<256, 256, 2, 4, EPI, true, 6>(g, s);
-    if (variant == 7) return launch_cfg<256, 256, 2, 4, EPI, true, 7>(g, s);
-    if (variant == 101) return launch_cfg<256, 256, 2, 4, EPI, true, 101>(g, s);
-    if (variant == 102) return launch_cfg<256, 256, 2, 4, EPI, true, 102>(g, s);
-    if (variant == 103) return launch_cfg<256, 256, 2, 4, EPI, true, 103>(g, s);
-    return launch_cfg<256, 256, 2, 4, EPI, true>(g, s);
+static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, void* scratch, size_t scratch_bytes, hipStream_t s) {
+  constexpr int OUT_BIG = (EPI == FASTAV_EPI_SWIGLU) ? 128 : 256, OUT_SMALL = OUT_BIG / 2;
+  const int tm = (g.M + 255) / 256;
+  const int tn = g.N / OUT_BIG;                         // tile columns of the 256 x 256 tiling (valid if big_ok)
+  const int64_t tiles_big = (int64_t)tm * tn;
+  if (!big_ok) return launch_cfg<128, 128, 2, 2, EPI>(g, 0, g.N / OUT_SMALL, 1, s);
+
+  // Less than one round of 256 x 256 tiles and a linear epilogue: split K so that about one tile per CU
+  // is in flight; partial tiles go to scratch and are added to the residual in split order.
+  if (EPI == FASTAV_EPI_RESADD && tiles_big < (kCUs * 9) / 10 && scratch != nullptr && g.ldc % 4 == 0 &&
+      ((uintptr_t)g.C % 16) == 0) {
+    int best = 1;
+    double best_eff = (double)tiles_big / kCUs;
+    for (int sp = 2; sp <= 8; ++sp) {
+      if (tiles_big * sp > 2 * kCUs || (g.K / 32) / sp < 16) break;
+      if ((size_t)sp * g.M * g.N * sizeof(float) > scratch_bytes) break;
+      const double rounds = (double)((tiles_big * sp + kCUs - 1) / kCUs);
+      const double eff = (double)tiles_big * sp / (rounds * kCUs);
+      if (eff > best_eff + 0.05) { best_eff = eff; best = sp; }
+    }
+    if (best > 1) {
+      GemmArgs gp = g;
+      gp.partial = (float*)scratch;
+      fastav_status_t st = launch_cfg<256, 256, 2, 4, kEpiPartial>(gp, 0, tn, best, s);
+      if (st != FASTAV_OK) return st;
+      const int64_t total = (int64_t)g.M * (g.N / 4);
+      const unsigned blocks = (unsigned)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
+      hipLaunchKernelGGL(k_splitk_reduce, dim3(blocks), dim3(256), 0, s, (float*)g.C, g.ldc, (const float*)scratch, g.M, g.N, best);
+      return check_launch("splitk_reduce");
+    }
   }
-  return launch_cfg<128, 128, 2, 2, EPI, false>(g, s);
+  if (tiles_big < 192) return launch_cfg<128, 128, 2, 2, EPI>(g, 0, g.N / OUT_SMALL, 1, s);
+
+  // Whole rounds of big tiles, then the leftover tile columns with 128 x 128 tiles (two workgroups per CU)
+  // when the last round would leave three quarters of the CUs idle.
+  const int64_t rem = tiles_big % kCUs;
+  if (tiles_big > kCUs && rem != 0 && rem <= kCUs / 4) {
+    const int cols_full = (int)((tiles_big - rem) / tm);          // whole tile columns inside the full rounds
+    if (cols_full > 0 && cols_full < tn) {
+      fastav_status_t st = launch_cfg<256, 256, 2, 4, EPI>(g, 0, cols_full, 1, s);
+      if (st != FASTAV_OK) return st;
+      return launch_cfg<128, 128, 2, 2, EPI>(g, cols_full * 2, (tn - cols_full) * 2, 1, s);
+    }
+  }
+  return launch_cfg<256, 256, 2, 4, EPI>(g, 0, tn, 1, s);
 }
 
 fastav_status_t launch_linear_mfma(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
                                    const void* w2, void* c, int64_t ldc, int64_t m, int n, int k, int epilogue,
-                                   hipStream_t s) {
+                                   void* scratch, size_t scratch_bytes, hipStream_t s) {
   GemmArgs g;
   g.A = (const bf16_t*)a;
   int end = 0;
@@ -523,11 +344,11 @@ fastav_status_t launch_linear_mfma(const void* a, const void* const* w_seg, cons
     g.seg_end[i] = i < n_seg ? end : 0x7FFFFFFF;
   }
   g.W2 = (const bf16_t*)w2;
-  g.C = c; g.ldc = ldc; g.M = (int)m; g.N = n; g.K = k; g.pf_dist = 0;
+  g.C = c; g.ldc = ldc; g.M = (int)m; g.N = n; g.K = k; g.n_off = 0; g.splits = 1; g.partial = nullptr;
   if (((uintptr_t)a | (uintptr_t)w_seg[0]) % 16) return fail(FASTAV_EINVAL, "gemm: A and W must be 16-byte aligned");
-  if (epilogue == FASTAV_EPI_STORE) return launch_epi<FASTAV_EPI_STORE>(g, big_ok, s);
-  if (epilogue == FASTAV_EPI_RESADD) return launch_epi<FASTAV_EPI_RESADD>(g, big_ok, s);
-  return launch_epi<FASTAV_EPI_SWIGLU>(g, big_ok, s);
+  if (epilogue == FASTAV_EPI_STORE) return launch_epi<FASTAV_EPI_STORE>(g, big_ok, scratch, scratch_bytes, s);
+  if (epilogue == FASTAV_EPI_RESADD) return launch_epi<FASTAV_EPI_RESADD>(g, big_ok, scratch, scratch_bytes, s);
+  return launch_epi<FASTAV_EPI_SWIGLU>(g, big_ok, scratch, scratch_bytes, s);
 }
 
 }  // namespace fastav

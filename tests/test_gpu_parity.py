@@ -149,7 +149,11 @@ def test_rope_with_original_positions(dtype, dh, base):
 # ------------------------------------------------------------------------------------ linear layers
 LINEAR_SHAPES = [("f32", 100, 688, 256), ("f32", 37, 256, 688), ("bf16", 100, 200, 72),
                  ("bf16", 300, 1024, 512), ("bf16", 1205, 512, 1024), ("bf16", 257, 6144, 4096), ("bf16", 129, 3584, 1024),
-                 ("bf16", 2100, 6144, 256), ("bf16", 4000, 2048, 192)]
+                 ("bf16", 2100, 6144, 256), ("bf16", 4000, 2048, 192),
+                 ("bf16", 1205, 4096, 2048),      # < 1 round of big tiles: split-K for the residual epilogue
+                 ("bf16", 2458, 2048, 1536),      # 80 big tiles -> split 3
+                 ("bf16", 3000, 8192, 256),       # 384 big tiles = 1.5 rounds: big tiles + small-tile tail columns
+                 ("bf16", 1721, 2816, 320)]       # 77 tiles; SwiGLU has 154
 
 
 @pytest.mark.parametrize("dtype,M,N,K", LINEAR_SHAPES)
