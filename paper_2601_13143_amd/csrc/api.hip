@@ -202,7 +202,7 @@ static Workspace carve(const fastav_model_t& m, int64_t T, int B) {
   w.attn[0] = take((size_t)T * qd * es);
   w.attn[1] = take((size_t)T * qd * es);
   w.hmlp = take((size_t)T * m.mlp_dim * es);
-  w.logits = take((size_t)FASTAV_MAX_N_LAST * m.n_q_heads * T * 4);
+  w.logits = take(score_logits_bytes(m.n_q_heads, T, FASTAV_MAX_N_LAST));
   w.ml = take((size_t)B * FASTAV_MAX_N_LAST * m.n_q_heads * 2 * 4);
   w.partials = take(score_partials_bytes(m.n_q_heads, T, B, FASTAV_MAX_N_LAST));
   w.scores = take((size_t)T * 4);
@@ -452,7 +452,7 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
 
 size_t fastav_score_workspace_bytes(int32_t n_q_heads, int64_t total_tokens, int32_t batch, int32_t n_last) {
   if (n_q_heads < 1 || total_tokens < 0 || batch < 1 || n_last < 1) return 0;
-  return align_up((size_t)n_last * n_q_heads * total_tokens * 4, 256) +
+  return align_up(score_logits_bytes(n_q_heads, total_tokens, n_last), 256) +
          align_up(score_partials_bytes(n_q_heads, total_tokens, batch, n_last), 256);
 }
 
@@ -472,7 +472,7 @@ fastav_status_t fastav_score(const fastav_model_t* model, const void* q, int64_t
   const size_t need = fastav_score_workspace_bytes(model->n_q_heads, total_tokens, batch, n_last);
   if (workspace_bytes < need) return fail(FASTAV_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
   float* logits = (float*)workspace;
-  float* partials = (float*)((char*)workspace + align_up((size_t)n_last * model->n_q_heads * total_tokens * 4, 256));
+  float* partials = (float*)((char*)workspace + align_up(score_logits_bytes(model->n_q_heads, total_tokens, n_last), 256));
   hipStream_t s = (hipStream_t)stream;
   FASTAV_TRY(launch_score_logits(q, q_row_stride, k, k_row_stride, cu_seqlens_dev, batch, total_tokens, max_seqlen,
                                  model->n_q_heads, model->n_kv_heads, model->head_dim, n_last, logits, partials,

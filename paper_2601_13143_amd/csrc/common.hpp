@@ -81,6 +81,7 @@ fastav_status_t launch_attention(const void* q, int64_t q_stride, const void* k,
 
 // Eq. 4.  logits [n_last, Hq, T] fp32, ml [batch, n_last, Hq, 2] fp32.
 size_t score_partials_bytes(int Hq, int64_t T, int batch, int n_last);
+size_t score_logits_bytes(int Hq, int64_t T, int n_last);   // logits buffer handed to launch_score_logits
 fastav_status_t launch_score_logits(const void* q, int64_t q_stride, const void* k, int64_t k_stride,
                                     const int32_t* cu, int batch, int64_t T, int max_seqlen, int Hq, int Hkv, int dh,
                                     int n_last, float* logits, float* partials, int dtype, hipStream_t s);

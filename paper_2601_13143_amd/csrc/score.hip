@@ -126,6 +126,124 @@ __global__ __launch_bounds__(256) void k_score_logits(const T* __restrict__ q, i
   }
 }
 
+// bf16 variant on the matrix cores.  The contraction q . k over head_dim is dense, so it goes through
+// v_mfma_f32_16x16x32_bf16 with 16 keys as the M side and the query rows (heads of one KV group x last
+// rows, padded to 16) as the N side; K fragments are loaded from HBM straight into the MFMA operand layout
+// (lane = key, 16 bytes of head_dim each: every byte of K is fetched once, by one lane, and used once), so
+// there is no LDS staging, no cross-lane reduction and no workgroup barrier.  In the result a lane owns ONE
+// query row and four consecutive keys: it scales, masks, stores them and keeps a running (max, sum-exp)
+// for its row.  The matrix cores run mostly on padding here (4 of 16 columns at GQA 4:1); that costs
+// nothing next to the HBM stream this kernel is bound by.
+// Wave w of workgroup (x, b, z) handles KV head w + 4 z over kScoreChunk keys of sample b.
+template <int DH, int NBMAX>
+__global__ __launch_bounds__(256) void k_score_logits_mfma(const bf16_t* __restrict__ q, int64_t q_stride,
+                                                           const bf16_t* __restrict__ k, int64_t k_stride,
+                                                           const int32_t* __restrict__ cu, int Hq, int Hkv, int n_last,
+                                                           float scale, int64_t T_total, int64_t n_chunk_slots,
+                                                           float* __restrict__ logits, float* __restrict__ partials) {
+  constexpr int NSTEP = DH / 32;             // MFMA k-steps of 32
+  constexpr int KG = kScoreChunk / 16;       // key groups of 16 per chunk
+  // NBMAX: query-row batches of 16 this instantiation can hold (G * n_rows <= 16 * NBMAX)
+  const int b = blockIdx.y;
+  const int row0 = cu[b], n = cu[b + 1] - row0;
+  const int j0 = blockIdx.x * kScoreChunk;
+  if (j0 >= n) return;
+  const int g = threadIdx.x / 64 + 4 * (int)blockIdx.z;
+  if (g >= Hkv) return;                      // no barriers below, so a wave may simply leave
+  const int n_rows = n_last < n ? n_last : n;
+  const int G = Hq / Hkv;
+  const int R = G * n_rows;                  // query rows per KV head: index m = rl * G + hq
+  const int NB = (R + 15) / 16;
+  const int lane = threadIdx.x & 63;
+  const int l16 = lane & 15, l4 = lane >> 4;
+  const bool full_chunk = j0 + kScoreChunk <= n;
+  const bool vec_ok = full_chunk && ((row0 & 3) == 0) && ((T_total & 3) == 0);   // 16-byte aligned rows of 4 keys
+
+  // B operands: lane holds query row m = rb*16 + l16, head_dim chunk l4 of every k-step.  The same lane
+  // receives that query row's column of the result.
+  bf16x8_t qb[NBMAX][NSTEP];
+  int rr[NBMAX];                             // in-sample position of the query row, -1 for padding
+  float* dst[NBMAX];                         // &logits[rl][head][row0]
+  float mrun[NBMAX], lrun[NBMAX];
+#pragma unroll
+  for (int rb = 0; rb < NBMAX; ++rb) {
+    const int mrow = rb * 16 + l16;
+    const bool ok = (NBMAX == 1 || rb < NB) && mrow < R;
+    const int rl = ok ? mrow / G : 0, hq = ok ? mrow % G : 0;
+    rr[rb] = ok ? n - n_rows + rl : -1;
+    dst[rb] = logits + ((int64_t)rl * Hq + g * G + hq) * T_total + row0;
+    mrun[rb] = -INFINITY; lrun[rb] = 0.f;
+    const bf16_t* qp = q + (int64_t)(row0 + n - n_rows + rl) * q_stride + (g * G + hq) * DH + l4 * 8;
+#pragma unroll
+    for (int st = 0; st < NSTEP; ++st) {
+      bf16x8_t v = *(const bf16x8_t*)(qp + st * 32);
+      if (!ok) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (bf16_t)0.f;
+      }
+      qb[rb][st] = v;
+    }
+  }
+
+#pragma unroll 2
+  for (int kg = 0; kg < KG; ++kg) {
+    // A operand: lane = key l16 of the group, head_dim chunk l4
+    const int akey = j0 + kg * 16 + l16;
+    const int kr = akey < n ? akey : n - 1;
+    const bf16_t* kp = k + (int64_t)(row0 + kr) * k_stride + g * DH + l4 * 8;
+    bf16x8_t ka[NSTEP];
+#pragma unroll
+    for (int st = 0; st < NSTEP; ++st) ka[st] = *(const bf16x8_t*)(kp + st * 32);
+    const int key0 = j0 + kg * 16 + l4 * 4;  // result rows of this lane: keys key0 .. key0+3
+#pragma unroll
+    for (int rb = 0; rb < NBMAX; ++rb) {
+      if (NBMAX == 1 || rb < NB) {
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int st = 0; st < NSTEP; ++st) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[st], qb[rb][st], acc, 0, 0, 0);
+        float x[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) x[r] = (key0 + r <= rr[rb]) ? acc[r] * scale : -INFINITY;   // visible: key <= row < n
+        if (rr[rb] >= 0) {
+          if (vec_ok) {
+            f32x4_t xv = {x[0], x[1], x[2], x[3]};
+            *(f32x4_t*)(dst[rb] + key0) = xv;
+          } else if (full_chunk) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dst[rb][key0 + r] = x[r];
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) if (key0 + r < n) dst[rb][key0 + r] = x[r];
+          }
+        }
+        const float mn = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), mrun[rb]);
+        const float ms = (mn == -INFINITY) ? 0.f : mn;
+        lrun[rb] = lrun[rb] * __expf(mrun[rb] - ms) + (__expf(x[0] - ms) + __expf(x[1] - ms)) + (__expf(x[2] - ms) + __expf(x[3] - ms));
+        mrun[rb] = mn;
+      }
+    }
+  }
+  // merge the four lanes that hold the same query row (different keys); lanes 0..15 write the chunk partial
+#pragma unroll
+  for (int rb = 0; rb < NBMAX; ++rb) {
+    float m1 = mrun[rb], l1 = lrun[rb];
+#pragma unroll
+    for (int o = 16; o <= 32; o <<= 1) {
+      const float m2 = __shfl_xor(m1, o, kWave), l2 = __shfl_xor(l1, o, kWave);
+      const float mn = fmaxf(m1, m2);
+      const float ms = (mn == -INFINITY) ? 0.f : mn;
+      l1 = l1 * __expf(m1 - ms) + l2 * __expf(m2 - ms);
+      m1 = mn;
+    }
+    const int mrow = rb * 16 + l16;
+    if (l4 == 0 && rr[rb] >= 0) {
+      const int rl = mrow / G, hq = mrow % G;
+      float* p = partials + (((int64_t)rl * Hq + g * G + hq) * n_chunk_slots + row0 / kScoreChunk + b + blockIdx.x) * 2;
+      p[0] = m1; p[1] = l1;
+    }
+  }
+}
+
 // ml_in != nullptr: per-head (m, l) given as [batch, n_last, Hq, 2]; else merged here from partials.
 __global__ __launch_bounds__(256) void k_score_finalize(const float* __restrict__ logits,
                                                         const float* __restrict__ ml_in,
@@ -137,21 +255,27 @@ __global__ __launch_bounds__(256) void k_score_finalize(const float* __restrict_
   const int row0 = cu[b], n = cu[b + 1] - row0;
   if ((int)(blockIdx.x * 256) >= n) return;
   const int n_rows = n_last < n ? n_last : n;
-  for (int idx = threadIdx.x; idx < n_rows * Hq; idx += 256) {
-    const int rl = idx / Hq, h = idx % Hq;
-    float m, l;
-    if (ml_in) {
+  if (ml_in) {
+    for (int idx = threadIdx.x; idx < n_rows * Hq; idx += 256) {
+      const int rl = idx / Hq, h = idx % Hq;
       const float* p = ml_in + (((int64_t)b * n_last + rl) * Hq + h) * 2;
-      m = p[0]; l = p[1];
-    } else {
-      const float* p = partials + (((int64_t)rl * Hq + h) * n_chunk_slots + row0 / kScoreChunk + b) * 2;
-      const int nc = (n + kScoreChunk - 1) / kScoreChunk;
-      m = -INFINITY;
-      for (int c = 0; c < nc; ++c) m = fmaxf(m, p[2 * c]);
-      l = 0.f;
-      for (int c = 0; c < nc; ++c) { const float mc = p[2 * c]; if (mc > -INFINITY) l += p[2 * c + 1] * expf(mc - m); }
+      mls[2 * idx] = p[0]; mls[2 * idx + 1] = 1.0f / p[1];
     }
-    mls[2 * idx] = m; mls[2 * idx + 1] = 1.0f / l;
+  } else {
+    // merge the per-chunk (max, sum-exp) partials: one wave per (row, head), lanes strided over the chunks
+    const int nc = (n + kScoreChunk - 1) / kScoreChunk;
+    const int lane = threadIdx.x & 63;
+    for (int idx = threadIdx.x >> 6; idx < n_rows * Hq; idx += 4) {
+      const int rl = idx / Hq, h = idx % Hq;
+      const float* p = partials + (((int64_t)rl * Hq + h) * n_chunk_slots + row0 / kScoreChunk + b) * 2;
+      float m = -INFINITY;
+      for (int c = lane; c < nc; c += 64) m = fmaxf(m, p[2 * c]);
+      m = wave_max(m);
+      float l = 0.f;
+      for (int c = lane; c < nc; c += 64) { const float mc = p[2 * c]; if (mc > -INFINITY) l += p[2 * c + 1] * expf(mc - m); }
+      l = wave_sum(l);
+      if (lane == 0) { mls[2 * idx] = m; mls[2 * idx + 1] = 1.0f / l; }
+    }
   }
   __syncthreads();
   const int j = blockIdx.x * 256 + threadIdx.x;
@@ -166,6 +290,9 @@ __global__ __launch_bounds__(256) void k_score_finalize(const float* __restrict_
 
 // Chunk slots of the whole packed batch: sample b's chunks start at slot cu[b]/chunk + b.
 static int64_t chunk_slots(int64_t T, int batch) { return T / kScoreChunk + batch + 1; }
+
+// logits [n_last][Hq][T]
+size_t score_logits_bytes(int Hq, int64_t T, int n_last) { return (size_t)n_last * Hq * T * sizeof(float); }
 
 size_t score_partials_bytes(int Hq, int64_t T, int batch, int n_last) {
   return (size_t)n_last * Hq * chunk_slots(T, batch) * 2 * sizeof(float);
@@ -201,6 +328,18 @@ fastav_status_t launch_score_logits(const void* q, int64_t q_stride, const void*
   const int nsub = 256 / (dh / vec);
   const bool reg_ok = nsub >= Hkv;
   if (shmem > 64 * 1024) return fail(FASTAV_EUNSUPPORTED, "score: n_q_heads*(head_dim+128)*4 bytes must fit 64 KB of LDS");
+  if (dtype == FASTAV_BF16 && G * n_last <= 64 && q_stride % 8 == 0 && k_stride % 8 == 0 &&
+      (((uintptr_t)q | (uintptr_t)k) % 16) == 0) {
+    const dim3 grid_m(grid.x, grid.y, (unsigned)((Hkv + 3) / 4));
+#define FASTAV_SCORE_MFMA(DHH, NBB)                                                                                      \
+  hipLaunchKernelGGL((k_score_logits_mfma<DHH, NBB>), grid_m, dim3(256), 0, s, (const bf16_t*)q, q_stride, (const bf16_t*)k, \
+                     k_stride, cu, Hq, Hkv, n_last, scale, T, ncm, logits, partials)
+    const bool one = G * n_last <= 16;
+    if (dh == 128) { if (one) FASTAV_SCORE_MFMA(128, 1); else FASTAV_SCORE_MFMA(128, 4); }
+    else { if (one) FASTAV_SCORE_MFMA(64, 1); else FASTAV_SCORE_MFMA(64, 4); }
+#undef FASTAV_SCORE_MFMA
+    return check_launch("score_logits_mfma");
+  }
   if (dtype == FASTAV_BF16) {
     if (dh == 128) dispatch_logits<bf16_t, 128>(G, reg_ok, grid, shmem, s, (const bf16_t*)q, q_stride, (const bf16_t*)k, k_stride, cu, Hq, Hkv, n_last, scale, T, ncm, logits, partials);
     else dispatch_logits<bf16_t, 64>(G, reg_ok, grid, shmem, s, (const bf16_t*)q, q_stride, (const bf16_t*)k, k_stride, cu, Hq, Hkv, n_last, scale, T, ncm, logits, partials);
