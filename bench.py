@@ -28,6 +28,20 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 WORKLOADS = {"cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4, "cfg5": 5}
 
 
+def _recorded_traffic(workload):
+    """Bytes per launch of the gate/up GEMM from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE,
+    calibrated on a copy kernel); None when no summary exists for this workload.  A profiler cannot run inside
+    this process, so the figure is read back from profiles/."""
+    path = os.path.join(ROOT, "profiles", f"prefill_{workload}_pmc_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch_gemm_swiglu:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def _upload_weights(dec, m, seed, threads):
     import torch
 
@@ -82,6 +96,50 @@ def _cpu_baseline(w, threads):
     return {"value": w.total_tokens / total, "unit": "tokens/s", "cores": int(used), "kind": "oracle",
             "sample": f"fp64 NumPy oracle on a 4-layer surrogate (one layer per token count of the pruned schedule, "
                       f"{per_layer.sum():.1f} s measured), extrapolated to {m.n_layers} layers by layer counts {counts}"}
+
+
+def _prune_stress(fa, torch, model_struct, hq, hkv, dh, d):
+    """Score, select and gather on a batch large enough that bytes, not launch latency, set the time
+    (16 samples x 16384 tokens, 7B shapes): achieved GB/s of algorithmic bytes against the 8 TB/s peak."""
+    B, n = 16, 16384
+    T = B * n
+    cu = np.arange(B + 1, dtype=np.int32) * n
+    cu_dev = torch.from_numpy(cu).cuda()
+    g = torch.Generator(device="cuda").manual_seed(7)
+
+    def timeit(fn, iters=8):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e-3
+
+    q = torch.randn(T, hq, dh, device="cuda", generator=g).bfloat16()
+    k = torch.randn(T, hkv, dh, device="cuda", generator=g).bfloat16()
+    t_score = timeit(lambda: fa.fastav_score(model_struct, q, k, cu_dev, n, 1))
+    del q
+    scores = torch.rand(T, device="cuda", generator=g)
+    prot = (torch.rand(T, device="cuda", generator=g) < 0.05).to(torch.uint8)
+    kc = [int(0.7 * n)] * B
+    t_sel = timeit(lambda: fa.fastav_select_gather(scores, prot, cu, kc, []))
+    x = torch.randn(T, d, device="cuda", generator=g)
+    o = torch.randn(T, hq * dh, device="cuda", generator=g).bfloat16()
+    v = torch.randn(T, hkv * dh, device="cuda", generator=g).bfloat16()
+    pos = torch.arange(T, device="cuda", dtype=torch.int32)
+    tens = [x, o, k.view(T, hkv * dh), v, pos, prot]
+    t_all = timeit(lambda: fa.fastav_select_gather(scores, prot, cu, kc, tens), iters=4)
+    rows = sum(kc)
+    b_score = T * hkv * dh * 2 + 4 * T
+    b_sel = 5 * T + 4 * rows
+    b_gather = 2 * rows * (d * 4 + hq * dh * 2 + 2 * hkv * dh * 2 + 4 + 1) + 4 * rows
+    mk = lambda byt, t: {"us": t * 1e6, "achieved": byt / t / 1e9, "unit": "GB/s", "frac": byt / t / 1e9 / PEAK_HBM_GBS}
+    return {"shape": f"{B} samples x {n} tokens, Hq {hq}, Hkv {hkv}, head_dim {dh}, hidden {d}, keep 0.7",
+            "score": mk(b_score, t_score), "select": mk(b_sel, t_sel), "gather": mk(b_gather, t_all - t_sel)}
 
 
 def main():
@@ -169,6 +227,10 @@ def main():
     ms, n, wk = fa.fastav_profile_collect(dominant)
     achieved = wk / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
 
+    stress = None
+    if not args.no_kernel_passes and m.dtype == "bf16":
+        stress = _prune_stress(fa, torch, dec.model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.hidden)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = _cpu_baseline(w, host_threads)
@@ -186,9 +248,10 @@ def main():
         "pruned_over_unpruned": s_plain / s_pruned,
         "prune_steps_us_per_prefill": prune_us,
         "roofline": {"kernel": "k_gemm_mfma<SwiGLU> (gate/up projection)", "bound": "mfma", "achieved": achieved,
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": _recorded_traffic(args.workload),
                      "launches": n, "avg_launch_us": 1e3 * ms / max(n, 1)},
         "kernels": kernels,
+        "prune_kernels_stress": stress,
         "cpu_baseline": cpu,
         "setup_s": setup_s,
     }

@@ -2,8 +2,8 @@
 // with the last-query logits of Eq. 4 as a side output.
 //
 // One workgroup = 128 query rows of one head of one sample; each of its 4 waves owns 32 rows.  K/V tiles
-// of 64 keys are fetched with 16-byte loads into registers one tile ahead of the math and parked in one
-// of two LDS stages, both row-major [key][d] and XOR-swizzled so that the operand reads spread over all 64
+// of 64 keys are copied HBM/L2 -> LDS asynchronously (global_load_lds_dwordx4) one tile ahead of the math
+// into one of two LDS stages, both row-major [key][d] and XOR-swizzled so that the operand reads spread over all 64
 // LDS banks (K: 32 keys x one 16-byte chunk per MFMA operand; V: 4 keys x 32 bytes per 16 lanes of the
 // transposing read below).  The products are formed transposed,
 //     S^T = K Q^T   and   O^T = V^T P^T   (v_mfma_f32_32x32x16_bf16),
@@ -35,6 +35,12 @@ struct AttnArgs {
 
 typedef __attribute__((address_space(3))) bf16x4_t* lds_bf16x4_ptr;
 
+// Asynchronous 16-byte global -> LDS copy (no VGPR staging, no ds_write); lane l's data lands at
+// lds_byte_addr + 16 l.  Completion is tracked by vmcnt.
+__device__ __forceinline__ void attn_dma16(const void* gptr, uint32_t lds_byte_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_byte_addr) : "memory");
+}
+
 template <int DH>
 __global__ __launch_bounds__(256, 2) void k_attn_mfma(AttnArgs a) {
   constexpr int BQ = 128, BKV = 64;
@@ -49,8 +55,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(AttnArgs a) {
   //      eight pieces fall in eight distinct 32-byte slots.
   auto kswz = [](int key, int c) { return DH == 128 ? (c ^ (key & 15)) : (c ^ ((key >> 1) & 7)); };
   auto vswz = [](int key, int c) { return DH == 128 ? (c ^ ((key & 3) << 2)) : (c ^ ((key & 2) << 1)); };
-  __shared__ bf16x8_t Ks[2][BKV * DCH];
-  __shared__ bf16x8_t Vs[2][BKV * DCH];
+  extern __shared__ bf16x8_t attn_lds[];            // K stages then V stages: [2][BKV*DCH] each
+  bf16x8_t (*Ks)[BKV * DCH] = (bf16x8_t (*)[BKV * DCH])attn_lds;
+  bf16x8_t (*Vs)[BKV * DCH] = (bf16x8_t (*)[BKV * DCH])(attn_lds + 2 * BKV * DCH);
 
   int v = blockIdx.x;
   {
@@ -91,35 +98,31 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(AttnArgs a) {
   const bf16_t* kbase = a.k + (int64_t)row0 * a.kvs + g * DH;
   const bf16_t* vbase = a.v + (int64_t)row0 * a.kvs + g * DH;
 
-  // this thread's share of a tile: chunks idx = tid + 256 i -> (key, c)
-  bf16x8_t kreg[NLD], vreg[NLD];
-  auto fetch = [&](int j0) {
+  // Tile copies: a copy instruction fills 1 KB of LDS = RPI consecutive tile rows; wave w issues the groups
+  // w, w+4, ...  The XOR swizzles are applied on the global side: the lane that fills slot p of row `key`
+  // fetches the logical chunk that belongs there.  Rows past the sample are clamped to its last row (their
+  // probabilities are exactly 0 after masking, so they only need to be finite).
+  constexpr int RPI = 64 / DCH;                      // tile rows per copy instruction
+  constexpr int NCP = BKV / RPI / 4;                 // copy instructions per wave, per tile, for K and for V each
+  const uint32_t k_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)attn_lds;
+  const uint32_t v_lds = k_lds + 2u * BKV * DCH * 16u;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int cp_row = lane / DCH, cp_pos = lane % DCH;
+  auto fetch = [&](int j0, int st) {
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int idx = tid + 256 * i;
-      const int key = idx / DCH, c = idx % DCH;
-      const bool ok = j0 + key < n;
-      const int jr = ok ? j0 + key : n - 1;
-      kreg[i] = *(const bf16x8_t*)(kbase + (int64_t)jr * a.kvs + c * 8);
-      bf16x8_t vv = *(const bf16x8_t*)(vbase + (int64_t)jr * a.kvs + c * 8);
-      if (!ok) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) vv[e] = (bf16_t)0.f;          // masked keys must not inject NaN/Inf through 0 * x
-      }
-      vreg[i] = vv;
+    for (int i = 0; i < NCP; ++i) {
+      const int r0 = (i * 4 + wave_u) * RPI;
+      const int key = r0 + cp_row;
+      const int jr = (j0 + key < n) ? j0 + key : n - 1;
+      const uint32_t dst = (uint32_t)(st * BKV * DCH + r0 * DCH) * 16u;
+      // kswz / vswz are involutions in the chunk index
+      attn_dma16(kbase + (int64_t)jr * a.kvs + kswz(key, cp_pos) * 8, k_lds + dst);
+      attn_dma16(vbase + (int64_t)jr * a.kvs + vswz(key, cp_pos) * 8, v_lds + dst);
     }
   };
-  auto park = [&](int st) {
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int idx = tid + 256 * i;
-      const int key = idx / DCH, c = idx % DCH;
-      Ks[st][key * DCH + kswz(key, c)] = kreg[i];
-      Vs[st][key * DCH + vswz(key, c)] = vreg[i];
-    }
-  };
-  fetch(0);
-  park(0);
+  auto fetch_wait = [&]() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); };
+  fetch(0, 0);
+  fetch_wait();
   __syncthreads();
 
   // this lane's part of a transposing V read: 16 lanes cover 4 keys x 16 dims (two chunks)
@@ -130,7 +133,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(AttnArgs a) {
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = t * BKV;
     const int st = t & 1;
-    if (t + 1 < n_tiles) fetch(j0 + BKV);
+    if (t + 1 < n_tiles) fetch(j0 + BKV, st ^ 1);           // stage st^1 was last read before the previous barrier
 
     if (wave_live && j0 <= qw0 + 31) {                            // else nothing visible to this wave in this tile
       // ---- S^T = K Q^T : s[kb][r] is (key j0 + 32kb + (r/4)*8 + hf*4 + r%4, query qi)
@@ -158,6 +161,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(AttnArgs a) {
             if (emit && key <= qi) a.last_logits[(int64_t)h * a.T + row0 + key] = s[kb][r] * a.scale;
           }
       }
+      // max over the raw products (the scale is positive); masked entries become -inf
       float mx = -INFINITY;
       if ((j0 + BKV - 1 > qw0) || (j0 + BKV > n)) {                // diagonal or ragged tile: mask (wave-uniform test)
 #pragma unroll
@@ -165,36 +169,32 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(AttnArgs a) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int key = j0 + kb * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
-            float val = s[kb][r] * a.scale_log2;
-            if (!(key <= qi && key < n)) val = -INFINITY;
-            s[kb][r] = val;
-            mx = fmaxf(mx, val);
+            if (!(key <= qi && key < n)) s[kb][r] = -INFINITY;
+            mx = fmaxf(mx, s[kb][r]);
           }
       } else {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float val = s[kb][r] * a.scale_log2;
-            s[kb][r] = val;
-            mx = fmaxf(mx, val);
-          }
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
       }
       mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-      const float m_new = fmaxf(m, mx);
+      const float m_new = fmaxf(m, mx * a.scale_log2);            // running max in the log2 domain
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m - m_use);
-      l *= alpha;
+      if (__ballot(m_new > m) != 0) {                              // rescale only when some row's max moved
+        const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+        l *= alpha;
 #pragma unroll
-      for (int d = 0; d < NDB; ++d)
+        for (int d = 0; d < NDB; ++d)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+          for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+      }
       bf16x8_t pb[2][2];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(s[kb][r] - m_use);
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[kb][r], a.scale_log2, -m_use));   // exp2(-inf) = 0 for masked keys
           l += p;
           pb[kb][r >> 3][r & 7] = (bf16_t)p;
         }
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(AttnArgs a) {
         }
     }
 
-    if (t + 1 < n_tiles) park(st ^ 1);
+    fetch_wait();
     __syncthreads();
   }
 
@@ -268,8 +268,9 @@ fastav_status_t launch_attention_mfma(const void* q, int64_t q_stride, const voi
   a.scale = 1.0f / sqrtf((float)dh);
   a.scale_log2 = a.scale * 1.4426950408889634f;
   a.T = T; a.last_logits = last_logits; a.last_ml = last_ml;
-  if (dh == 128) hipLaunchKernelGGL(k_attn_mfma<128>, dim3((unsigned)blocks), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(k_attn_mfma<64>, dim3((unsigned)blocks), dim3(256), 0, s, a);
+  // two stages of a 64-key K tile and V tile
+  if (dh == 128) hipLaunchKernelGGL(k_attn_mfma<128>, dim3((unsigned)blocks), dim3(256), 4 * 64 * 128 * 2, s, a);
+  else hipLaunchKernelGGL(k_attn_mfma<64>, dim3((unsigned)blocks), dim3(256), 4 * 64 * 64 * 2, s, a);
   return check_launch("attention_mfma");
 }
 
