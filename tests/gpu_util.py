@@ -66,3 +66,24 @@ def make_decoder(m: fi.Model, weights):
 
 def prune_tuples(w: fi.Workload):
     return [(p.layer, p.kind, p.keep_ratio) for p in w.prunes]
+
+
+def make_decoder_streamed(m: fi.Model, seed: int, threads: int = 8):
+    """Full-size models: generate each layer's seeded weights on host threads and upload it at once, so that
+    only a few layers of fp32 host copies are alive at any time."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    dec = fa.Decoder(model_struct(m))
+
+    def gen(l):
+        W = fi.layer_weights(m, l, seed)
+        return l, {k: (fi.bf16_bits(v) if m.dtype == "bf16" else v) for k, v in W.items()}
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        for l, W in ex.map(gen, range(m.n_layers)):
+            d = {}
+            for k, v in W.items():
+                t = torch.from_numpy(v).cuda()
+                d[k] = t.view(torch.bfloat16) if m.dtype == "bf16" else t
+            dec.fastav_set_weights(l, d)
+    return dec

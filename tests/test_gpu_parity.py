@@ -3,6 +3,8 @@
 Integer / index work (selection, compaction) must match bit for bit; floating-point stages stay within the
 tolerances in gpu_util (bf16: max-abs 2e-2, relative L2 1e-2 on O(1)-scale outputs).  End-to-end kept sets
 may differ only on tokens whose oracle score lies within 1e-3 of the k-th score."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -10,7 +12,8 @@ import torch
 import fastav_inputs as fi
 from oracle import fastav_oracle as orc
 import paper_2601_13143_amd as fa
-from gpu_util import (TIE_BAND, assert_close, dev, host, make_decoder, model_struct, prune_tuples, rel_l2)
+from gpu_util import (TIE_BAND, assert_close, dev, host, make_decoder, make_decoder_streamed, model_struct, prune_tuples,
+                      rel_l2)
 
 pytestmark = pytest.mark.gpu
 
@@ -287,6 +290,9 @@ def _check_prefill(w: fi.Workload, out, ref, x_scale_from_ref=True):
         common, gi, ri = np.intersect1d(mine_pos, r["kept_pos"], return_indices=True)
         assert len(common) >= len(mine_pos) - stats["flipped"]
         gx, rx = x_out[got_cu[b]:got_cu[b + 1]][gi], r["x_out"][ri]
+        have = np.isfinite(rx).all(axis=1)      # a stored oracle result holds a sample of the rows only
+        gx, rx = gx[have], rx[have]
+        assert len(rx) > 0
         scale = float(np.sqrt(np.mean(rx ** 2)))
         stats[f"x_rel_l2_{b}"] = rel_l2(gx, rx)
         stats[f"x_max_abs_over_rms_{b}"] = float(np.max(np.abs(gx - rx))) / scale
@@ -382,3 +388,49 @@ def test_prefill_cfg2_7b_single_layer():
     common, gi, ri = np.intersect1d(out["kept_pos"].cpu().numpy(), ref[0]["kept_pos"], return_indices=True)
     assert_close(host(out["kv"][0][0])[gi], rk[ri], "bf16", scale=float(np.sqrt(np.mean(rk ** 2))), what="K")
     assert_close(host(out["kv"][0][1])[gi], rv[ri], "bf16", scale=float(np.sqrt(np.mean(rv ** 2))), what="V")
+
+
+# ------------------------------------------------------------------------ full-size configs vs stored oracle
+def _stored_oracle(cfg: int, w: fi.Workload):
+    """The fp64 oracle's results for a full-size config, written by tests/golden/make_goldens.py (which calls
+    the oracle only), in the shape _check_prefill reads: hidden states are NaN outside the stored rows."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", f"cfg{cfg}_oracle.npz")
+    if not os.path.exists(path):
+        pytest.skip(f"{os.path.basename(path)} has not been generated (python tests/golden/make_goldens.py {cfg})")
+    z = np.load(path)
+    ref = []
+    for b in range(len(w.samples)):
+        prunes = []
+        for i, p in enumerate(w.prunes):
+            pos_in, keep_pos = z[f"s{b}_p{i}_pos_in"], z[f"s{b}_p{i}_keep_pos"]
+            keep = np.searchsorted(pos_in, keep_pos)
+            assert np.array_equal(pos_in[keep], keep_pos)
+            prunes.append({"kind": p.kind, "n_in": len(pos_in), "k": len(keep_pos), "keep": keep, "pos_in": pos_in,
+                           "scores": z[f"s{b}_p{i}_scores"] if f"s{b}_p{i}_scores" in z else None})
+        kept = z[f"s{b}_kept_pos"]
+        x = np.full((len(kept), w.model.hidden), np.nan)
+        x[z[f"s{b}_x_rows"]] = z[f"s{b}_x_out"]
+        ref.append({"prunes": prunes, "kept_pos": kept, "x_out": x, "x_rms": float(z[f"s{b}_x_rms"])})
+    return ref
+
+
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_prefill_full_size_against_stored_oracle(cfg):
+    """The benchmark configurations at their full sizes, launched as bench.py launches them: kept sets, surviving
+    positions and a sample of final hidden-state rows against the stored fp64 oracle results."""
+    w = fi.config(cfg)
+    ref = _stored_oracle(cfg, w)
+    print(f"cfg{cfg}: generating and uploading {w.model.n_layers} layers", flush=True)
+    dec = make_decoder_streamed(w.model, w.weight_seed)
+    spans, offs = fi.span_table(w)
+    x = dev(fi.embeddings(w), w.model.dtype)
+    print(f"cfg{cfg}: prefill of {sum(w.seqlens)} tokens", flush=True)
+    out = dec.fastav_prefill(x, fi.cu_seqlens(w), spans, offs, prune_tuples(w), w.n_last, want_kv=False, want_trace=True)
+    torch.cuda.synchronize()
+    st = _check_prefill(w, out, ref)
+    print(f"cfg{cfg}: {st}", flush=True)
+    for b in range(len(w.samples)):
+        # 28-32 bf16 layers against fp64: the error of a deep stack, not of one stage
+        assert st[f"x_rel_l2_{b}"] <= 3e-2 and st[f"x_max_abs_over_rms_{b}"] <= 0.25, st
+    del dec
+    torch.cuda.empty_cache()
