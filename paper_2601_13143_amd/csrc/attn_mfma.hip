@@ -17,8 +17,9 @@
 // The lane whose query is the last row of a sample also writes that row's scaled logits for every key
 // and its final (max, sum): the fine-prune score is finalised from those without a second pass over K.
 //
-// Workgroup ids are re-dealt so that each XCD owns a contiguous run of (head, tile) pairs: the query heads
-// that share a KV head then share an L2.  Inside a head the longest (last) query tiles run first.
+// A workgroup processes query tiles i and last - i one after the other, which gives every workgroup of a
+// sample the same number of key tiles.  Workgroup ids are re-dealt so that each XCD owns a contiguous run of
+// heads: the query heads that share a KV head then share an L2.
 #include "common.hpp"
 
 namespace fastav {
@@ -27,7 +28,7 @@ struct AttnArgs {
   const bf16_t* q; const bf16_t* k; const bf16_t* v; bf16_t* o;
   int64_t qs, kvs, os;                 // row strides in elements
   const int32_t* cu;
-  int Hq, Hkv, n_qtiles, n_blocks;
+  int Hq, Hkv, n_qtiles, n_pairs;
   float scale, scale_log2;             // 1/sqrt(dh) and the same times log2(e)
   int64_t T;
   float* last_logits; float* last_ml;
@@ -59,20 +60,33 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(AttnArgs a) {
   bf16x8_t (*Ks)[BKV * DCH] = (bf16x8_t (*)[BKV * DCH])attn_lds;
   bf16x8_t (*Vs)[BKV * DCH] = (bf16x8_t (*)[BKV * DCH])(attn_lds + 2 * BKV * DCH);
 
-  int v = blockIdx.x;
-  {
-    const int per = a.n_blocks / 8, rem = a.n_blocks % 8, xcd = v % 8, idx = v / 8;
-    v = xcd * per + (xcd < rem ? xcd : rem) + idx;
+  // Work item = one (sample, head) pair x one PAIR of query tiles (i, last - i): under the causal mask tile i
+  // sees i + 1 tiles' worth of keys, so every item of a sample carries the same amount of work and a launch
+  // has no long tail.  When the (sample, head) pairs divide evenly over the 8 XCDs (block id % 8 is the XCD),
+  // each XCD owns a contiguous run of them: the query heads of one KV head share an L2.
+  const int v = blockIdx.x;
+  int pair, item;
+  if (a.n_pairs % 8 == 0) {
+    const int per = a.n_pairs / 8, xcd = v % 8, idx = v / 8;
+    pair = xcd * per + idx % per;
+    item = idx / per;
+  } else {
+    pair = v % a.n_pairs;
+    item = v / a.n_pairs;
   }
-  const int qt = a.n_qtiles - 1 - v % a.n_qtiles;                 // longest tiles first
-  const int h = (v / a.n_qtiles) % a.Hq;
-  const int b = v / (a.n_qtiles * a.Hq);
+  const int h = pair % a.Hq;
+  const int b = pair / a.Hq;
   const int row0 = a.cu[b], n = a.cu[b + 1] - row0;
-  const int q0 = qt * BQ;
-  if (q0 >= n) return;
+  const int nq = (n + BQ - 1) / BQ;                               // this sample's query tiles
+  if (item >= (nq + 1) / 2) return;
   const int g = h / (a.Hq / a.Hkv);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hf = lane >> 5;
+#pragma nounroll
+  for (int part = 0; part < 2; ++part) {
+  const int qt = part == 0 ? nq - 1 - item : item;                // the long tile first
+  if (part == 1 && qt == nq - 1 - item) break;                    // odd count: the middle tile stands alone
+  const int q0 = qt * BQ;
   const int qw0 = q0 + 32 * wave;
   const int qi = qw0 + l32;                                       // this lane's query row (in-sample)
   const bool wave_live = qw0 < n;
@@ -245,6 +259,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(AttnArgs a) {
       a.last_ml[((int64_t)b * a.Hq + h) * 2 + 1] = l_tot;
     }
   }
+  }  // part
 }
 
 bool mfma_attention_supported(int dh, int dtype, int64_t q_stride, int64_t kv_stride, int64_t o_stride) {
@@ -262,9 +277,9 @@ fastav_status_t launch_attention_mfma(const void* q, int64_t q_stride, const voi
   a.q = (const bf16_t*)q; a.k = (const bf16_t*)k; a.v = (const bf16_t*)v; a.o = (bf16_t*)o;
   a.qs = q_stride; a.kvs = kv_stride; a.os = o_stride; a.cu = cu; a.Hq = Hq; a.Hkv = Hkv;
   a.n_qtiles = (max_seqlen + 127) / 128;
-  const int64_t blocks = (int64_t)a.n_qtiles * Hq * batch;
+  a.n_pairs = Hq * batch;
+  const int64_t blocks = (int64_t)((a.n_qtiles + 1) / 2) * a.n_pairs;       // balanced pairs of query tiles
   if (blocks > 0x7FFFFFFF) return fail(FASTAV_EUNSUPPORTED, "attention: too many workgroups");
-  a.n_blocks = (int)blocks;
   a.scale = 1.0f / sqrtf((float)dh);
   a.scale_log2 = a.scale * 1.4426950408889634f;
   a.T = T; a.last_logits = last_logits; a.last_ml = last_ml;
