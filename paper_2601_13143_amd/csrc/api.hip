@@ -40,7 +40,7 @@ fastav_status_t launch_attention_generic(const void* q, int64_t q_stride, const 
                                          int64_t kv_stride, void* o, int64_t o_stride, const int32_t* cu, int batch,
                                          int64_t T, int max_seqlen, int Hq, int Hkv, int dh, float* last_logits,
                                          float* last_ml, int dtype, hipStream_t s);
-bool mfma_attention_supported(int dh, int dtype, int64_t q_stride, int64_t kv_stride, int64_t o_stride);
+bool mfma_attention_supported(int dh, int dtype, int64_t q_stride, int64_t kv_stride, int64_t o_stride, int max_seqlen);
 fastav_status_t launch_attention_mfma(const void* q, int64_t q_stride, const void* k, const void* v,
                                       int64_t kv_stride, void* o, int64_t o_stride, const int32_t* cu, int batch,
                                       int64_t T, int max_seqlen, int Hq, int Hkv, int dh, float* last_logits,
@@ -82,7 +82,7 @@ fastav_status_t launch_attention(const void* q, int64_t q_stride, const void* k,
                                  int Hq, int Hkv, int dh, float* last_logits, float* last_ml, int dtype,
                                  double flops_hint, hipStream_t s) {
   ProfScope prof(FASTAV_PROF_ATTENTION, flops_hint, s);
-  if (mfma_attention_supported(dh, dtype, q_stride, kv_stride, o_stride))
+  if (mfma_attention_supported(dh, dtype, q_stride, kv_stride, o_stride, max_seqlen))
     return launch_attention_mfma(q, q_stride, k, v, kv_stride, o, o_stride, cu, batch, T, max_seqlen, Hq, Hkv, dh,
                                  last_logits, last_ml, s);
   return launch_attention_generic(q, q_stride, k, v, kv_stride, o, o_stride, cu, batch, T, max_seqlen, Hq, Hkv, dh,
