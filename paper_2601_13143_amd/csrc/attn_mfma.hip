@@ -18,8 +18,8 @@
 // and its final (max, sum): the fine-prune score is finalised from those without a second pass over K.
 //
 // A workgroup processes query tiles i and last - i one after the other, which gives every workgroup of a
-// sample the same number of key tiles.  Workgroup ids are re-dealt so that each XCD owns a contiguous run of
-// heads: the query heads that share a KV head then share an L2.
+// sample the same number of key tiles.  Workgroup ids are re-dealt so that the query heads that share a KV
+// head run on one XCD and share its L2.
 #include "common.hpp"
 
 namespace fastav {
@@ -74,13 +74,17 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(AttnArgs a) {
 
   // Work item = one (sample, head) pair x one PAIR of query tiles (i, last - i): under the causal mask tile i
   // sees i + 1 tiles' worth of keys, so every item of a sample carries the same amount of work and a launch
-  // has no long tail.  When the (sample, head) pairs divide evenly over the 8 XCDs (block id % 8 is the XCD),
-  // each XCD owns a contiguous run of them: the query heads of one KV head share an L2.
+  // has no long tail.  When the KV groups divide evenly over the 8 XCDs (block id % 8 is the XCD), the query
+  // heads of one KV head are placed on one XCD and share its L2.
   const int v = blockIdx.x;
   int pair, item;
-  if (a.n_pairs % 8 == 0) {
-    const int per = a.n_pairs / 8, xcd = v % 8, idx = v / 8;
-    pair = xcd * per + idx % per;
+  const int G = a.Hq / a.Hkv, n_groups = a.n_pairs / G;
+  if (n_groups % 8 == 0) {
+    // KV groups are dealt round-robin over the XCDs, so a batch of samples of different lengths loads them
+    // evenly; the G query heads of a group stay together
+    const int per = (n_groups / 8) * G, xcd = v % 8, idx = v / 8;
+    const int pl = idx % per;
+    pair = (xcd + 8 * (pl / G)) * G + pl % G;
     item = idx / per;
   } else {
     pair = v % a.n_pairs;
@@ -92,7 +96,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_mfma(AttnArgs a) {
   const int n = __builtin_amdgcn_readfirstlane(a.cu[b + 1]) - row0;
   const int nq = (n + BQ - 1) / BQ;                               // this sample's query tiles
   if (item >= (nq + 1) / 2) return;
-  const int g = h / (a.Hq / a.Hkv);
+  const int g = h / G;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, so control flow stays scalar
   const int l32 = lane & 31, hf = lane >> 5;

@@ -38,12 +38,15 @@ struct GemmArgs {
   int64_t ldc;
   int M, N, K;             // N = output columns
   int tiles_m, tiles_n;
+  int band;                // tile columns per band of the tile order (1 = column-major)
   int n_off;               // first output column of this launch (a launch may cover a range of tile columns)
   int splits;              // split-K: blockIdx.y picks a K range and writes an fp32 partial tile to `partial`
   float* partial;          // [splits][M][N] fp32 (split-K only)
 };
 
+constexpr int kNumCUs = 256;
 constexpr int kEpiPartial = 100;   // internal epilogue: plain fp32 store of a split-K partial
+constexpr int kEpiResAtomic = 101; // internal epilogue: residual update through fire-and-forget hardware adds
 
 // Asynchronous 16-byte global -> LDS copy; lane l's data lands at lds_byte_addr + 16 l.  Completion is
 // tracked by vmcnt (copies complete in issue order).
@@ -79,7 +82,15 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_mfma(GemmArgs g) {
     const int per = nblk / 8, rem = nblk % 8, xcd = pid % 8, idx = pid / 8;
     pid = xcd * per + (xcd < rem ? xcd : rem) + idx;
   }
-  const int tile_m = pid % g.tiles_m, tile_n = pid / g.tiles_m;
+  // Tile order: bands of `band` tile columns, swept row by row.  With several rounds of tiles per launch the
+  // ~32 tiles an XCD works on at one time then form a block of about 8 x 4 tiles instead of 2 whole columns,
+  // which cuts the operand panels it streams through its L2 per round by a third or more.  A launch of a
+  // single round keeps whole columns (band = 1), which measured faster there.
+  const int kb = g.band;
+  const int band = pid / (kb * g.tiles_m);
+  const int bw = (g.tiles_n - band * kb < kb) ? g.tiles_n - band * kb : kb;   // columns in this band
+  const int inb = pid - band * kb * g.tiles_m;
+  const int tile_m = inb / bw, tile_n = band * kb + inb % bw;
   const int m0 = tile_m * BM;
   const int n0 = g.n_off + tile_n * OUT_BN;
 
@@ -226,6 +237,12 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_mfma(GemmArgs g) {
           if (row < g.M) {
             if (EPI == FASTAV_EPI_STORE) ((bf16_t*)g.C)[(int64_t)row * g.ldc + col] = (bf16_t)acc[i][j][r];
             else if (EPI == kEpiPartial) g.partial[((int64_t)blockIdx.y * g.M + row) * g.N + col] = acc[i][j][r];
+            else if (EPI == kEpiResAtomic) {
+              // Residual update as a fire-and-forget hardware add at the L2: no read round trip holds the
+              // wave, so the next tile's main loop on this CU overlaps the drain.  Each element receives
+              // exactly one addend per launch, so the result is that of a read-modify-write.
+              unsafeAtomicAdd(&((float*)g.C)[(int64_t)row * g.ldc + col], acc[i][j][r]);
+            }
             else ((float*)g.C)[(int64_t)row * g.ldc + col] += acc[i][j][r];
           }
         }
@@ -263,6 +280,7 @@ static fastav_status_t launch_cfg(GemmArgs g, int col0, int ncols, int splits, h
   g.tiles_n = ncols;
   g.n_off = col0 * OUT_BN;
   g.splits = splits;
+  g.band = (g.tiles_m * g.tiles_n > kNumCUs) ? 4 : 1;
   const size_t shmem = (size_t)4 * (BM + BN) * 4 * sizeof(bf16x8_t);
   if (shmem > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WM, WN, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
@@ -273,7 +291,18 @@ static fastav_status_t launch_cfg(GemmArgs g, int col0, int ncols, int splits, h
   return check_launch("gemm_mfma");
 }
 
-constexpr int kCUs = 256;
+constexpr int kCUs = kNumCUs;
+
+// 256 x 256 tiles.  A residual epilogue over several rounds of tiles uses the hardware-add form (it overlaps
+// with the next round); within a single round the plain read-modify-write drains sooner.
+template <int EPI>
+static fastav_status_t launch_big(const GemmArgs& g, int col0, int ncols, int64_t tiles, hipStream_t s) {
+  if constexpr (EPI == FASTAV_EPI_RESADD) {
+    if (tiles >= 2 * kCUs) return launch_cfg<256, 256, 2, 4, kEpiResAtomic>(g, col0, ncols, 1, s);
+  }
+  return launch_cfg<256, 256, 2, 4, EPI>(g, col0, ncols, 1, s);
+}
+
 constexpr size_t kSplitKScratchBytes = (size_t)2 * kCUs * 256 * 256 * sizeof(float);   // <= 512 partial tiles
 
 size_t mfma_linear_scratch_bytes() { return kSplitKScratchBytes; }
@@ -318,12 +347,12 @@ static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, void* scratch, size_
   if (tiles_big > kCUs && rem != 0 && rem <= kCUs / 4) {
     const int cols_full = (int)((tiles_big - rem) / tm);          // whole tile columns inside the full rounds
     if (cols_full > 0 && cols_full < tn) {
-      fastav_status_t st = launch_cfg<256, 256, 2, 4, EPI>(g, 0, cols_full, 1, s);
+      fastav_status_t st = launch_big<EPI>(g, 0, cols_full, tiles_big - rem, s);
       if (st != FASTAV_OK) return st;
       return launch_cfg<128, 128, 2, 2, EPI>(g, cols_full * 2, (tn - cols_full) * 2, 1, s);
     }
   }
-  return launch_cfg<256, 256, 2, 4, EPI>(g, 0, tn, 1, s);
+  return launch_big<EPI>(g, 0, tn, tiles_big, s);
 }
 
 fastav_status_t launch_linear_mfma(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
