@@ -107,39 +107,42 @@ def _prune_stress(fa, torch, model_struct, hq, hkv, dh, d):
     cu_dev = torch.from_numpy(cu).cuda()
     g = torch.Generator(device="cuda").manual_seed(7)
 
-    def timeit(fn, iters=8):
+    def timeit(fn, kind, iters=8):
+        """GPU time per call of one kernel kind, from the library's own HIP events around its launches (the
+        Python call around them also allocates outputs, which is not part of the kernels' time)."""
         for _ in range(2):
             fn()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
+        fa.fastav_profile_enable([kind])
+        ms0, n0, _ = fa.fastav_profile_collect(kind)
         for _ in range(iters):
             fn()
-        e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / iters * 1e-3
+        ms1, n1, _ = fa.fastav_profile_collect(kind)
+        fa.fastav_profile_enable([])
+        return (ms1 - ms0) / iters * 1e-3
 
     q = torch.randn(T, hq, dh, device="cuda", generator=g).bfloat16()
     k = torch.randn(T, hkv, dh, device="cuda", generator=g).bfloat16()
-    t_score = timeit(lambda: fa.fastav_score(model_struct, q, k, cu_dev, n, 1))
+    t_score = timeit(lambda: fa.fastav_score(model_struct, q, k, cu_dev, n, 1), "score")
     del q
     scores = torch.rand(T, device="cuda", generator=g)
     prot = (torch.rand(T, device="cuda", generator=g) < 0.05).to(torch.uint8)
     kc = [int(0.7 * n)] * B
-    t_sel = timeit(lambda: fa.fastav_select_gather(scores, prot, cu, kc, []))
+    t_sel = timeit(lambda: fa.fastav_select_gather(scores, prot, cu, kc, []), "select")
     x = torch.randn(T, d, device="cuda", generator=g)
     o = torch.randn(T, hq * dh, device="cuda", generator=g).bfloat16()
     v = torch.randn(T, hkv * dh, device="cuda", generator=g).bfloat16()
     pos = torch.arange(T, device="cuda", dtype=torch.int32)
     tens = [x, o, k.view(T, hkv * dh), v, pos, prot]
-    t_all = timeit(lambda: fa.fastav_select_gather(scores, prot, cu, kc, tens), iters=4)
+    t_gather = timeit(lambda: fa.fastav_select_gather(scores, prot, cu, kc, tens), "gather", iters=4)
     rows = sum(kc)
     b_score = T * hkv * dh * 2 + 4 * T
     b_sel = 5 * T + 4 * rows
     b_gather = 2 * rows * (d * 4 + hq * dh * 2 + 2 * hkv * dh * 2 + 4 + 1) + 4 * rows
     mk = lambda byt, t: {"us": t * 1e6, "achieved": byt / t / 1e9, "unit": "GB/s", "frac": byt / t / 1e9 / PEAK_HBM_GBS}
     return {"shape": f"{B} samples x {n} tokens, Hq {hq}, Hkv {hkv}, head_dim {dh}, hidden {d}, keep 0.7",
-            "score": mk(b_score, t_score), "select": mk(b_sel, t_sel), "gather": mk(b_gather, t_all - t_sel)}
+            "score": mk(b_score, t_score), "select": mk(b_sel, t_sel), "gather": mk(b_gather, t_gather)}
 
 
 def main():
@@ -148,6 +151,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS))
+    ap.add_argument("--paper-schedule", action="store_true",
+                    help="prune as the paper does: global at the middle layer, then 20 %% fine at every later layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-passes", action="store_true", help="skip the per-kernel timing passes")
     args = ap.parse_args()
@@ -162,6 +167,8 @@ def main():
     fa.lib()
     host_threads = len(os.sched_getaffinity(0))
     w = fi.config(WORKLOADS[args.workload])
+    if args.paper_schedule:
+        w = fi.paper_schedule(w, global_keep=w.prunes[0].keep_ratio if w.prunes else 0.6)
     m = w.model
     dec = fa.Decoder(fa.make_model(m.n_layers, m.hidden, m.n_q_heads, m.n_kv_heads, m.head_dim, m.mlp_dim, m.rope_base,
                                    m.rms_eps, fa.BF16 if m.dtype == "bf16" else fa.F32))
@@ -183,22 +190,29 @@ def main():
         return o
 
     def timed(pr, steps, warmup):
+        """-> (wall seconds per step over exactly `steps` steps, per-step GPU times in ms from events on the
+        launch stream)."""
         o = run(pr, warmup)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         torch.cuda.synchronize()
         t = time.perf_counter()
-        run(pr, steps, o)
+        for i in range(steps):
+            ev[i].record()
+            o = dec.fastav_prefill(x, cu, spans, offs, pr, w.n_last, want_kv=True, outputs=o)
+        ev[steps].record()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t) / steps
+        wall = (time.perf_counter() - t) / steps
+        return wall, [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
 
     fa.fastav_profile_reset()
     fa.fastav_profile_enable([dominant])              # events around the dominant kernel only, whole run
-    s_pruned = timed(prunes, args.steps, args.warmup)
-    s_plain = timed([], args.steps, args.warmup)
+    s_pruned, per_pruned = timed(prunes, args.steps, args.warmup)
+    s_plain, per_plain = timed([], args.steps, args.warmup)
 
     # ---- per-kernel passes (not part of `value`): all kinds timed with events, pruned then unpruned
     kernels = {}
     if not args.no_kernel_passes:
-        kinds = [k for k in fa.PROF_KINDS if k != "other"]
+        kinds = list(fa.PROF_KINDS)          # "other" = plain row copies: KV-cache writes and outputs
         fa.fastav_profile_enable(kinds)
         o = run(prunes, 1)
         torch.cuda.synchronize()
@@ -244,7 +258,9 @@ def main():
                    "kv_heads": m.n_kv_heads, "head_dim": m.head_dim, "mlp": m.mlp_dim, "batch": len(w.samples),
                    "tokens": tokens, "prunes": [[p.layer, "global" if p.kind == fi.GLOBAL else "fine", p.keep_ratio] for p in w.prunes],
                    "kv_cache_written": True},
+        "ms_per_step_median": float(np.median(per_pruned)), "ms_per_step_min": float(np.min(per_pruned)),
         "unpruned_tokens_per_s": tokens / s_plain, "unpruned_ms_per_step": s_plain * 1e3,
+        "unpruned_ms_per_step_median": float(np.median(per_plain)), "unpruned_ms_per_step_min": float(np.min(per_plain)),
         "pruned_over_unpruned": s_plain / s_pruned,
         "prune_steps_us_per_prefill": prune_us,
         "roofline": {"kernel": "k_gemm_mfma<SwiGLU> (gate/up projection)", "bound": "mfma", "achieved": achieved,

@@ -141,6 +141,15 @@ def unpruned(w: Workload) -> Workload:
     return Workload(w.name + "_unpruned", w.model, w.samples, [], w.n_last, w.seed, w.weight_seed)
 
 
+def paper_schedule(w: Workload, global_keep: float = 0.6, fine_drop: float = 0.2) -> Workload:
+    """Same workload under the schedule the paper runs (Sec. 4, implementation details): one global prune at
+    the middle layer, then a fine prune at every layer after it, each dropping ``fine_drop`` (the paper's
+    P = 20 %) of the tokens that are left."""
+    mid = w.model.n_layers // 2
+    prunes = [Prune(mid, GLOBAL, global_keep)] + [Prune(l, FINE, 1.0 - fine_drop) for l in range(mid + 1, w.model.n_layers)]
+    return Workload(w.name + "_paper_schedule", w.model, w.samples, prunes, w.n_last, w.seed, w.weight_seed)
+
+
 def with_layers(w: Workload, n_layers: int) -> Workload:
     """Same workload on a decoder truncated to its first ``n_layers`` layers (prunes beyond are dropped)."""
     m = w.model

@@ -251,11 +251,11 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs a, const int32_t* __r
 }
 
 static fastav_status_t gather_impl(const GatherArgs& a, int n_tensors, const int32_t* keep_idx, int64_t n_rows,
-                                   hipStream_t s) {
+                                   int prof_kind, hipStream_t s) {
   if (n_rows == 0 || n_tensors == 0) return FASTAV_OK;
   double bytes = keep_idx ? 4.0 * n_rows : 0.0;
   for (int i = 0; i < n_tensors; ++i) bytes += 2.0 * a.row_bytes[i] * n_rows;
-  ProfScope prof(FASTAV_PROF_GATHER, bytes, s);
+  ProfScope prof(prof_kind, bytes, s);
   // aim at >= 4 KB of payload per workgroup, judged by the widest tensor
   int64_t widest = 1;
   for (int i = 0; i < n_tensors; ++i) widest = a.row_bytes[i] > widest ? a.row_bytes[i] : widest;
@@ -278,7 +278,7 @@ fastav_status_t launch_gather(const GatherTensor* t, int n_tensors, const int32_
     a.row_bytes[m] = t[i].row_bytes; a.src_stride[m] = t[i].src_stride_bytes ? t[i].src_stride_bytes : t[i].row_bytes; ++m;
   }
   for (int i = m; i < FASTAV_MAX_GATHER_TENSORS; ++i) { a.src[i] = nullptr; a.dst[i] = nullptr; a.row_bytes[i] = 0; a.src_stride[i] = 0; }
-  return gather_impl(a, m, keep_idx, n_rows, s);
+  return gather_impl(a, m, keep_idx, n_rows, FASTAV_PROF_GATHER, s);
 }
 
 fastav_status_t launch_copy_rows(const void* src, int64_t src_row_bytes_stride, void* dst, int64_t row_bytes,
@@ -286,7 +286,8 @@ fastav_status_t launch_copy_rows(const void* src, int64_t src_row_bytes_stride, 
   GatherArgs a;
   for (int i = 0; i < FASTAV_MAX_GATHER_TENSORS; ++i) { a.src[i] = nullptr; a.dst[i] = nullptr; a.row_bytes[i] = 0; a.src_stride[i] = 0; }
   a.src[0] = (const char*)src; a.dst[0] = (char*)dst; a.row_bytes[0] = row_bytes; a.src_stride[0] = src_row_bytes_stride;
-  return gather_impl(a, 1, idx, rows, s);
+  // plain row copies (KV-cache writes, outputs) are not part of a prune step: they are timed as "other"
+  return gather_impl(a, 1, idx, rows, idx ? FASTAV_PROF_GATHER : FASTAV_PROF_OTHER, s);
 }
 
 }  // namespace fastav

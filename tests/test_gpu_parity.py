@@ -377,6 +377,21 @@ def test_prefill_n_last_greater_than_one():
         assert st[f"x_rel_l2_{b}"] <= 1e-2, st
 
 
+def test_prefill_paper_schedule_fine_prune_at_every_later_layer():
+    """The schedule the paper runs (global prune at the middle layer, a 20 % fine prune at every layer after
+    it) on a small 8-layer model and a ragged batch: 1 + 3 prune steps' worth of kept sets against the oracle."""
+    m = fi.Model(8, 512, 8, 2, 128, 1024, 1.0e4, 1e-6, "bf16")
+    base = fi.Workload("small8", m, [[(fi.VIDEO, 288), (fi.AUDIO, 150), (fi.TEXT, 30)], [(fi.VIDEO, 144), (fi.AUDIO, 97), (fi.TEXT, 9)]],
+                       [], seed=43)
+    w = fi.paper_schedule(base, global_keep=0.6, fine_drop=0.2)
+    assert [p.layer for p in w.prunes] == [4, 5, 6, 7] and w.prunes[0].kind == fi.GLOBAL
+    weights = [fi.layer_weights(m, l, 9) for l in range(m.n_layers)]
+    out, ref = _oracle_and_gpu(w, weights, fi.embeddings(w), want_kv=False)
+    st = _check_prefill(w, out, ref)
+    for b in range(2):
+        assert st[f"x_rel_l2_{b}"] <= 2e-2 and st[f"x_max_abs_over_rms_{b}"] <= 0.1, st
+
+
 def test_prefill_cfg2_7b_single_layer():
     w = fi.config(2)
     weights = [fi.layer_weights(w.model, 0, w.weight_seed)]
