@@ -47,8 +47,9 @@ Pins (tests/test_oracle_pins.py): brute-force loops on tiny inputs, library
 special cases (torch SDPA / rms_norm / silu, numpy stable argsort), closed forms
 (zero queries -> uniform scores; one dominant key -> one-hot), invariants (rows
 sum to 1, keep ratio 1.0 is the identity, RoPE relative-position property,
-batched == per-sample), and the paper's printed FLOPs column of Table 4 for the
-schedule semantics.  Parity unpinned: the absolute hidden-state values for random
+batched == per-sample; a decode step on unpruned caches equals the last row of a
+prefill one token longer; cache order does not matter), and the paper's printed
+FLOPs column of Table 4 for the schedule semantics.  Parity unpinned: the absolute hidden-state values for random
 weights (the paper prints no worked numeric example).
 """
 from __future__ import annotations
@@ -295,6 +296,45 @@ def prefill(workload, weights, x: np.ndarray, dtype=np.float64, keep_kv: bool = 
                                    workload.n_last, dtype, keep_kv, trace))
         row += n
     return outs
+
+
+# --------------------------------------------------------------------------- one decode step on the caches
+def single_query_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray) -> np.ndarray:
+    """softmax(q k^T / sqrt(dh)) v for ONE query that sees every key (readings R1, R3).
+
+    q[Hq,dh], k,v[n,Hkv,dh] -> [Hq,dh].  The generated token is the last position, so no mask applies."""
+    Hq, dh = q.shape
+    G = Hq // k.shape[1]
+    out = np.empty_like(q)
+    for h in range(Hq):
+        z = (k[:, h // G, :] @ q[h]) / math.sqrt(dh)
+        out[h] = _softmax_rows(z[None, :])[0] @ v[:, h // G, :]
+    return out
+
+
+def decode_step(m, weights, x_new: np.ndarray, pos_new: int, kv: Sequence[Tuple[np.ndarray, np.ndarray]],
+                dtype=np.float64) -> Dict:
+    """Forward of ONE new token of one sample over the per-layer K/V caches a (pruned) prefill left behind
+    (Section 3.1: the paper's latency is the time to generate a single token; the memory it saves is these
+    compacted caches).
+
+    ``kv[l]`` = (K [n_l,Hkv,dh], V [n_l,Hkv,dh]) of layer l: post-RoPE keys of the tokens that survived that
+    layer, plus anything generated since; n_l differs per layer once pruning has happened.  The new token
+    carries RoPE position ``pos_new`` (its index in the ORIGINAL sequence, reading R8) and attends to the
+    cache and to itself.  Returns x_out [d] and the token's own (k, v) per layer, to be appended."""
+    get_w = weights if callable(weights) else (lambda l: weights[l])
+    x = np.asarray(x_new, dtype=dtype)[None, :]
+    pos = np.array([pos_new], dtype=np.int64)
+    new_kv = []
+    for l in range(m.n_layers):
+        W = {name: np.asarray(a, dtype=dtype) for name, a in get_w(l).items()}
+        q, k, v = layer_qkv(x, W, pos, m)                                   # [1,H,dh] each
+        K = np.concatenate([np.asarray(kv[l][0], dtype=dtype), k], axis=0)
+        V = np.concatenate([np.asarray(kv[l][1], dtype=dtype), v], axis=0)
+        attn = single_query_attention(q[0], K, V)
+        x = layer_finish(x, attn[None], W, m)
+        new_kv.append((k[0], v[0]))
+    return {"x_out": x[0], "kv": new_kv}
 
 
 # --------------------------------------------------------------------------- FLOPs accounting

@@ -329,3 +329,52 @@ def test_input_generators_shapes():
     r = fi.round_bf16(a.copy())
     assert r[0] == 1.0 and r[1] == 1.0 and r[2] == np.float32(1.015625)
     assert r[3] == torch.tensor(3.14159).to(torch.bfloat16).float().item()
+
+
+# ------------------------------------------------------------------------------------ decode step
+def test_decode_step_equals_last_row_of_a_longer_prefill():
+    """With unpruned caches, the forward of token n over the caches of tokens 0..n-1 IS row n of a causal
+    prefill over n+1 tokens: the definition the decode step must reproduce."""
+    m, w, weights, x = _tiny()
+    n = x.shape[0] - 1
+    spans = [(fi.TEXT, n)]
+    head = orc.prefill_sample(m, weights, x[:n], spans, [])
+    full = orc.prefill_sample(m, weights, x, [(fi.TEXT, n + 1)], [])
+    step = orc.decode_step(m, weights, x[n], n, head["kv"])
+    np.testing.assert_allclose(step["x_out"], full["x_out"][n], rtol=1e-11, atol=1e-12)
+    for l in range(m.n_layers):
+        np.testing.assert_allclose(step["kv"][l][0], full["kv"][l][0][n], rtol=1e-11, atol=1e-12)
+        np.testing.assert_allclose(step["kv"][l][1], full["kv"][l][1][n], rtol=1e-11, atol=1e-12)
+    # a second step on the grown caches equals row n+1 of a prefill over n+2 tokens
+    x2 = np.concatenate([x, x[3:4] * 0.5 + 0.1], axis=0)
+    grown = [(np.concatenate([head["kv"][l][0], step["kv"][l][0][None]]), np.concatenate([head["kv"][l][1], step["kv"][l][1][None]]))
+             for l in range(m.n_layers)]
+    step2 = orc.decode_step(m, weights, x2[n + 1], n + 1, grown)
+    full2 = orc.prefill_sample(m, weights, x2, [(fi.TEXT, n + 2)], [])
+    np.testing.assert_allclose(step2["x_out"], full2["x_out"][n + 1], rtol=1e-11, atol=1e-12)
+
+
+def test_decode_step_on_pruned_caches_sees_a_set_of_keys():
+    """On pruned caches the layers hold different numbers of keys; the step depends on each cache as a SET
+    (keys carry their rotary position already), and matches brute-force loops."""
+    m, w, weights, x = _tiny()
+    out = orc.prefill(w, weights, x)[0]
+    assert [kv[0].shape[0] for kv in out["kv"]] == [41, 25, 18, 13]
+    x_new = x[5] * 0.7 - 0.2
+    step = orc.decode_step(m, weights, x_new, 41, out["kv"])
+    rng = np.random.default_rng(0)
+    shuffled = []
+    for K, V in out["kv"]:
+        p = rng.permutation(K.shape[0])
+        shuffled.append((K[p], V[p]))
+    step_p = orc.decode_step(m, weights, x_new, 41, shuffled)
+    np.testing.assert_allclose(step_p["x_out"], step["x_out"], rtol=1e-11, atol=1e-12)
+    # layer 0 attention by explicit loops: query = the new token, keys = cache + itself
+    W0 = {k: v.astype(np.float64) for k, v in weights[0].items()}
+    q, k, v = orc.layer_qkv(x_new[None].astype(np.float64), W0, np.array([41]), m)
+    K = np.concatenate([out["kv"][0][0], k]); V = np.concatenate([out["kv"][0][1], v])
+    nk = K.shape[0]
+    qq = np.concatenate([np.zeros((nk - 1,) + q.shape[1:]), q])          # brute works on causal rows: use the last
+    want = np.array(brute.attention_output(qq.tolist(), K.tolist(), V.tolist(), m.n_q_heads // m.n_kv_heads)[nk - 1])
+    got = orc.single_query_attention(q[0], K, V)
+    np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-12)
