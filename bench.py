@@ -145,6 +145,43 @@ def _prune_stress(fa, torch, model_struct, hq, hkv, dh, d):
             "score": mk(b_score, t_score), "select": mk(b_sel, t_sel), "gather": mk(b_gather, t_gather)}
 
 
+def _decode_bench(fa, torch, dec, m, w, x, cu, spans, offs, prunes, iters=20):
+    """One generated token's forward (the paper's latency metric, Section 3.1) on the caches the pruned prefill
+    left, and on the unpruned caches: ms per step and bytes moved (all weights once + every layer's cache once)
+    against the HBM peak.  Not part of `value`."""
+    if m.dtype != "bf16" or len(w.samples) > 16:
+        return None
+    B = len(w.samples)
+    qd, kd = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
+    w_bytes = m.n_layers * 2.0 * ((qd + 2 * kd) * m.hidden + m.hidden * qd + 3 * m.hidden * m.mlp_dim)
+    g = torch.Generator(device="cuda").manual_seed(11)
+    x_new = torch.randn(B, m.hidden, device="cuda", generator=g).bfloat16()
+    pos = torch.tensor(w.seqlens, dtype=torch.int32, device="cuda")
+    res = {}
+    for name, pr in (("pruned", prunes), ("unpruned", [])):
+        out = dec.fastav_prefill(x, cu, spans, offs, pr, w.n_last, want_kv=True)
+        lens = fa.fastav_schedule_lens(cu, spans, offs, pr, w.n_last, m.n_layers)
+        st = None
+        for _ in range(3):
+            st = dec.fastav_decode_step(x_new, pos, out["kv"], lens, state=st)["state"]
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+        torch.cuda.synchronize()
+        for i in range(iters):
+            ev[i].record()
+            dec.fastav_decode_step(x_new, pos, out["kv"], lens, state=st)
+        ev[iters].record()
+        torch.cuda.synchronize()
+        ts = [ev[i].elapsed_time(ev[i + 1]) for i in range(iters)]
+        cache_bytes = float(lens.sum()) * 2 * kd * 2
+        med = float(np.median(ts))
+        res[name] = {"ms_per_token_median": med, "ms_per_token_min": float(np.min(ts)),
+                     "cache_MB": cache_bytes / 1e6, "weights_MB": w_bytes / 1e6,
+                     "achieved": (w_bytes + cache_bytes) / (med * 1e-3) / 1e9, "unit": "GB/s",
+                     "frac": (w_bytes + cache_bytes) / (med * 1e-3) / 1e9 / PEAK_HBM_GBS}
+        del out
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -245,6 +282,10 @@ def main():
     if not args.no_kernel_passes and m.dtype == "bf16":
         stress = _prune_stress(fa, torch, dec.model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.hidden)
 
+    decode = None
+    if not args.no_kernel_passes:
+        decode = _decode_bench(fa, torch, dec, m, w, x, cu, spans, offs, prunes)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = _cpu_baseline(w, host_threads)
@@ -268,6 +309,7 @@ def main():
                      "launches": n, "avg_launch_us": 1e3 * ms / max(n, 1)},
         "kernels": kernels,
         "prune_kernels_stress": stress,
+        "decode_step": decode,
         "cpu_baseline": cpu,
         "setup_s": setup_s,
     }

@@ -50,6 +50,7 @@ typedef enum { FASTAV_BF16 = 0, FASTAV_F32 = 1 } fastav_dtype_t;
 #define FASTAV_MAX_N_LAST 8     /* most last-query rows Eq. 4 may be averaged over */
 #define FASTAV_MAX_PRUNES 128
 #define FASTAV_MAX_GATHER_TENSORS 8
+#define FASTAV_MAX_DECODE_BATCH 16 /* most samples one decode step serves (one matrix-instruction tile of rows) */
 
 /* One modality span of a sample (Section 2.1: X = [X^vis, X^aud, X^lang]).  start is relative to the
  * sample; the spans of a sample are sorted, disjoint and cover [0, n). */
@@ -117,6 +118,12 @@ int64_t fastav_keep_count(int64_t n, double keep_ratio, int64_t n_protected);
 fastav_status_t fastav_schedule(const fastav_batch_t* in, const fastav_prune_t* prunes, int32_t n_prunes,
                                 int32_t n_last, int32_t n_layers, int64_t* tokens_in_out,
                                 int64_t* tokens_out_out, int32_t* final_lens_out);
+
+/* Tokens per sample that LEAVE each layer (= rows per sample of that layer's K/V cache in kv_out), from
+ * shapes alone: lens_out [n_layers * batch], entry [l * batch + b].  A decode step needs these to find each
+ * sample's rows in a pruned layer's cache. */
+fastav_status_t fastav_schedule_lens(const fastav_batch_t* in, const fastav_prune_t* prunes, int32_t n_prunes,
+                                     int32_t n_last, int32_t n_layers, int32_t* lens_out);
 
 const char* fastav_last_error(void);
 
@@ -209,6 +216,42 @@ fastav_status_t fastav_attention(const fastav_model_t* model, const void* q, int
  * algorithmic work of a launch: flops for LINEAR_* (2 M N K; SwiGLU counts both matrices) and ATTENTION
  * (2 Hq dh n(n+1) per sample, the causal half only), bytes for the others (what the step must read and
  * write once). */
+/* ---- one decode step on the pruned caches ------------------------------------------------------------
+ * Section 3.1 measures latency as the time to generate a single token, and the memory FastAV saves is the
+ * per-layer K/V cache of the surviving tokens.  This is that forward for ONE new token per sample (bf16
+ * models; at most FASTAV_MAX_DECODE_BATCH samples): every layer runs RMSNorm, the Q/K/V projections, RoPE at
+ * pos_new, single-query grouped-query attention over
+ *     [ that layer's prefill cache | tokens generated before this step | the new token itself ],
+ * the output projection, and the SwiGLU MLP, with fp32 residuals.  After a pruned prefill the layers hold
+ * different numbers of keys per sample; keys carry their original rotary positions, so a cache is a set.
+ *
+ * All pointers inside are DEVICE pointers unless stated; the pointer ARRAYS (k_prefix ...) live on the host.
+ * The library reads the caches, never frees or reallocates anything; if k_gen / v_gen are given it writes
+ * the new token's key / value into slot gen_len of every layer's generated-token cache (the caller then
+ * passes gen_len + 1 on the next step). */
+typedef struct {
+  int32_t batch;
+  const void* x_new;                /* [batch, hidden], model dtype: the new token's input embedding */
+  const int32_t* pos_new;           /* [batch] rotary position of the new token (original length + generated) */
+  const void* const* k_prefix;      /* host array [n_layers]: [T_l, n_kv_heads*head_dim] packed per sample */
+  const void* const* v_prefix;      /* host array [n_layers] */
+  const int32_t* const* cu_prefix;  /* host array [n_layers] of device int32 [batch + 1] prefix sums of the
+                                       per-sample rows of that layer's cache */
+  const int32_t* max_prefix;        /* HOST [n_layers]: the longest sample's rows in that layer's cache */
+  void* const* k_gen;               /* host array [n_layers] of [batch, gen_cap, n_kv_heads*head_dim], or NULL */
+  void* const* v_gen;               /* host array [n_layers], or NULL (both or neither) */
+  int32_t gen_len;                  /* generated tokens already in k_gen / v_gen (the same for every sample) */
+  int32_t gen_cap;
+} fastav_decode_in_t;
+
+/* Bytes of device workspace (256-byte aligned, scratch) one decode step needs for at most max_batch samples. */
+fastav_status_t fastav_decode_workspace_bytes(fastav_handle_t h, int32_t max_batch, size_t* out);
+/* x_out: device [batch, hidden] fp32, the hidden state leaving the last layer (before the final norm and
+ * the vocabulary projection, like fastav_prefill).  Errors: FASTAV_EINVAL on bad arguments,
+ * FASTAV_EUNSUPPORTED for fp32 models or dimensions that are not multiples of 128, FASTAV_EWORKSPACE. */
+fastav_status_t fastav_decode_step(fastav_handle_t h, const fastav_decode_in_t* in, float* x_out, void* workspace,
+                                   size_t workspace_bytes, void* stream);
+
 typedef enum {
   FASTAV_PROF_LINEAR_STORE = 0, FASTAV_PROF_LINEAR_RESADD = 1, FASTAV_PROF_LINEAR_SWIGLU = 2,
   FASTAV_PROF_ATTENTION = 3, FASTAV_PROF_SCORE = 4, FASTAV_PROF_SELECT = 5, FASTAV_PROF_GATHER = 6,

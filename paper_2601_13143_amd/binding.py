@@ -61,11 +61,22 @@ class PrefillOut(C.Structure):
 
 _lib = None
 
+class DecodeIn(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("x_new", C.c_void_p), ("pos_new", C.c_void_p),
+                ("k_prefix", C.POINTER(C.c_void_p)), ("v_prefix", C.POINTER(C.c_void_p)),
+                ("cu_prefix", C.POINTER(C.c_void_p)), ("max_prefix", C.POINTER(C.c_int32)),
+                ("k_gen", C.POINTER(C.c_void_p)), ("v_gen", C.POINTER(C.c_void_p)),
+                ("gen_len", C.c_int32), ("gen_cap", C.c_int32)]
+
+
 _SIGS = {
     "fastav_last_error": (C.c_char_p, []),
     "fastav_keep_count": (C.c_int64, [C.c_int64, C.c_double, C.c_int64]),
     "fastav_schedule": (C.c_int, [C.POINTER(Batch), C.POINTER(Prune), C.c_int32, C.c_int32, C.c_int32,
                                   C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]),
+    "fastav_schedule_lens": (C.c_int, [C.POINTER(Batch), C.POINTER(Prune), C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
+    "fastav_decode_workspace_bytes": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_size_t)]),
+    "fastav_decode_step": (C.c_int, [C.c_void_p, C.POINTER(DecodeIn), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "fastav_create": (C.c_int, [C.POINTER(Model), C.POINTER(C.c_void_p)]),
     "fastav_destroy": (None, [C.c_void_p]),
     "fastav_set_weights": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(LayerWeights)]),
@@ -176,6 +187,15 @@ def fastav_schedule(cu_seqlens, spans, span_offsets, prunes: Sequence, n_last: i
     return tin[:n_layers], tout[:n_layers], fl
 
 
+def fastav_schedule_lens(cu_seqlens, spans, span_offsets, prunes: Sequence, n_last: int, n_layers: int) -> np.ndarray:
+    """-> int32 [n_layers, batch]: tokens of each sample that leave each layer (rows per sample of its K/V cache)."""
+    hb = _HostBatch(None, cu_seqlens, spans, span_offsets)
+    out = np.zeros((n_layers, hb.c.batch), dtype=np.int32)
+    _check(lib().fastav_schedule_lens(C.byref(hb.c), _prune_array(prunes), len(prunes), n_last, n_layers,
+                                      out.ctypes.data_as(C.POINTER(C.c_int32))))
+    return out
+
+
 class Decoder:
     """Owns a fastav handle, the device weights handed to it and a reusable workspace tensor."""
 
@@ -262,6 +282,43 @@ class Decoder:
                                     ws.numel(), C.byref(po), _stream()))
         o["tokens_in"], o["tokens_out"], o["final_lens"] = tin, tout, fl
         return o
+
+
+    def fastav_decode_step(self, x_new: torch.Tensor, pos_new: torch.Tensor, kv: Sequence, lens: np.ndarray,
+                           gen: Optional[Sequence] = None, gen_len: int = 0, state: Optional[Dict] = None) -> Dict:
+        """One decode step on the current stream.  ``kv``: per layer (K, V) device tensors [T_l, Hkv, dh] as
+        fastav_prefill returned them; ``lens``: int32 [n_layers, batch] rows per sample of every layer's cache
+        (fastav_schedule_lens); ``gen``: per layer (K, V) tensors [batch, gen_cap, Hkv, dh] holding ``gen_len``
+        generated tokens, slot gen_len is written.  -> {"x_out": fp32 [batch, hidden], "state": reusable}."""
+        m = self.model
+        B = x_new.shape[0]
+        if x_new.dtype != self.torch_dtype or not x_new.is_contiguous() or tuple(x_new.shape) != (B, m.hidden):
+            raise ValueError("x_new must be a contiguous [batch, hidden] tensor in the model dtype")
+        st = state if state is not None else {}
+        if "cu" not in st:                                   # per-layer prefix sums of the cache rows, on the device
+            lens = np.asarray(lens, dtype=np.int32).reshape(m.n_layers, B)
+            cu = np.zeros((m.n_layers, B + 1), dtype=np.int32)
+            cu[:, 1:] = np.cumsum(lens, axis=1)
+            st["cu"] = torch.from_numpy(cu).to(x_new.device)
+            st["max_prefix"] = np.ascontiguousarray(lens.max(axis=1).astype(np.int32))
+            st["x_out"] = torch.empty((B, m.hidden), dtype=torch.float32, device=x_new.device)
+            need = C.c_size_t()
+            _check(lib().fastav_decode_workspace_bytes(self._h, B, C.byref(need)))
+            st["ws"] = torch.empty(need.value, dtype=torch.uint8, device=x_new.device)
+        L = m.n_layers
+        kp = (C.c_void_p * L)(*[kv[l][0].data_ptr() for l in range(L)])
+        vp = (C.c_void_p * L)(*[kv[l][1].data_ptr() for l in range(L)])
+        cup = (C.c_void_p * L)(*[st["cu"][l].data_ptr() for l in range(L)])
+        kg = vg = None
+        gen_cap = 0
+        if gen is not None:
+            kg = (C.c_void_p * L)(*[gen[l][0].data_ptr() for l in range(L)])
+            vg = (C.c_void_p * L)(*[gen[l][1].data_ptr() for l in range(L)])
+            gen_cap = gen[0][0].shape[1]
+        di = DecodeIn(B, x_new.data_ptr(), pos_new.data_ptr(), kp, vp, cup,
+                      st["max_prefix"].ctypes.data_as(C.POINTER(C.c_int32)), kg, vg, gen_len, gen_cap)
+        _check(lib().fastav_decode_step(self._h, C.byref(di), st["x_out"].data_ptr(), st["ws"].data_ptr(), st["ws"].numel(), _stream()))
+        return {"x_out": st["x_out"], "state": st}
 
 
 def fastav_score(model: Model, q: torch.Tensor, k: torch.Tensor, cu_seqlens_dev: torch.Tensor, max_seqlen: int,

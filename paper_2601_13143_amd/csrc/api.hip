@@ -46,6 +46,18 @@ fastav_status_t launch_attention_mfma(const void* q, int64_t q_stride, const voi
                                       int64_t T, int max_seqlen, int Hq, int Hkv, int dh, float* last_logits,
                                       float* last_ml, hipStream_t s);
 
+bool skinny_linear_supported(int64_t m, int n, int k, int dtype, int64_t ldy);
+fastav_status_t launch_skinny_linear(const void* x, const void* const* w_seg, const int* seg_rows, int n_seg,
+                                     const void* w2, void* y, int64_t ldy, int B, int n, int k, int epilogue,
+                                     hipStream_t s);
+size_t decode_attn_workspace_bytes(int batch, int Hq, int dh, int max_splits);
+fastav_status_t launch_decode_attention(const void* q, const void* k_self, const void* v_self, int64_t q_stride,
+                                        const void* k_prefix, const void* v_prefix, const int32_t* cu_prefix,
+                                        int max_prefix, const void* k_gen, const void* v_gen, int gen_len,
+                                        int gen_cap, int batch, int Hq, int Hkv, int dh, float* part,
+                                        size_t part_bytes, void* out, int64_t out_stride, double bytes_hint,
+                                        hipStream_t s);
+
 // One linear layer whose weight rows may come from up to three matrices stacked along N (Q|K|V).
 static fastav_status_t linear_segments(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
                                        const void* w2, void* c, int64_t ldc, int64_t m, int k, int epilogue, int dtype,
@@ -53,6 +65,12 @@ static fastav_status_t linear_segments(const void* a, const void* const* w_seg, 
   int n = 0;
   for (int i = 0; i < n_seg; ++i) n += seg_rows[i];
   if (m == 0 || n == 0) return FASTAV_OK;
+  // a handful of rows (a decode step): stream the weights through the skinny kernel, which times itself
+  if (m <= FASTAV_MAX_DECODE_BATCH && skinny_linear_supported(m, n, k, dtype, ldc)) {
+    bool sk = (((uintptr_t)a | (uintptr_t)c) % 16) == 0;
+    for (int i = 0; i < n_seg && sk; ++i) sk = seg_rows[i] % 16 == 0;
+    if (sk) return launch_skinny_linear(a, w_seg, seg_rows, n_seg, w2, c, ldc, (int)m, n, k, epilogue, s);
+  }
   const int kind = epilogue == FASTAV_EPI_STORE ? FASTAV_PROF_LINEAR_STORE
                    : epilogue == FASTAV_EPI_RESADD ? FASTAV_PROF_LINEAR_RESADD : FASTAV_PROF_LINEAR_SWIGLU;
   ProfScope prof(kind, 2.0 * (double)m * n * k * (epilogue == FASTAV_EPI_SWIGLU ? 2.0 : 1.0), s);
@@ -260,6 +278,24 @@ fastav_status_t fastav_schedule(const fastav_batch_t* in, const fastav_prune_t* 
     if (tokens_out_out) tokens_out_out[l] = tot[stage];
   }
   if (final_lens_out) for (int b = 0; b < in->batch; ++b) final_lens_out[b] = lens[n_prunes][b];
+  return FASTAV_OK;
+}
+
+fastav_status_t fastav_schedule_lens(const fastav_batch_t* in, const fastav_prune_t* prunes, int32_t n_prunes,
+                                     int32_t n_last, int32_t n_layers, int32_t* lens_out) {
+  int64_t T; int max_len;
+  fastav_status_t st = check_batch(in, false, &T, &max_len);
+  if (st != FASTAV_OK) return st;
+  if (n_layers < 1 || !lens_out) return fail(FASTAV_EINVAL, "n_layers must be >= 1 and lens_out non-NULL");
+  st = check_prunes(prunes, n_prunes, n_layers, n_last);
+  if (st != FASTAV_OK) return st;
+  std::vector<std::vector<int32_t>> lens;
+  build_schedule(in, prunes, n_prunes, n_last, lens);
+  int stage = 0, pi = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    while (pi < n_prunes && prunes[pi].layer == l) { ++stage; ++pi; }     // global, then fine, of this layer
+    for (int b = 0; b < in->batch; ++b) lens_out[(size_t)l * in->batch + b] = lens[stage][b];
+  }
   return FASTAV_OK;
 }
 
@@ -566,6 +602,106 @@ fastav_status_t fastav_attention(const fastav_model_t* model, const void* q, int
   return launch_attention(q, q_row_stride, k, v, kv_row_stride, o, o_row_stride, cu_seqlens_dev, batch, total_tokens,
                           max_seqlen, model->n_q_heads, model->n_kv_heads, model->head_dim, last_logits, last_ml,
                           model->dtype, 0.0, (hipStream_t)stream);
+}
+
+// ---- decode step ------------------------------------------------------------------------------------
+struct DecodeWs { size_t x, hn, qkv, attn, hmlp, part, part_bytes, total; };
+
+static DecodeWs carve_decode(const fastav_model_t& m, int B) {
+  DecodeWs w;
+  size_t at = 0;
+  auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes, 256); return o; };
+  const size_t qd = (size_t)m.n_q_heads * m.head_dim, kd = (size_t)m.n_kv_heads * m.head_dim;
+  w.x = take((size_t)B * m.hidden * 4);
+  w.hn = take((size_t)B * m.hidden * 2);
+  w.qkv = take((size_t)B * (qd + 2 * kd) * 2);
+  w.attn = take((size_t)B * qd * 2);
+  w.hmlp = take((size_t)B * m.mlp_dim * 2);
+  w.part_bytes = decode_attn_workspace_bytes(B, m.n_q_heads, m.head_dim, 64);
+  w.part = take(w.part_bytes);
+  w.total = at;
+  return w;
+}
+
+fastav_status_t fastav_decode_workspace_bytes(fastav_handle_t h, int32_t max_batch, size_t* out) {
+  if (!h || !out) return fail(FASTAV_EINVAL, "handle or out is NULL");
+  if (max_batch < 1 || max_batch > FASTAV_MAX_DECODE_BATCH) return fail(FASTAV_EINVAL, "max_batch must be in [1, %d]", FASTAV_MAX_DECODE_BATCH);
+  *out = carve_decode(h->m, max_batch).total;
+  return FASTAV_OK;
+}
+
+fastav_status_t fastav_decode_step(fastav_handle_t h, const fastav_decode_in_t* in, float* x_out, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+  if (!h || !in || !x_out) return fail(FASTAV_EINVAL, "handle, in or x_out is NULL");
+  const fastav_model_t& m = h->m;
+  hipStream_t s = (hipStream_t)stream;
+  const int B = in->batch;
+  if (B < 1 || B > FASTAV_MAX_DECODE_BATCH) return fail(FASTAV_EINVAL, "batch must be in [1, %d]", FASTAV_MAX_DECODE_BATCH);
+  if (m.dtype != FASTAV_BF16) return fail(FASTAV_EUNSUPPORTED, "the decode step is built for bf16 models");
+  if (!in->x_new || !in->pos_new || !in->k_prefix || !in->v_prefix || !in->cu_prefix || !in->max_prefix)
+    return fail(FASTAV_EINVAL, "x_new, pos_new, k_prefix, v_prefix, cu_prefix and max_prefix must be non-NULL");
+  if (in->gen_len < 0 || in->gen_cap < 0 || in->gen_len > in->gen_cap) return fail(FASTAV_EINVAL, "need 0 <= gen_len <= gen_cap");
+  if ((in->k_gen == nullptr) != (in->v_gen == nullptr)) return fail(FASTAV_EINVAL, "k_gen and v_gen go together");
+  if (in->gen_len > 0 && !in->k_gen) return fail(FASTAV_EINVAL, "gen_len > 0 needs k_gen / v_gen");
+  if (in->k_gen && in->gen_len >= in->gen_cap) return fail(FASTAV_EINVAL, "the generated-token caches are full (gen_len == gen_cap)");
+  if (!workspace || ((uintptr_t)workspace % 256)) return fail(FASTAV_EINVAL, "workspace must be non-NULL and 256-byte aligned");
+  if (((uintptr_t)in->x_new % 16) || ((uintptr_t)x_out % 16)) return fail(FASTAV_EINVAL, "x_new and x_out must be 16-byte aligned");
+  const DecodeWs ws = carve_decode(m, B);
+  if (workspace_bytes < ws.total) return fail(FASTAV_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, ws.total);
+  const int qd = m.n_q_heads * m.head_dim, kd = m.n_kv_heads * m.head_dim, qkvd = qd + 2 * kd;
+  if (!skinny_linear_supported(B, qd, m.hidden, m.dtype, qkvd) || !skinny_linear_supported(B, kd, m.hidden, m.dtype, qkvd) ||
+      !skinny_linear_supported(B, m.hidden, qd, m.dtype, m.hidden) || !skinny_linear_supported(B, m.mlp_dim, m.hidden, m.dtype, m.mlp_dim) ||
+      !skinny_linear_supported(B, m.hidden, m.mlp_dim, m.dtype, m.hidden))
+    return fail(FASTAV_EUNSUPPORTED, "decode step: hidden, heads*head_dim and mlp_dim must be multiples of 128");
+  for (int l = 0; l < m.n_layers; ++l) {
+    if (!h->has_w[l]) return fail(FASTAV_EINVAL, "weights of layer %d were never set", l);
+    if (!in->k_prefix[l] || !in->v_prefix[l] || !in->cu_prefix[l]) return fail(FASTAV_EINVAL, "a cache pointer of layer %d is NULL", l);
+    if (in->max_prefix[l] < 0) return fail(FASTAV_EINVAL, "max_prefix[%d] is negative", l);
+    if (in->k_gen && (!in->k_gen[l] || !in->v_gen[l])) return fail(FASTAV_EINVAL, "a generated-token cache pointer of layer %d is NULL", l);
+  }
+  char* base = (char*)workspace;
+  float* x = (float*)(base + ws.x);
+  void* hn = base + ws.hn;
+  char* qkv = base + ws.qkv;
+  void* attn = base + ws.attn;
+  void* hmlp = base + ws.hmlp;
+
+  FASTAV_TRY(launch_to_f32(in->x_new, x, (int64_t)B * m.hidden, m.dtype, s));
+  for (int l = 0; l < m.n_layers; ++l) {
+    const fastav_layer_weights_t& W = h->w[l];
+    FASTAV_TRY(launch_rmsnorm(x, W.g_attn, hn, B, m.hidden, m.rms_eps, m.dtype, s));
+    const void* seg[3] = {W.wq, W.wk, W.wv};
+    const int rows[3] = {qd, kd, kd};
+    FASTAV_TRY(launch_skinny_linear(hn, seg, rows, 3, nullptr, qkv, qkvd, B, qkvd, m.hidden, FASTAV_EPI_STORE, s));
+    // the key heads follow the query heads in the row: one launch rotates both
+    FASTAV_TRY(launch_rope(qkv, qkvd, in->pos_new, B, m.n_q_heads + m.n_kv_heads, m.head_dim, m.rope_base, m.dtype, s));
+    const void* kg = in->k_gen ? in->k_gen[l] : nullptr;
+    const void* vg = in->v_gen ? in->v_gen[l] : nullptr;
+    // bytes the attention step has to move: the caches once (upper bound: the longest sample for all)
+    const double abytes = 2.0 * B * ((double)in->max_prefix[l] + in->gen_len + 1) * kd * 2.0;
+    FASTAV_TRY(launch_decode_attention(qkv, qkv + (size_t)qd * 2, qkv + (size_t)(qd + kd) * 2, qkvd, in->k_prefix[l],
+                                       in->v_prefix[l], in->cu_prefix[l], in->max_prefix[l], kg, vg, in->gen_len,
+                                       in->gen_cap, B, m.n_q_heads, m.n_kv_heads, m.head_dim, (float*)(base + ws.part),
+                                       ws.part_bytes, attn, qd, abytes, s));
+    if (in->k_gen) {
+      // append the token's own key / value: slot gen_len of [B, gen_cap, kd]
+      FASTAV_TRY(launch_copy_rows(qkv + (size_t)qd * 2, (int64_t)qkvd * 2, (char*)in->k_gen[l] + (size_t)in->gen_len * kd * 2,
+                                  (int64_t)kd * 2, B, nullptr, s, (int64_t)in->gen_cap * kd * 2));
+      FASTAV_TRY(launch_copy_rows(qkv + (size_t)(qd + kd) * 2, (int64_t)qkvd * 2, (char*)in->v_gen[l] + (size_t)in->gen_len * kd * 2,
+                                  (int64_t)kd * 2, B, nullptr, s, (int64_t)in->gen_cap * kd * 2));
+    }
+    const void* so[1] = {W.wo};
+    const int ro[1] = {m.hidden};
+    FASTAV_TRY(launch_skinny_linear(attn, so, ro, 1, nullptr, x, m.hidden, B, m.hidden, qd, FASTAV_EPI_RESADD, s));
+    FASTAV_TRY(launch_rmsnorm(x, W.g_mlp, hn, B, m.hidden, m.rms_eps, m.dtype, s));
+    const void* sg[1] = {W.w_gate};
+    const int rg[1] = {m.mlp_dim};
+    FASTAV_TRY(launch_skinny_linear(hn, sg, rg, 1, W.w_up, hmlp, m.mlp_dim, B, m.mlp_dim, m.hidden, FASTAV_EPI_SWIGLU, s));
+    const void* sd[1] = {W.w_down};
+    FASTAV_TRY(launch_skinny_linear(hmlp, sd, ro, 1, nullptr, x, m.hidden, B, m.hidden, m.mlp_dim, FASTAV_EPI_RESADD, s));
+  }
+  FASTAV_TRY(launch_copy_rows(x, (int64_t)m.hidden * 4, x_out, (int64_t)m.hidden * 4, B, nullptr, s));
+  return FASTAV_OK;
 }
 
 }  // extern "C"

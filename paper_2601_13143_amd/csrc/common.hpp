@@ -65,8 +65,9 @@ fastav_status_t launch_init_tokens(const int32_t* cu, const int32_t* span_offset
                                    int batch, int64_t T, int max_seqlen, int n_last, int32_t* pos, uint8_t* prot,
                                    hipStream_t s);
 fastav_status_t launch_to_f32(const void* x, float* y, int64_t n, int dtype, hipStream_t s);
+// dst_row_bytes_stride == 0: destination rows are packed
 fastav_status_t launch_copy_rows(const void* src, int64_t src_row_bytes_stride, void* dst, int64_t row_bytes,
-                                 int64_t rows, const int32_t* idx, hipStream_t s);
+                                 int64_t rows, const int32_t* idx, hipStream_t s, int64_t dst_row_bytes_stride = 0);
 fastav_status_t launch_rmsnorm(const float* x, const void* g, void* y, int64_t rows, int d, float eps, int dtype,
                                hipStream_t s);
 fastav_status_t launch_rope(void* x, int64_t row_stride, const int32_t* pos, int64_t rows, int n_heads, int head_dim,

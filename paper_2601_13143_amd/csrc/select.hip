@@ -216,6 +216,7 @@ struct GatherArgs {
   char* dst[FASTAV_MAX_GATHER_TENSORS];
   int64_t row_bytes[FASTAV_MAX_GATHER_TENSORS];
   int64_t src_stride[FASTAV_MAX_GATHER_TENSORS];
+  int64_t dst_stride[FASTAV_MAX_GATHER_TENSORS];   // bytes between destination rows (row_bytes when packed)
 };
 
 // grid (row groups, tensor).  Rows whose size and addresses are multiples of 16 bytes move as uint4 with
@@ -225,11 +226,11 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs a, const int32_t* __r
                                                 int rows_per_block) {
   const int t = blockIdx.y;
   const int64_t rb = a.row_bytes[t];
-  const int64_t ss = a.src_stride[t];
+  const int64_t ss = a.src_stride[t], ds = a.dst_stride[t];
   const char* src = a.src[t];
   char* dst = a.dst[t];
   const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
-  const bool vec = ((rb | ss) % 16 == 0) && (((uintptr_t)src | (uintptr_t)dst) % 16 == 0);
+  const bool vec = ((rb | ss | ds) % 16 == 0) && (((uintptr_t)src | (uintptr_t)dst) % 16 == 0);
   if (vec) {
     const int64_t v_per_row = rb / 16;
     const int64_t total = v_per_row * rows_per_block;
@@ -237,7 +238,7 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs a, const int32_t* __r
       const int64_t r = r0 + i / v_per_row, c = i % v_per_row;
       if (r >= n_rows) break;
       const int64_t sr = idx ? (int64_t)idx[r] : r;
-      ((uint4*)(dst + r * rb))[c] = ((const uint4*)(src + sr * ss))[c];
+      ((uint4*)(dst + r * ds))[c] = ((const uint4*)(src + sr * ss))[c];
     }
   } else {
     const int64_t total = rb * rows_per_block;
@@ -245,7 +246,7 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs a, const int32_t* __r
       const int64_t r = r0 + i / rb, c = i % rb;
       if (r >= n_rows) break;
       const int64_t sr = idx ? (int64_t)idx[r] : r;
-      dst[r * rb + c] = src[sr * ss + c];
+      dst[r * ds + c] = src[sr * ss + c];
     }
   }
 }
@@ -275,17 +276,19 @@ fastav_status_t launch_gather(const GatherTensor* t, int n_tensors, const int32_
   for (int i = 0; i < n_tensors; ++i) {
     if (t[i].row_bytes == 0) continue;
     a.src[m] = (const char*)t[i].src; a.dst[m] = (char*)t[i].dst;
-    a.row_bytes[m] = t[i].row_bytes; a.src_stride[m] = t[i].src_stride_bytes ? t[i].src_stride_bytes : t[i].row_bytes; ++m;
+    a.row_bytes[m] = t[i].row_bytes; a.src_stride[m] = t[i].src_stride_bytes ? t[i].src_stride_bytes : t[i].row_bytes;
+    a.dst_stride[m] = t[i].row_bytes; ++m;
   }
-  for (int i = m; i < FASTAV_MAX_GATHER_TENSORS; ++i) { a.src[i] = nullptr; a.dst[i] = nullptr; a.row_bytes[i] = 0; a.src_stride[i] = 0; }
+  for (int i = m; i < FASTAV_MAX_GATHER_TENSORS; ++i) { a.src[i] = nullptr; a.dst[i] = nullptr; a.row_bytes[i] = 0; a.src_stride[i] = 0; a.dst_stride[i] = 0; }
   return gather_impl(a, m, keep_idx, n_rows, FASTAV_PROF_GATHER, s);
 }
 
 fastav_status_t launch_copy_rows(const void* src, int64_t src_row_bytes_stride, void* dst, int64_t row_bytes,
-                                 int64_t rows, const int32_t* idx, hipStream_t s) {
+                                 int64_t rows, const int32_t* idx, hipStream_t s, int64_t dst_row_bytes_stride) {
   GatherArgs a;
-  for (int i = 0; i < FASTAV_MAX_GATHER_TENSORS; ++i) { a.src[i] = nullptr; a.dst[i] = nullptr; a.row_bytes[i] = 0; a.src_stride[i] = 0; }
+  for (int i = 0; i < FASTAV_MAX_GATHER_TENSORS; ++i) { a.src[i] = nullptr; a.dst[i] = nullptr; a.row_bytes[i] = 0; a.src_stride[i] = 0; a.dst_stride[i] = 0; }
   a.src[0] = (const char*)src; a.dst[0] = (char*)dst; a.row_bytes[0] = row_bytes; a.src_stride[0] = src_row_bytes_stride;
+  a.dst_stride[0] = dst_row_bytes_stride ? dst_row_bytes_stride : row_bytes;
   // plain row copies (KV-cache writes, outputs) are not part of a prune step: they are timed as "other"
   return gather_impl(a, 1, idx, rows, idx ? FASTAV_PROF_GATHER : FASTAV_PROF_OTHER, s);
 }
