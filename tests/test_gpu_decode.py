@@ -173,6 +173,26 @@ def test_decode_step_7b_layer_shape():
     assert_close(host(r["x_out"]), want, "bf16", scale=float(np.sqrt(np.mean(want ** 2))), what="7B-shape decode step")
 
 
+@pytest.mark.parametrize("hq,hkv,dh,batch", [(28, 4, 128, 3), (8, 8, 64, 16), (16, 2, 64, 5)])
+def test_decode_step_head_layouts(hq, hkv, dh, batch):
+    """Seven and eight query heads per KV head (two head passes), one query head per KV head, head_dim 64,
+    a full batch of 16: ragged unpruned caches written by the oracle, two layers."""
+    m = fi.Model(2, hq * dh // 2 if hq * dh >= 1024 else 512, hq, hkv, dh, 1024, 1.0e4, 1e-6, "bf16")
+    rng = np.random.default_rng(hq + batch)
+    lens1 = rng.integers(70, 330, size=batch)
+    samples = [[(fi.VIDEO, int(n) - 20), (fi.TEXT, 20)] for n in lens1]
+    w = fi.Workload("heads", m, samples, [fi.Prune(1, fi.FINE, 0.5)], seed=77)
+    weights = [fi.layer_weights(m, l, 3) for l in range(m.n_layers)]
+    ref, kv, lens = _caches_from_oracle(w, weights, fi.embeddings(w))
+    dec = make_decoder(m, weights)
+    x_new = fi.round_bf16(rng.standard_normal((batch, m.hidden)).astype(np.float32))
+    pos0 = np.array(w.seqlens, dtype=np.int32)
+    want = _oracle_steps(m, weights, kv, lens, [x_new], pos0)[0]
+    r = dec.fastav_decode_step(dev(x_new, "bf16"), torch.from_numpy(pos0).cuda(), [(dev(K, "bf16"), dev(V, "bf16")) for K, V in kv], lens)
+    torch.cuda.synchronize()
+    assert_close(host(r["x_out"]), want, "bf16", scale=float(np.sqrt(np.mean(want ** 2))), what=f"decode Hq{hq} Hkv{hkv} dh{dh} B{batch}")
+
+
 def test_decode_step_rejects_bad_arguments():
     w, weights, x = _small()
     m = w.model

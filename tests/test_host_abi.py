@@ -173,3 +173,49 @@ def test_score_and_select_reject_bad_arguments():
     assert g(kc=np.array([-1, 2], dtype=np.int32)) == B.EINVAL
     assert g(cu=np.array([0, 10, 5], dtype=np.int32)) == B.EINVAL
     assert g(nt=9) == B.EINVAL and g(nt=1) == B.EINVAL and g(wsb=4, kc=np.array([5, 15], dtype=np.int32)) == B.EWORKSPACE
+
+
+@pytest.mark.parametrize("cfg", [1, 3, 5])
+def test_schedule_lens_matches_oracle_cache_rows(cfg):
+    """Rows per sample of every layer's K/V cache (what a decode step needs) equal the oracle's token schedule."""
+    w = fi.config(cfg)
+    spans, offs = fi.span_table(w)
+    prunes = [(p.layer, p.kind, p.keep_ratio) for p in w.prunes]
+    lens = fa.fastav_schedule_lens(fi.cu_seqlens(w), spans, offs, prunes, w.n_last, w.model.n_layers)
+    assert lens.shape == (w.model.n_layers, len(w.samples))
+    for b, s in enumerate(w.samples):
+        n = sum(l for _, l in s)
+        n_prot = int(orc.protected_mask(s, w.n_last).sum())
+        cur, want = n, []
+        for l in range(w.model.n_layers):
+            for p in sorted([p for p in w.prunes if p.layer == l], key=lambda p: p.kind):
+                cur = orc.keep_count(cur, p.keep_ratio, n_prot)
+            want.append(cur)                                         # tokens that leave layer l
+        assert lens[:, b].tolist() == want
+    _, tout, _ = fa.fastav_schedule(fi.cu_seqlens(w), spans, offs, prunes, w.n_last, w.model.n_layers)
+    assert lens.sum(axis=1).tolist() == tout.tolist()
+
+
+def test_decode_step_rejects_bad_arguments_before_any_launch():
+    lib = fa.lib()
+    h = C.c_void_p()
+    assert lib.fastav_create(C.byref(fa.make_model(2, 256, 4, 2, 64, 256)), C.byref(h)) == B.OK
+    need = C.c_size_t()
+    assert lib.fastav_decode_workspace_bytes(h, 4, C.byref(need)) == B.OK and need.value > 0 and need.value % 256 == 0
+    assert lib.fastav_decode_workspace_bytes(h, 0, C.byref(need)) == B.EINVAL
+    assert lib.fastav_decode_workspace_bytes(h, 17, C.byref(need)) == B.EINVAL
+    assert lib.fastav_decode_workspace_bytes(None, 4, C.byref(need)) == B.EINVAL
+    di = B.DecodeIn()
+    assert lib.fastav_decode_step(None, C.byref(di), None, None, 0, None) == B.EINVAL
+    assert lib.fastav_decode_step(h, None, None, None, 0, None) == B.EINVAL
+    fake = C.c_void_p(4096)
+    di.batch = 0
+    assert lib.fastav_decode_step(h, C.byref(di), fake, fake, 1 << 20, None) == B.EINVAL     # batch out of range
+    di.batch = 2
+    assert lib.fastav_decode_step(h, C.byref(di), fake, fake, 1 << 20, None) == B.EINVAL     # NULL inputs
+    assert b"must be non-NULL" in lib.fastav_last_error()
+    f32 = C.c_void_p()
+    assert lib.fastav_create(C.byref(fa.make_model(1, 256, 4, 2, 64, 256, dtype=fa.F32)), C.byref(f32)) == B.OK
+    assert lib.fastav_decode_step(f32, C.byref(di), fake, fake, 1 << 20, None) == B.EUNSUPPORTED   # fp32 model
+    lib.fastav_destroy(h)
+    lib.fastav_destroy(f32)
