@@ -23,12 +23,14 @@ def _cu(lens):
 
 
 # ------------------------------------------------------------------------------------ select + gather
-def _select_case(lens, score_kind, seed, prot_frac=0.1, ratio=0.6, positional=False):
+def _select_case(lens, score_kind, seed, prot_frac=0.1, ratio=0.6, positional=False, negate=False):
     rng = np.random.default_rng(seed)
     cu = _cu(lens)
     T = int(cu[-1])
     kind = score_kind or "softmax"
     scores = np.concatenate([fi.random_scores(n, seed + i, kind) if n else np.zeros(0, np.float32) for i, n in enumerate(lens)])
+    if negate:
+        scores = -scores
     prot = (rng.random(T) < prot_frac)
     for b in range(len(lens)):
         if lens[b] > 0:
@@ -75,6 +77,14 @@ def test_select_gather_long_samples():
     _select_case([16384], "softmax", 21, ratio=0.7)
     _select_case([32768, 33000], "ties", 22, ratio=0.5)            # second sample exceeds the LDS-resident limit
     _select_case([70001], "softmax", 23, ratio=0.35)
+
+
+def test_select_variant_strategies_of_the_ablation_tables():
+    """Tables 2-3 compare selectors: keeping the LEAST attended tokens is the same selection on negated
+    scores (signed zeros and ties included), a random selector the same selection on random scores."""
+    _select_case([4096, 777], "softmax", 41, ratio=0.5, negate=True)
+    _select_case([300, 1, 900], "ties", 42, prot_frac=0.3, ratio=0.4, negate=True)
+    _select_case([2000], "equal", 43, ratio=0.5, negate=True)
 
 
 def test_select_positional_is_the_global_rule():
@@ -187,7 +197,9 @@ def test_linear(dtype, M, N, K, epi):
 # ------------------------------------------------------------------------------------ attention (+ side output)
 @pytest.mark.parametrize("dtype,Hq,Hkv,dh,lens", [("f32", 4, 2, 64, [130, 1, 77]), ("bf16", 8, 2, 128, [300, 129, 64]),
                                                  ("bf16", 4, 4, 64, [200, 65]), ("bf16", 32, 8, 128, [700]),
-                                                 ("bf16", 28, 4, 128, [257, 500])])
+                                                 ("bf16", 28, 4, 128, [257, 500]),
+                                                 ("bf16", 8, 2, 128, [1, 2, 33, 63, 128, 256, 191]),   # shorter than a tile, exact tile multiples
+                                                 ("bf16", 4, 2, 64, [1, 31, 64, 127, 385])])
 def test_attention_and_last_row_side_output(dtype, Hq, Hkv, dh, lens):
     rng = np.random.default_rng(Hq + dh + len(lens))
     T = sum(lens)
@@ -390,6 +402,26 @@ def test_prefill_paper_schedule_fine_prune_at_every_later_layer():
     st = _check_prefill(w, out, ref)
     for b in range(2):
         assert st[f"x_rel_l2_{b}"] <= 2e-2 and st[f"x_max_abs_over_rms_{b}"] <= 0.1, st
+
+
+def test_prefill_frame_interleaved_spans():
+    """video-SALMONN2 layout (Section 3.1, implementation details): video and audio tokens interleaved frame by
+    frame; the global prune keeps the first frames (earliest candidates), text stays."""
+    m = fi.Model(3, 512, 8, 2, 128, 1024, 1.0e4, 1e-6, "bf16")
+    frames = []
+    for f in range(10):
+        frames += [(fi.VIDEO, 36), (fi.AUDIO, 13)]
+    s0 = [(fi.TEXT, 7)] + frames + [(fi.TEXT, 21)]
+    s1 = frames[:8] + [(fi.TEXT, 5)]
+    # keep 4 of 10 frames: 4 * 49 candidates + 28 text of 518 tokens
+    w = fi.Workload("interleaved", m, [s0, s1], [fi.Prune(1, fi.GLOBAL, (4 * 49 + 28) / 518), fi.Prune(2, fi.FINE, 0.8)], seed=47)
+    weights = [fi.layer_weights(m, l, 11) for l in range(m.n_layers)]
+    out, ref = _oracle_and_gpu(w, weights, fi.embeddings(w), want_kv=False)
+    st = _check_prefill(w, out, ref)
+    g = ref[0]["prunes"][0]
+    assert g["k"] == 4 * 49 + 28 and g["keep"].tolist() == list(range(7 + 4 * 49)) + list(range(497, 518))
+    for b in range(2):
+        assert st[f"x_rel_l2_{b}"] <= 1e-2, st
 
 
 def test_prefill_cfg2_7b_single_layer():
