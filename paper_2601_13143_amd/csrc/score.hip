@@ -134,9 +134,11 @@ __global__ __launch_bounds__(256) void k_score_logits(const T* __restrict__ q, i
 // query row and four consecutive keys: it scales, masks, stores them and keeps a running (max, sum-exp)
 // for its row.  The matrix cores run mostly on padding here (4 of 16 columns at GQA 4:1); that costs
 // nothing next to the HBM stream this kernel is bound by.
-// Wave w of workgroup (x, b, z) handles KV head w + 4 z over kScoreChunk keys of sample b.
+// Wave w of workgroup (x, b, z) handles KV head w + W z over kScoreChunk keys of sample b, W = waves per
+// workgroup (up to 8): with all KV heads of a key chunk in one workgroup the chunk is one contiguous run of
+// whole K rows.
 template <int DH, int NBMAX>
-__global__ __launch_bounds__(256) void k_score_logits_mfma(const bf16_t* __restrict__ q, int64_t q_stride,
+__global__ __launch_bounds__(512) void k_score_logits_mfma(const bf16_t* __restrict__ q, int64_t q_stride,
                                                            const bf16_t* __restrict__ k, int64_t k_stride,
                                                            const int32_t* __restrict__ cu, int Hq, int Hkv, int n_last,
                                                            float scale, int64_t T_total, int64_t n_chunk_slots,
@@ -148,7 +150,7 @@ __global__ __launch_bounds__(256) void k_score_logits_mfma(const bf16_t* __restr
   const int row0 = cu[b], n = cu[b + 1] - row0;
   const int j0 = blockIdx.x * kScoreChunk;
   if (j0 >= n) return;
-  const int g = threadIdx.x / 64 + 4 * (int)blockIdx.z;
+  const int g = threadIdx.x / 64 + (int)(blockDim.x / 64) * (int)blockIdx.z;
   if (g >= Hkv) return;                      // no barriers below, so a wave may simply leave
   const int n_rows = n_last < n ? n_last : n;
   const int G = Hq / Hkv;
@@ -185,15 +187,21 @@ __global__ __launch_bounds__(256) void k_score_logits_mfma(const bf16_t* __restr
     }
   }
 
-#pragma unroll 2
+  // A operands of the whole chunk are requested up front (KG * NSTEP 16-byte loads per lane in flight): the
+  // kernel is a pure HBM stream and this is what keeps the memory system busy.  lane = key l16 of a group,
+  // head_dim chunk l4.
+  bf16x8_t ka_all[KG][NSTEP];
+#pragma unroll
   for (int kg = 0; kg < KG; ++kg) {
-    // A operand: lane = key l16 of the group, head_dim chunk l4
     const int akey = j0 + kg * 16 + l16;
     const int kr = akey < n ? akey : n - 1;
     const bf16_t* kp = k + (int64_t)(row0 + kr) * k_stride + g * DH + l4 * 8;
-    bf16x8_t ka[NSTEP];
 #pragma unroll
-    for (int st = 0; st < NSTEP; ++st) ka[st] = *(const bf16x8_t*)(kp + st * 32);
+    for (int st = 0; st < NSTEP; ++st) ka_all[kg][st] = *(const bf16x8_t*)(kp + st * 32);
+  }
+#pragma unroll
+  for (int kg = 0; kg < KG; ++kg) {
+    const bf16x8_t (&ka)[NSTEP] = ka_all[kg];
     const int key0 = j0 + kg * 16 + l4 * 4;  // result rows of this lane: keys key0 .. key0+3
 #pragma unroll
     for (int rb = 0; rb < NBMAX; ++rb) {
@@ -262,30 +270,44 @@ __global__ __launch_bounds__(256) void k_score_finalize(const float* __restrict_
       mls[2 * idx] = p[0]; mls[2 * idx + 1] = 1.0f / p[1];
     }
   } else {
-    // merge the per-chunk (max, sum-exp) partials: one wave per (row, head), lanes strided over the chunks
+    // merge the per-chunk (max, sum-exp) partials: eight lanes per (row, head) pair, strided over the chunks,
+    // 32 pairs per pass of the workgroup (every workgroup of a sample repeats this small merge, so it is laid
+    // out for few dependent steps: independent loads, then two 8-lane butterflies)
     const int nc = (n + kScoreChunk - 1) / kScoreChunk;
-    const int lane = threadIdx.x & 63;
-    for (int idx = threadIdx.x >> 6; idx < n_rows * Hq; idx += 4) {
-      const int rl = idx / Hq, h = idx % Hq;
+    const int sub = threadIdx.x & 7;
+    for (int base = 0; base < n_rows * Hq; base += 32) {
+      const int idx = base + (threadIdx.x >> 3);
+      const bool live = idx < n_rows * Hq;
+      const int rl = live ? idx / Hq : 0, h = live ? idx % Hq : 0;
       const float* p = partials + (((int64_t)rl * Hq + h) * n_chunk_slots + row0 / kScoreChunk + b) * 2;
       float m = -INFINITY;
-      for (int c = lane; c < nc; c += 64) m = fmaxf(m, p[2 * c]);
-      m = wave_max(m);
+      if (live) for (int c = sub; c < nc; c += 8) m = fmaxf(m, p[2 * c]);
+#pragma unroll
+      for (int o = 1; o < 8; o <<= 1) m = fmaxf(m, __shfl_xor(m, o, kWave));
       float l = 0.f;
-      for (int c = lane; c < nc; c += 64) { const float mc = p[2 * c]; if (mc > -INFINITY) l += p[2 * c + 1] * expf(mc - m); }
-      l = wave_sum(l);
-      if (lane == 0) { mls[2 * idx] = m; mls[2 * idx + 1] = 1.0f / l; }
+      if (live) for (int c = sub; c < nc; c += 8) { const float mc = p[2 * c]; if (mc > -INFINITY) l += p[2 * c + 1] * expf(mc - m); }
+#pragma unroll
+      for (int o = 1; o < 8; o <<= 1) l += __shfl_xor(l, o, kWave);
+      if (live && sub == 0) { mls[2 * idx] = m; mls[2 * idx + 1] = 1.0f / l; }
     }
   }
   __syncthreads();
   const int j = blockIdx.x * 256 + threadIdx.x;
   if (j >= n) return;
+  // eight loads in flight per lane; the terms are added in index order, as a plain loop would
+  const int P = n_rows * Hq;
+  const float* lp = logits + row0 + j;                            // idx = rl*Hq + h selects the plane
   float s = 0.f;
-  for (int idx = 0; idx < n_rows * Hq; ++idx) {
-    const float L = logits[(int64_t)idx * T_total + row0 + j];   // idx = rl*Hq + h
-    s += expf(L - mls[2 * idx]) * mls[2 * idx + 1];
+  int idx = 0;
+  for (; idx + 8 <= P; idx += 8) {
+    float L[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) L[u] = lp[(int64_t)(idx + u) * T_total];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += expf(L[u] - mls[2 * (idx + u)]) * mls[2 * (idx + u) + 1];
   }
-  scores[row0 + j] = s / (float)(n_rows * Hq);
+  for (; idx < P; ++idx) s += expf(lp[(int64_t)idx * T_total] - mls[2 * idx]) * mls[2 * idx + 1];
+  scores[row0 + j] = s / (float)P;
 }
 
 // Chunk slots of the whole packed batch: sample b's chunks start at slot cu[b]/chunk + b.
@@ -330,9 +352,10 @@ fastav_status_t launch_score_logits(const void* q, int64_t q_stride, const void*
   if (shmem > 64 * 1024) return fail(FASTAV_EUNSUPPORTED, "score: n_q_heads*(head_dim+128)*4 bytes must fit 64 KB of LDS");
   if (dtype == FASTAV_BF16 && G * n_last <= 64 && q_stride % 8 == 0 && k_stride % 8 == 0 &&
       (((uintptr_t)q | (uintptr_t)k) % 16) == 0) {
-    const dim3 grid_m(grid.x, grid.y, (unsigned)((Hkv + 3) / 4));
+    const int wpg = Hkv < 8 ? Hkv : 8;                            // waves (KV heads) per workgroup
+    const dim3 grid_m(grid.x, grid.y, (unsigned)((Hkv + wpg - 1) / wpg));
 #define FASTAV_SCORE_MFMA(DHH, NBB)                                                                                      \
-  hipLaunchKernelGGL((k_score_logits_mfma<DHH, NBB>), grid_m, dim3(256), 0, s, (const bf16_t*)q, q_stride, (const bf16_t*)k, \
+  hipLaunchKernelGGL((k_score_logits_mfma<DHH, NBB>), grid_m, dim3(64 * wpg), 0, s, (const bf16_t*)q, q_stride, (const bf16_t*)k, \
                      k_stride, cu, Hq, Hkv, n_last, scale, T, ncm, logits, partials)
     const bool one = G * n_last <= 16;
     if (dh == 128) { if (one) FASTAV_SCORE_MFMA(128, 1); else FASTAV_SCORE_MFMA(128, 4); }
