@@ -468,8 +468,10 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
       cur ^= 1; ++stage; ++pi;
       attn_cur = attn[1];
     } else {
-      if (k_out) FASTAV_TRY(launch_copy_rows(kptr, qkv_stride * (int64_t)es, k_out, (int64_t)kd * (int64_t)es, Tl, nullptr, s));
-      if (v_out) FASTAV_TRY(launch_copy_rows(vptr, qkv_stride * (int64_t)es, v_out, (int64_t)kd * (int64_t)es, Tl, nullptr, s));
+      // this layer's K and V rows go to the caller's cache in one launch
+      GatherTensor kvc[2] = {{kptr, k_out, k_out ? (int64_t)kd * (int64_t)es : 0, qkv_stride * (int64_t)es},
+                             {vptr, v_out, v_out ? (int64_t)kd * (int64_t)es : 0, qkv_stride * (int64_t)es}};
+      if (k_out || v_out) FASTAV_TRY(launch_gather(kvc, 2, nullptr, Tl, s));
     }
     const int64_t To = T_stage[stage];
     FASTAV_TRY(launch_linear(attn_cur, W.wo, nullptr, resid[cur], To, m.hidden, qd, FASTAV_EPI_RESADD, m.dtype, gscr, ws.gemm_scratch_bytes, s));

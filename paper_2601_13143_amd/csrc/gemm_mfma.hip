@@ -23,8 +23,6 @@
 // Workgroup ids are first re-dealt so that each of the 8 XCDs (ids are dispatched round-robin over them)
 // owns a contiguous run of tiles, then walk M fastest: the 32 CUs of an XCD share a few W panels and the
 // A panels through their common L2.
-#include <cstdlib>
-
 #include "common.hpp"
 
 namespace fastav {
@@ -59,18 +57,20 @@ template <int N> __device__ __forceinline__ void dma_wait_keep() {   // until at
 
 __device__ __forceinline__ int swz4(int row, int chunk) { return row * 4 + (chunk ^ ((row >> 2) & 3)); }   // 16-byte units
 
-template <int BM, int BN, int WM, int WN, int EPI>
-__global__ __launch_bounds__(WM * WN * 64) void k_gemm_mfma(GemmArgs g) {
+// NST = LDS ring depth in stages of 32 k (copies run NST-1 stages ahead).  A 256 x 128 tile with 4 waves and
+// NST = 3 lets two workgroups share a CU (one computes while the other sits in its prologue, epilogue or at a
+// barrier); it measured 15 % slower than one 8-wave 256 x 256 workgroup with NST = 4 on every shape of the 7B
+// model (half again as many copy bytes per flop, copies only two stages ahead), so nothing launches it.
+template <int BM, int BN, int WM, int WN, int EPI, int NST = 4>
+__global__ __launch_bounds__(WM * WN * 64, (WM * WN == 4 && NST == 3) ? 2 : 1) void k_gemm_mfma(GemmArgs g) {
   constexpr int NW = WM * WN;                          // waves
   constexpr int WTM = BM / WM, WTN = BN / WN;          // wave tile
   constexpr int TM = WTM / 32, TN = WTN / 32;          // 32x32 blocks per wave
-  constexpr int NST = 4;                               // LDS stages of 32 k
   constexpr int A_D = BM / (16 * NW), B_D = BN / (16 * NW);   // copy instructions per wave and stage
   constexpr int D = A_D + B_D;
   constexpr int NMF = TM * TN;                         // MFMAs per k-slice
-  constexpr int GRP = NMF / (D / 2);                   // MFMAs between two copies
   constexpr int OUT_BN = (EPI == FASTAV_EPI_SWIGLU) ? BN / 2 : BN;
-  static_assert(A_D >= 1 && B_D >= 1 && D % 2 == 0 && NMF % (D / 2) == 0 && TN % 2 == 0, "tile shape");
+  static_assert(A_D >= 1 && B_D >= 1 && D % 2 == 0 && NMF >= D / 2 && TN % 2 == 0 && NST >= 3, "tile shape");
   extern __shared__ bf16x8_t lds[];
   bf16x8_t* A4 = lds;                                  // [NST][BM*4]
   bf16x8_t* B4 = lds + NST * BM * 4;                   // [NST][BN*4]
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_mfma(GemmArgs g) {
   // redundant copies per workgroup.
   auto dma_one = [&](int t, int c) {
     const int koff = (t < KT ? t : KT - 1) * 32;
-    const uint32_t slot = (uint32_t)(t & (NST - 1));
+    const uint32_t slot = (uint32_t)t % (uint32_t)NST;
     if (c < A_D) dma16(a_src[c < A_D ? c : 0] + koff, a_dst[c < A_D ? c : 0] + slot * (BM * 64u));
     else dma16(b_src[c >= A_D ? c - A_D : 0] + koff, b_dst[c >= A_D ? c - A_D : 0] + slot * (BN * 64u));
   };
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_mfma(GemmArgs g) {
 #pragma unroll
     for (int grp = 0; grp < D / 2; ++grp) {
 #pragma unroll
-      for (int q = grp * GRP; q < (grp + 1) * GRP; ++q) {
+      for (int q = grp * NMF / (D / 2); q < (grp + 1) * NMF / (D / 2); ++q) {     // MFMAs between two copies
         const int i = q / TN, j = q % TN;
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
       }
@@ -186,23 +186,23 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_mfma(GemmArgs g) {
     }
   };
 
-  // ---- prologue: three stages in flight, the first one landed and published
+  // ---- prologue: NST-1 stages in flight, the first one landed and published
 #pragma unroll
-  for (int t = 0; t < 3; ++t)
+  for (int t = 0; t < NST - 1; ++t)
 #pragma unroll
     for (int c = 0; c < D; ++c) dma_one(t, c);
-  dma_wait_keep<2 * D>();
+  dma_wait_keep<(NST - 2) * D>();
   __syncthreads();
   frags(0, 0, 0);
 
   for (int t = 0; t < KT; ++t) {
-    // the ring slot of stage t+3 held stage t-1, which nobody reads after the previous barrier
-    frags(1, t & (NST - 1), 1);
-    slice(0, t + 3, 0);
-    dma_wait_keep<D + D / 2>();                          // stage t+1 has landed (this wave's share)
+    // the ring slot of stage t+NST-1 held stage t-1, which nobody reads after the previous barrier
+    frags(1, (uint32_t)t % (uint32_t)NST, 1);
+    slice(0, t + NST - 1, 0);
+    dma_wait_keep<(NST - 3) * D + D / 2>();              // stage t+1 has landed (this wave's share)
     __syncthreads();
-    frags(0, (t + 1) & (NST - 1), 0);                    // (after the last stage: a harmless read of an idle slot)
-    slice(1, t + 3, D / 2);
+    frags(0, (uint32_t)(t + 1) % (uint32_t)NST, 0);                          // (after the last stage: a harmless read of an idle slot)
+    slice(1, t + NST - 1, D / 2);
   }
   dma_wait_keep<0>();
 
@@ -273,7 +273,7 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(float* __restrict__ R, in
 }
 
 // Launches tile columns [col0, col0 + ncols) (in units of the tile's output width) of the GEMM.
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int WM, int WN, int EPI, int NST = 4>
 static fastav_status_t launch_cfg(GemmArgs g, int col0, int ncols, int splits, hipStream_t s) {
   constexpr int OUT_BN = (EPI == FASTAV_EPI_SWIGLU) ? BN / 2 : BN;
   g.tiles_m = (g.M + BM - 1) / BM;
@@ -281,12 +281,12 @@ static fastav_status_t launch_cfg(GemmArgs g, int col0, int ncols, int splits, h
   g.n_off = col0 * OUT_BN;
   g.splits = splits;
   g.band = (g.tiles_m * g.tiles_n > kNumCUs) ? 4 : 1;
-  const size_t shmem = (size_t)4 * (BM + BN) * 4 * sizeof(bf16x8_t);
+  const size_t shmem = (size_t)NST * (BM + BN) * 4 * sizeof(bf16x8_t);
   if (shmem > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WM, WN, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    hipError_t e = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WM, WN, EPI, NST>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     if (e != hipSuccess) return fail(FASTAV_EHIP, "gemm: hipFuncSetAttribute: %s", hipGetErrorString(e));
   }
-  hipLaunchKernelGGL((k_gemm_mfma<BM, BN, WM, WN, EPI>), dim3((unsigned)(g.tiles_m * g.tiles_n), (unsigned)splits),
+  hipLaunchKernelGGL((k_gemm_mfma<BM, BN, WM, WN, EPI, NST>), dim3((unsigned)(g.tiles_m * g.tiles_n), (unsigned)splits),
                      dim3(WM * WN * 64), shmem, s, g);
   return check_launch("gemm_mfma");
 }

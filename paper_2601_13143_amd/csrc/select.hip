@@ -280,7 +280,8 @@ fastav_status_t launch_gather(const GatherTensor* t, int n_tensors, const int32_
     a.dst_stride[m] = t[i].row_bytes; ++m;
   }
   for (int i = m; i < FASTAV_MAX_GATHER_TENSORS; ++i) { a.src[i] = nullptr; a.dst[i] = nullptr; a.row_bytes[i] = 0; a.src_stride[i] = 0; a.dst_stride[i] = 0; }
-  return gather_impl(a, m, keep_idx, n_rows, FASTAV_PROF_GATHER, s);
+  // without an index this is a plain copy (KV-cache write), timed apart from the prune-step gathers
+  return gather_impl(a, m, keep_idx, n_rows, keep_idx ? FASTAV_PROF_GATHER : FASTAV_PROF_OTHER, s);
 }
 
 fastav_status_t launch_copy_rows(const void* src, int64_t src_row_bytes_stride, void* dst, int64_t row_bytes,
