@@ -48,7 +48,8 @@ special cases (torch SDPA / rms_norm / silu, numpy stable argsort), closed forms
 (zero queries -> uniform scores; one dominant key -> one-hot), invariants (rows
 sum to 1, keep ratio 1.0 is the identity, RoPE relative-position property,
 batched == per-sample; a decode step on unpruned caches equals the last row of a
-prefill one token longer; cache order does not matter), and the paper's printed
+prefill one token longer; cache order does not matter; rollout rows sum to 1, alpha = 0
+gives the identity, uniform attention has a closed form), and the paper's printed
 FLOPs column of Table 4 for the schedule semantics.  Parity unpinned: the absolute hidden-state values for random
 weights (the paper prints no worked numeric example).
 """
@@ -335,6 +336,47 @@ def decode_step(m, weights, x_new: np.ndarray, pos_new: int, kv: Sequence[Tuple[
         x = layer_finish(x, attn[None], W, m)
         new_kv.append((k[0], v[0]))
     return {"x_out": x[0], "kv": new_kv}
+
+
+# --------------------------------------------------------------------------- attention rollout (Eq. 2-3)
+def head_mean_attention_map(q: np.ndarray, k: np.ndarray) -> np.ndarray:
+    """A^l of Section 2.2: the causal attention weights of one layer averaged over the query heads.
+
+    q[n,Hq,dh], k[n,Hkv,dh] post-RoPE (readings R1-R3) -> A[n,n]; row i is token i's attention distribution
+    over tokens 0..i (it sums to 1, entries right of the diagonal are 0)."""
+    n, Hq, dh = q.shape
+    G = Hq // k.shape[1]
+    A = np.zeros((n, n), dtype=np.float64)
+    rows, cols = np.arange(n)[:, None], np.arange(n)[None, :]
+    for h in range(Hq):
+        z = (q[:, h, :].astype(np.float64) @ k[:, h // G, :].astype(np.float64).T) / math.sqrt(dh)
+        A += _softmax_rows(np.where(cols <= rows, z, -np.inf))
+    return A / Hq
+
+
+def rollout_step(R_prev: np.ndarray, A: np.ndarray, alpha: float) -> np.ndarray:
+    """Eq. 2 then one factor of Eq. 3: R^l = (alpha A^l + (1 - alpha) I) R^{l-1}."""
+    n = A.shape[0]
+    return (alpha * A + (1.0 - alpha) * np.eye(n)) @ R_prev
+
+
+def attention_rollout(m, weights, x: np.ndarray, alpha: float, dtype=np.float64) -> List[np.ndarray]:
+    """R^1 .. R^L of Eq. 3 for one sample run through the UNPRUNED decoder (the paper computes the rollout on
+    the full model to decide where to prune).  Entry [i, j] of R^l says how much input token j influences token
+    i after l layers; every row sums to 1 and the matrices are lower triangular."""
+    get_w = weights if callable(weights) else (lambda l: weights[l])
+    x = np.asarray(x, dtype=dtype)
+    n = x.shape[0]
+    pos = np.arange(n, dtype=np.int64)
+    R = np.eye(n)
+    out = []
+    for l in range(m.n_layers):
+        W = {name: np.asarray(a, dtype=dtype) for name, a in get_w(l).items()}
+        q, k, v = layer_qkv(x, W, pos, m)
+        R = rollout_step(R, head_mean_attention_map(q, k), alpha)
+        out.append(R)
+        x = layer_finish(x, causal_gqa_attention(q, k, v), W, m)
+    return out
 
 
 # --------------------------------------------------------------------------- FLOPs accounting

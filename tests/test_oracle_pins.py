@@ -378,3 +378,45 @@ def test_decode_step_on_pruned_caches_sees_a_set_of_keys():
     want = np.array(brute.attention_output(qq.tolist(), K.tolist(), V.tolist(), m.n_q_heads // m.n_kv_heads)[nk - 1])
     got = orc.single_query_attention(q[0], K, V)
     np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-12)
+
+
+# ------------------------------------------------------------------------------------ attention rollout (Eq. 2-3)
+def test_attention_map_is_the_head_mean_of_brute_force_maps():
+    rng = np.random.default_rng(4)
+    n, Hq, Hkv, dh = 9, 4, 2, 8
+    q, k = rng.standard_normal((n, Hq, dh)), rng.standard_normal((n, Hkv, dh))
+    A = orc.head_mean_attention_map(q, k)
+    want = np.mean([np.array(brute.attention_map(q.tolist(), k.tolist(), h, Hq // Hkv)) for h in range(Hq)], axis=0)
+    np.testing.assert_allclose(A, want, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(A.sum(axis=1), 1.0, rtol=1e-13)
+    assert np.all(np.triu(A, 1) == 0.0)
+    # its last row is Eq. 4's score vector: the fine prune and the rollout look at the same attention weights
+    np.testing.assert_allclose(A[-1], orc.last_query_scores(q, k), rtol=1e-12, atol=1e-15)
+
+
+def test_rollout_matches_explicit_products_and_closed_forms():
+    m, w, weights, x = _tiny()
+    alpha = 0.6
+    R = orc.attention_rollout(m, weights, x, alpha)
+    assert len(R) == m.n_layers
+    # Eq. 3 by explicit loops over the layer maps, in the printed order (newest factor on the left)
+    out = orc.prefill(fi.unpruned(w), weights, x, trace=True)[0]
+    n = x.shape[0]
+    At = [alpha * orc.head_mean_attention_map(t["q"], t["k"]) + (1 - alpha) * np.eye(n) for t in out["trace"]]
+    prod = [[float(i == j) for j in range(n)] for i in range(n)]
+    for A in At:                                            # triple loop: prod = A @ prod
+        prod = [[sum(A[i][kk] * prod[kk][j] for kk in range(n)) for j in range(n)] for i in range(n)]
+    np.testing.assert_allclose(R[-1], np.array(prod), rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(R[1], At[1] @ At[0], rtol=1e-12, atol=1e-14)
+    for r in R:
+        np.testing.assert_allclose(r.sum(axis=1), 1.0, rtol=1e-12)      # product of row-stochastic matrices
+        assert np.all(np.triu(r, 1) == 0.0) and (r >= 0).all()
+    # alpha = 0 keeps every token's own representation only
+    for r in orc.attention_rollout(m, weights, x, 0.0):
+        np.testing.assert_array_equal(r, np.eye(n))
+    # uniform attention (Wq = 0): A[i][j] = 1/(i+1) for j <= i in every layer
+    flat = [dict(W, wq=np.zeros_like(W["wq"])) for W in weights]
+    U = np.tril(np.ones((n, n))) / np.arange(1, n + 1)[:, None]
+    R1 = orc.attention_rollout(m, flat, x, 1.0)
+    np.testing.assert_allclose(R1[0], U, rtol=1e-12)
+    np.testing.assert_allclose(R1[2], U @ U @ U, rtol=1e-11)
