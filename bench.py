@@ -290,6 +290,19 @@ def main():
     if not args.no_kernel_passes:
         decode = _decode_bench(fa, torch, dec, m, w, x, cu, spans, offs, prunes)
 
+    rollout = None
+    if not args.no_kernel_passes and m.dtype == "bf16" and len(w.samples) == 1 and w.prunes and tokens % 4 == 0:
+        # the analysis behind the global prune (Eq. 2-3): rollout up to the global-prune layer, alpha 0.5
+        upto = max(1, w.prunes[0].layer)
+        dec.fastav_rollout(x, 0.5, upto)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        R = dec.fastav_rollout(x, 0.5, upto)
+        torch.cuda.synchronize()
+        rollout = {"layers": upto, "alpha": 0.5, "ms": (time.perf_counter() - t0) * 1e3,
+                   "max_row_sum_error": float((R.sum(dim=1) - 1.0).abs().max())}
+        del R
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = _cpu_baseline(w, host_threads)
@@ -314,6 +327,7 @@ def main():
         "kernels": kernels,
         "prune_kernels_stress": stress,
         "decode_step": decode,
+        "rollout": rollout,
         "cpu_baseline": cpu,
         "setup_s": setup_s,
     }

@@ -252,6 +252,28 @@ fastav_status_t fastav_decode_workspace_bytes(fastav_handle_t h, int32_t max_bat
 fastav_status_t fastav_decode_step(fastav_handle_t h, const fastav_decode_in_t* in, float* x_out, void* workspace,
                                    size_t workspace_bytes, void* stream);
 
+/* ---- attention rollout (Section 2.2, Eq. 2-3): the analysis behind the global-pruning decision -------------
+ * A^l = causal attention weights of layer l averaged over the query heads; A~^l = alpha A^l + (1 - alpha) I;
+ * R^l = A~^l A~^(l-1) ... A~^1.  Entry [i][j] of R^l is the influence of input token j on token i after l layers.
+ *
+ * fastav_attention_map: q [n, >= Hq*dh], k [n, >= Hkv*dh] (device, bf16, post-RoPE, ONE sample, explicit row
+ * strides in elements) -> a_out: device bf16 [n, n], row i = token i's head-mean attention over tokens 0..i
+ * (zeros right of the diagonal).  n must be a multiple of 4.  workspace: device, 256-byte aligned,
+ * fastav_attention_map_workspace_bytes(n, Hq) bytes of scratch. */
+size_t fastav_attention_map_workspace_bytes(int32_t n, int32_t n_q_heads);
+fastav_status_t fastav_attention_map(const fastav_model_t* model, const void* q, int64_t q_row_stride, const void* k,
+                                     int64_t k_row_stride, int32_t n, void* a_out, void* workspace,
+                                     size_t workspace_bytes, void* stream);
+/* fastav_rollout: runs ONE sample x [n, hidden] (device, model dtype, bf16 models) through the first
+ * upto_layers layers of the UNPRUNED decoder and accumulates Eq. 3 with the given alpha in [0, 1].
+ * rt_out: device fp32 [n, n] receives the TRANSPOSE of R^upto_layers (rt_out[j][i] = R[i][j]: the library's
+ * GEMM multiplies by row-major [out, in] matrices, so the product is carried transposed).  The map of every
+ * layer is rounded to bf16 and the running product is fed to the GEMM as bf16 (fp32 master copy).
+ * Errors: FASTAV_EINVAL (arguments), FASTAV_EUNSUPPORTED (fp32 model), FASTAV_EWORKSPACE. */
+fastav_status_t fastav_rollout_workspace_bytes(fastav_handle_t h, int32_t n, size_t* out);
+fastav_status_t fastav_rollout(fastav_handle_t h, const void* x, int32_t n, float alpha, int32_t upto_layers,
+                               float* rt_out, void* workspace, size_t workspace_bytes, void* stream);
+
 typedef enum {
   FASTAV_PROF_LINEAR_STORE = 0, FASTAV_PROF_LINEAR_RESADD = 1, FASTAV_PROF_LINEAR_SWIGLU = 2,
   FASTAV_PROF_ATTENTION = 3, FASTAV_PROF_SCORE = 4, FASTAV_PROF_SELECT = 5, FASTAV_PROF_GATHER = 6,

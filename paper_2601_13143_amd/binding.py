@@ -77,6 +77,12 @@ _SIGS = {
     "fastav_schedule_lens": (C.c_int, [C.POINTER(Batch), C.POINTER(Prune), C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
     "fastav_decode_workspace_bytes": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_size_t)]),
     "fastav_decode_step": (C.c_int, [C.c_void_p, C.POINTER(DecodeIn), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "fastav_attention_map_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32]),
+    "fastav_attention_map": (C.c_int, [C.POINTER(Model), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p,
+                                       C.c_void_p, C.c_size_t, C.c_void_p]),
+    "fastav_rollout_workspace_bytes": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_size_t)]),
+    "fastav_rollout": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
+                                 C.c_void_p]),
     "fastav_create": (C.c_int, [C.POINTER(Model), C.POINTER(C.c_void_p)]),
     "fastav_destroy": (None, [C.c_void_p]),
     "fastav_set_weights": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(LayerWeights)]),
@@ -319,6 +325,34 @@ class Decoder:
                       st["max_prefix"].ctypes.data_as(C.POINTER(C.c_int32)), kg, vg, gen_len, gen_cap)
         _check(lib().fastav_decode_step(self._h, C.byref(di), st["x_out"].data_ptr(), st["ws"].data_ptr(), st["ws"].numel(), _stream()))
         return {"x_out": st["x_out"], "state": st}
+
+
+    def fastav_rollout(self, x: torch.Tensor, alpha: float, upto_layers: Optional[int] = None) -> torch.Tensor:
+        """Eq. 3 for one sample x [n, hidden] through the first ``upto_layers`` layers of the unpruned decoder.
+        -> fp32 [n, n] view of R^l (the library writes its transpose; the view flips it back)."""
+        m = self.model
+        n = x.shape[0]
+        L = m.n_layers if upto_layers is None else upto_layers
+        if x.dtype != self.torch_dtype or not x.is_contiguous() or x.shape[1] != m.hidden:
+            raise ValueError("x must be a contiguous [n, hidden] tensor in the model dtype")
+        need = C.c_size_t()
+        _check(lib().fastav_rollout_workspace_bytes(self._h, n, C.byref(need)))
+        ws = torch.empty(need.value, dtype=torch.uint8, device=x.device)
+        rt = torch.empty((n, n), dtype=torch.float32, device=x.device)
+        _check(lib().fastav_rollout(self._h, x.data_ptr(), n, alpha, L, rt.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+        return rt.t()
+
+
+def fastav_attention_map(model: Model, q: torch.Tensor, k: torch.Tensor) -> torch.Tensor:
+    """q [n, Hq, dh], k [n, Hkv, dh] (bf16, post-RoPE, one sample; views with a row stride are fine)
+    -> bf16 [n, n] head-mean causal attention map."""
+    n = q.shape[0]
+    a = torch.empty((n, n), dtype=torch.bfloat16, device=q.device)
+    need = lib().fastav_attention_map_workspace_bytes(n, model.n_q_heads)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    _check(lib().fastav_attention_map(C.byref(model), q.data_ptr(), q.stride(0), k.data_ptr(), k.stride(0), n, a.data_ptr(),
+                                      ws.data_ptr(), ws.numel(), _stream()))
+    return a
 
 
 def fastav_score(model: Model, q: torch.Tensor, k: torch.Tensor, cu_seqlens_dev: torch.Tensor, max_seqlen: int,

@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfastav.so")
 
-SOURCES = ["api", "elementwise", "score", "select", "gemm_generic", "attn_generic", "gemm_mfma", "attn_mfma", "decode", "profile"]
+SOURCES = ["api", "elementwise", "score", "select", "gemm_generic", "attn_generic", "gemm_mfma", "attn_mfma", "decode", "rollout", "profile"]
 
 # packed fp32 VALU forms are switched off for every device compile
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

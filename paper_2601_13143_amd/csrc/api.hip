@@ -58,6 +58,14 @@ fastav_status_t launch_decode_attention(const void* q, const void* k_self, const
                                         size_t part_bytes, void* out, int64_t out_stride, double bytes_hint,
                                         hipStream_t s);
 
+size_t attention_map_stats_bytes(int n, int Hq);
+fastav_status_t launch_attention_map(const void* q, int64_t q_stride, const void* k, int64_t k_stride, int n, int Hq,
+                                     int Hkv, int dh, float* stats, void* a_out, hipStream_t s);
+fastav_status_t launch_iota(int32_t* p, int n, hipStream_t s);
+fastav_status_t launch_rollout_init(float* rt, void* rt16, int n, hipStream_t s);
+fastav_status_t launch_rollout_step(float* rt, void* rt16, const void* a16, float* c, int n, float alpha,
+                                    void* linear_ws, size_t linear_ws_bytes, hipStream_t s);
+
 // One linear layer whose weight rows may come from up to three matrices stacked along N (Q|K|V).
 static fastav_status_t linear_segments(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
                                        const void* w2, void* c, int64_t ldc, int64_t m, int k, int epilogue, int dtype,
@@ -703,6 +711,110 @@ fastav_status_t fastav_decode_step(fastav_handle_t h, const fastav_decode_in_t* 
     FASTAV_TRY(launch_skinny_linear(hmlp, sd, ro, 1, nullptr, x, m.hidden, B, m.hidden, m.mlp_dim, FASTAV_EPI_RESADD, s));
   }
   FASTAV_TRY(launch_copy_rows(x, (int64_t)m.hidden * 4, x_out, (int64_t)m.hidden * 4, B, nullptr, s));
+  return FASTAV_OK;
+}
+
+// ---- attention rollout (Eq. 2-3) ----------------------------------------------------------------------
+size_t fastav_attention_map_workspace_bytes(int32_t n, int32_t n_q_heads) {
+  if (n < 0 || n_q_heads < 1) return 0;
+  return attention_map_stats_bytes(n, n_q_heads);
+}
+
+fastav_status_t fastav_attention_map(const fastav_model_t* model, const void* q, int64_t q_row_stride, const void* k,
+                                     int64_t k_row_stride, int32_t n, void* a_out, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
+  FASTAV_TRY(check_model(model));
+  if (!q || !k || !a_out || !workspace) return fail(FASTAV_EINVAL, "a pointer argument is NULL");
+  if (model->dtype != FASTAV_BF16) return fail(FASTAV_EUNSUPPORTED, "the attention map is built for bf16 inputs");
+  if (n < 1 || n % 4) return fail(FASTAV_EINVAL, "n must be a positive multiple of 4");
+  if (((uintptr_t)workspace % 256) || workspace_bytes < attention_map_stats_bytes(n, model->n_q_heads))
+    return fail(FASTAV_EWORKSPACE, "workspace must be 256-byte aligned and hold fastav_attention_map_workspace_bytes()");
+  if (q_row_stride < (int64_t)model->n_q_heads * model->head_dim || k_row_stride < (int64_t)model->n_kv_heads * model->head_dim)
+    return fail(FASTAV_EINVAL, "row strides are smaller than a row");
+  return launch_attention_map(q, q_row_stride, k, k_row_stride, n, model->n_q_heads, model->n_kv_heads, model->head_dim,
+                              (float*)workspace, a_out, (hipStream_t)stream);
+}
+
+struct RolloutWs { size_t resid, hn, qkv, attn, hmlp, pos, cu, stats, a16, c, rt16, gemm, gemm_bytes, total; };
+
+static RolloutWs carve_rollout(const fastav_model_t& m, int64_t n) {
+  RolloutWs w;
+  size_t at = 0;
+  auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes, 256); return o; };
+  const size_t qd = (size_t)m.n_q_heads * m.head_dim, kd = (size_t)m.n_kv_heads * m.head_dim;
+  w.resid = take((size_t)n * m.hidden * 4);
+  w.hn = take((size_t)n * m.hidden * 2);
+  w.qkv = take((size_t)n * (qd + 2 * kd) * 2);
+  w.attn = take((size_t)n * qd * 2);
+  w.hmlp = take((size_t)n * m.mlp_dim * 2);
+  w.pos = take((size_t)n * 4);
+  w.cu = take(256);
+  w.stats = take(attention_map_stats_bytes((int)n, m.n_q_heads));
+  w.a16 = take((size_t)n * n * 2);
+  w.c = take((size_t)n * n * 4);
+  w.rt16 = take((size_t)n * n * 2);
+  w.gemm_bytes = mfma_linear_scratch_bytes();
+  w.gemm = take(w.gemm_bytes);
+  w.total = at;
+  return w;
+}
+
+fastav_status_t fastav_rollout_workspace_bytes(fastav_handle_t h, int32_t n, size_t* out) {
+  if (!h || !out) return fail(FASTAV_EINVAL, "handle or out is NULL");
+  if (n < 1 || n % 4) return fail(FASTAV_EINVAL, "n must be a positive multiple of 4");
+  *out = carve_rollout(h->m, n).total;
+  return FASTAV_OK;
+}
+
+fastav_status_t fastav_rollout(fastav_handle_t h, const void* x, int32_t n, float alpha, int32_t upto_layers,
+                               float* rt_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!h || !x || !rt_out) return fail(FASTAV_EINVAL, "handle, x or rt_out is NULL");
+  const fastav_model_t& m = h->m;
+  hipStream_t s = (hipStream_t)stream;
+  if (m.dtype != FASTAV_BF16) return fail(FASTAV_EUNSUPPORTED, "the rollout is built for bf16 models");
+  if (n < 1 || n % 4) return fail(FASTAV_EINVAL, "n must be a positive multiple of 4");
+  if (!(alpha >= 0.f && alpha <= 1.f)) return fail(FASTAV_EINVAL, "alpha must lie in [0, 1]");
+  if (upto_layers < 1 || upto_layers > m.n_layers) return fail(FASTAV_EINVAL, "upto_layers must be in [1, n_layers]");
+  if (!workspace || ((uintptr_t)workspace % 256)) return fail(FASTAV_EINVAL, "workspace must be non-NULL and 256-byte aligned");
+  if (((uintptr_t)x % 16) || ((uintptr_t)rt_out % 16)) return fail(FASTAV_EINVAL, "x and rt_out must be 16-byte aligned");
+  const RolloutWs ws = carve_rollout(m, n);
+  if (workspace_bytes < ws.total) return fail(FASTAV_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, ws.total);
+  for (int l = 0; l < upto_layers; ++l)
+    if (!h->has_w[l]) return fail(FASTAV_EINVAL, "weights of layer %d were never set", l);
+  char* base = (char*)workspace;
+  float* resid = (float*)(base + ws.resid);
+  void* hn = base + ws.hn;
+  char* qkv = base + ws.qkv;
+  void* attn = base + ws.attn;
+  void* hmlp = base + ws.hmlp;
+  int32_t* pos = (int32_t*)(base + ws.pos);
+  int32_t* cu = (int32_t*)(base + ws.cu);
+  const int qd = m.n_q_heads * m.head_dim, kd = m.n_kv_heads * m.head_dim, qkvd = qd + 2 * kd;
+  const int32_t cu_host[2] = {0, n};
+  FASTAV_TRY(upload_small(cu, cu_host, sizeof(cu_host), s));
+  FASTAV_TRY(launch_iota(pos, n, s));
+  FASTAV_TRY(launch_to_f32(x, resid, (int64_t)n * m.hidden, m.dtype, s));
+  FASTAV_TRY(launch_rollout_init(rt_out, base + ws.rt16, n, s));
+  for (int l = 0; l < upto_layers; ++l) {
+    const fastav_layer_weights_t& W = h->w[l];
+    FASTAV_TRY(launch_rmsnorm(resid, W.g_attn, hn, n, m.hidden, m.rms_eps, m.dtype, s));
+    const void* seg[3] = {W.wq, W.wk, W.wv};
+    const int rows[3] = {qd, kd, kd};
+    FASTAV_TRY(linear_segments(hn, seg, rows, 3, nullptr, qkv, qkvd, n, m.hidden, FASTAV_EPI_STORE, m.dtype, nullptr, 0, s));
+    FASTAV_TRY(launch_rope(qkv, qkvd, pos, n, m.n_q_heads + m.n_kv_heads, m.head_dim, m.rope_base, m.dtype, s));
+    FASTAV_TRY(launch_attention_map(qkv, qkvd, qkv + (size_t)qd * 2, qkvd, n, m.n_q_heads, m.n_kv_heads, m.head_dim,
+                                    (float*)(base + ws.stats), base + ws.a16, s));
+    FASTAV_TRY(launch_rollout_step(rt_out, base + ws.rt16, base + ws.a16, (float*)(base + ws.c), n, alpha,
+                                   base + ws.gemm, ws.gemm_bytes, s));
+    if (l + 1 == upto_layers) break;                   // the hidden state past the last requested layer is not needed
+    FASTAV_TRY(launch_attention(qkv, qkvd, qkv + (size_t)qd * 2, qkv + (size_t)(qd + kd) * 2, qkvd, attn, qd, cu, 1, n, n,
+                                m.n_q_heads, m.n_kv_heads, m.head_dim, nullptr, nullptr, m.dtype,
+                                2.0 * m.n_q_heads * m.head_dim * (double)n * ((double)n + 1.0), s));
+    FASTAV_TRY(launch_linear(attn, W.wo, nullptr, resid, n, m.hidden, qd, FASTAV_EPI_RESADD, m.dtype, base + ws.gemm, ws.gemm_bytes, s));
+    FASTAV_TRY(launch_rmsnorm(resid, W.g_mlp, hn, n, m.hidden, m.rms_eps, m.dtype, s));
+    FASTAV_TRY(launch_linear(hn, W.w_gate, W.w_up, hmlp, n, m.mlp_dim, m.hidden, FASTAV_EPI_SWIGLU, m.dtype, nullptr, 0, s));
+    FASTAV_TRY(launch_linear(hmlp, W.w_down, nullptr, resid, n, m.hidden, m.mlp_dim, FASTAV_EPI_RESADD, m.dtype, base + ws.gemm, ws.gemm_bytes, s));
+  }
   return FASTAV_OK;
 }
 
