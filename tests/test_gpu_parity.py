@@ -482,3 +482,43 @@ def test_prefill_full_size_against_stored_oracle(cfg):
         assert st[f"x_rel_l2_{b}"] <= 3e-2 and st[f"x_max_abs_over_rms_{b}"] <= 0.25, st
     del dec
     torch.cuda.empty_cache()
+
+
+def test_prefill_and_decode_replay_from_a_hip_graph():
+    """Nothing in the path allocates, synchronises or copies through the host, so a caller may capture it in a
+    HIP graph.  The graph is replayed several times, with eager work and synchronisations in between, and every
+    replay must reproduce the eager result bit for bit."""
+    w, weights, x = _small_bf16()
+    m = w.model
+    dec = make_decoder(m, weights)
+    spans, offs = fi.span_table(w)
+    xd = dev(x, "bf16")
+    cu = fi.cu_seqlens(w)
+    prunes = prune_tuples(w)
+    out = dec.fastav_prefill(xd, cu, spans, offs, prunes, 1, want_kv=True)       # allocates outputs + workspace
+    lens = fa.fastav_schedule_lens(cu, spans, offs, prunes, 1, m.n_layers)
+    x_new = dev(fi.round_bf16(np.random.default_rng(2).standard_normal((2, m.hidden)).astype(np.float32)), "bf16")
+    pos = torch.from_numpy(np.array(w.seqlens, dtype=np.int32)).cuda()
+    st = dec.fastav_decode_step(x_new, pos, out["kv"], lens)["state"]
+    torch.cuda.synchronize()
+    eager_x, eager_pos = out["x_out"].clone(), out["kept_pos"].clone()
+    eager_k = [k.clone() for k, _ in out["kv"]]
+    eager_dec = st["x_out"].clone()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=torch.cuda.Stream()):
+        dec.fastav_prefill(xd, cu, spans, offs, prunes, 1, outputs=out)
+        dec.fastav_decode_step(x_new, pos, out["kv"], lens, state=st)
+    for rep in range(3):
+        out["x_out"].zero_(); out["kept_pos"].zero_(); st["x_out"].zero_()
+        for k, v in out["kv"]:
+            k.zero_(); v.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out["x_out"], eager_x) and torch.equal(out["kept_pos"], eager_pos), rep
+        assert all(torch.equal(k, ek) for (k, _), ek in zip(out["kv"], eager_k)), rep
+        assert torch.equal(st["x_out"], eager_dec), rep
+        # eager work of the same kind between the replays
+        other = dec.fastav_prefill(xd, cu, spans, offs, [], 1)
+        torch.cuda.synchronize()
+        assert other["x_out"].shape[0] == sum(w.seqlens)
