@@ -47,9 +47,11 @@ fastav_status_t launch_attention_mfma(const void* q, int64_t q_stride, const voi
                                       float* last_ml, hipStream_t s);
 
 bool skinny_linear_supported(int64_t m, int n, int k, int dtype, int64_t ldy);
+bool skinny_norm_supported(int B, int k);
 fastav_status_t launch_skinny_linear(const void* x, const void* const* w_seg, const int* seg_rows, int n_seg,
                                      const void* w2, void* y, int64_t ldy, int B, int n, int k, int epilogue,
-                                     hipStream_t s);
+                                     hipStream_t s, const float* norm_x = nullptr, const void* norm_g = nullptr,
+                                     float norm_eps = 0.f);
 size_t decode_attn_workspace_bytes(int batch, int Hq, int dh, int max_splits);
 fastav_status_t launch_decode_attention(const void* q, const void* k_self, const void* v_self, int64_t q_stride,
                                         const void* k_prefix, const void* v_prefix, const int32_t* cu_prefix,
@@ -679,10 +681,14 @@ fastav_status_t fastav_decode_step(fastav_handle_t h, const fastav_decode_in_t* 
   FASTAV_TRY(launch_to_f32(in->x_new, x, (int64_t)B * m.hidden, m.dtype, s));
   for (int l = 0; l < m.n_layers; ++l) {
     const fastav_layer_weights_t& W = h->w[l];
-    FASTAV_TRY(launch_rmsnorm(x, W.g_attn, hn, B, m.hidden, m.rms_eps, m.dtype, s));
+    // for a few rows RMSNorm is folded into the projection that consumes it (every workgroup normalises the
+    // rows into its LDS): one launch less per norm
+    const bool fuse_norm = skinny_norm_supported(B, m.hidden);
+    if (!fuse_norm) FASTAV_TRY(launch_rmsnorm(x, W.g_attn, hn, B, m.hidden, m.rms_eps, m.dtype, s));
     const void* seg[3] = {W.wq, W.wk, W.wv};
     const int rows[3] = {qd, kd, kd};
-    FASTAV_TRY(launch_skinny_linear(hn, seg, rows, 3, nullptr, qkv, qkvd, B, qkvd, m.hidden, FASTAV_EPI_STORE, s));
+    FASTAV_TRY(launch_skinny_linear(hn, seg, rows, 3, nullptr, qkv, qkvd, B, qkvd, m.hidden, FASTAV_EPI_STORE, s,
+                                    fuse_norm ? x : nullptr, W.g_attn, m.rms_eps));
     // the key heads follow the query heads in the row: one launch rotates both
     FASTAV_TRY(launch_rope(qkv, qkvd, in->pos_new, B, m.n_q_heads + m.n_kv_heads, m.head_dim, m.rope_base, m.dtype, s));
     const void* kg = in->k_gen ? in->k_gen[l] : nullptr;
@@ -703,10 +709,11 @@ fastav_status_t fastav_decode_step(fastav_handle_t h, const fastav_decode_in_t* 
     const void* so[1] = {W.wo};
     const int ro[1] = {m.hidden};
     FASTAV_TRY(launch_skinny_linear(attn, so, ro, 1, nullptr, x, m.hidden, B, m.hidden, qd, FASTAV_EPI_RESADD, s));
-    FASTAV_TRY(launch_rmsnorm(x, W.g_mlp, hn, B, m.hidden, m.rms_eps, m.dtype, s));
+    if (!fuse_norm) FASTAV_TRY(launch_rmsnorm(x, W.g_mlp, hn, B, m.hidden, m.rms_eps, m.dtype, s));
     const void* sg[1] = {W.w_gate};
     const int rg[1] = {m.mlp_dim};
-    FASTAV_TRY(launch_skinny_linear(hn, sg, rg, 1, W.w_up, hmlp, m.mlp_dim, B, m.mlp_dim, m.hidden, FASTAV_EPI_SWIGLU, s));
+    FASTAV_TRY(launch_skinny_linear(hn, sg, rg, 1, W.w_up, hmlp, m.mlp_dim, B, m.mlp_dim, m.hidden, FASTAV_EPI_SWIGLU, s,
+                                    fuse_norm ? x : nullptr, W.g_mlp, m.rms_eps));
     const void* sd[1] = {W.w_down};
     FASTAV_TRY(launch_skinny_linear(hmlp, sd, ro, 1, nullptr, x, m.hidden, B, m.hidden, m.mlp_dim, FASTAV_EPI_RESADD, s));
   }

@@ -25,6 +25,13 @@ namespace fastav {
 
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
+// Workgroup barrier that orders LDS traffic only: global loads already issued stay in flight across it.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // ---------------------------------------------------------------------------------------- skinny linear
 struct SkinnyArgs {
   const bf16_t* x;            // [B, K] bf16
@@ -34,11 +41,18 @@ struct SkinnyArgs {
   void* y;                    // store / SwiGLU: bf16 [B, ldy]; residual: fp32 [B, ldy]
   int64_t ldy;
   int B, N, K;
+  // NORM kernels: the input is the fp32 residual stream, RMS-normalised by every workgroup for itself into
+  // LDS, X = bf16(xres * r * g), which saves the separate one-row norm launches of a decode step
+  const float* xres;          // [B, K] fp32
+  const bf16_t* g;            // [K] gain
+  float eps;
 };
 
-template <int EPI, int NW>
+template <int EPI, int NW, bool NORM>
 __global__ __launch_bounds__(64 * NW) void k_skinny_linear(SkinnyArgs a) {
   __shared__ f32x4v red[2][NW][64];
+  __shared__ float rs[16];                                      // NORM: 1 / rms of every batch row
+  extern __shared__ __attribute__((aligned(16))) bf16_t xs[];   // NORM: [B][K] normalised input
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n0 = blockIdx.x * 16;
@@ -54,20 +68,63 @@ __global__ __launch_bounds__(64 * NW) void k_skinny_linear(SkinnyArgs a) {
   const bf16x8_t* wp = (const bf16x8_t*)(wbase + wrow + kc);
   const bf16x8_t* w2p = (EPI == FASTAV_EPI_SWIGLU) ? (const bf16x8_t*)(a.w2 + wrow + kc) : nullptr;
   const int xb = r16 < a.B ? r16 : a.B - 1;                   // padded batch rows re-read the last real one
-  const bf16x8_t* xp = (const bf16x8_t*)(a.x + (int64_t)xb * a.K + kc);
-
+  const bf16x8_t* xp = NORM ? (const bf16x8_t*)(xs + xb * a.K + kc) : (const bf16x8_t*)(a.x + (int64_t)xb * a.K + kc);
   f32x4v acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f};
   const int steps = a.K / 32;                                  // K % (32 NW) == 0: every wave gets steps / NW
   constexpr int U = (EPI == FASTAV_EPI_SWIGLU) ? 8 : 16;       // 16-byte loads in flight per lane and weight stream
   int s = wave;
-  for (; s + NW * (U - 1) < steps; s += NW * U) {
-    bf16x8_t wf[U], xf[U], w2f[U];
+  bf16x8_t wf[U], w2f[U];
+  // NORM: the first batch of weight loads is issued before the norm prologue and stays in flight across its
+  // barriers (they wait on LDS traffic only), so the prologue costs no bandwidth time
+  bool preloaded = false;
+  if (NORM && s + NW * (U - 1) < steps) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       wf[u] = wp[(s + NW * u) * 4];
       if (EPI == FASTAV_EPI_SWIGLU) w2f[u] = w2p[(s + NW * u) * 4];
-      xf[u] = xp[(s + NW * u) * 4];
     }
+    preloaded = true;
+  }
+  if (NORM) {
+    // wave w reduces the rows w, w + NW, ...; then all threads write the normalised rows, rounded the way
+    // k_rmsnorm rounds them
+    for (int b = wave; b < a.B; b += NW) {
+      const f32x4v* xr = (const f32x4v*)(a.xres + (int64_t)b * a.K);
+      float ss = 0.f;
+      for (int i = lane; i < a.K / 4; i += 64) {
+        const f32x4v v = xr[i];
+        ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+      }
+      ss = wave_sum(ss);
+      if (lane == 0) rs[b] = 1.0f / sqrtf(ss / (float)a.K + a.eps);
+    }
+    lds_barrier();
+    const int per_row = a.K / 4;
+    for (int i = tid; i < a.B * per_row; i += 64 * NW) {
+      const int b = i / per_row, c = i % per_row;
+      const f32x4v v = ((const f32x4v*)(a.xres + (int64_t)b * a.K))[c];
+      const bf16x4_t gv = ((const bf16x4_t*)a.g)[c];
+      const float r = rs[b];
+      bf16x4_t o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = (bf16_t)(v[e] * r * (float)gv[e]);
+      ((bf16x4_t*)(xs + b * a.K))[c] = o;
+    }
+    lds_barrier();
+  }
+
+  for (; s + NW * (U - 1) < steps; s += NW * U) {
+    bf16x8_t xf[U];
+    if (!(NORM && preloaded)) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        wf[u] = wp[(s + NW * u) * 4];
+        if (EPI == FASTAV_EPI_SWIGLU) w2f[u] = w2p[(s + NW * u) * 4];
+      }
+    }
+    preloaded = false;
+#pragma unroll
+    for (int u = 0; u < U; ++u) xf[u] = xp[(s + NW * u) * 4];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], xf[u], acc, 0, 0, 0);
@@ -112,13 +169,21 @@ bool skinny_linear_supported(int64_t m, int n, int k, int dtype, int64_t ldy) {
   return dtype == FASTAV_BF16 && m >= 1 && m <= 16 && n % 16 == 0 && k % 128 == 0 && ldy % 4 == 0;
 }
 
+// norm_x != nullptr: the input is rmsnorm(norm_x [B,k] fp32; gain norm_g, norm_eps) and x is ignored (needs
+// B * k <= 32768 so that the normalised rows fit 64 KB of LDS; not with the residual epilogue)
+bool skinny_norm_supported(int B, int k) { return (int64_t)B * k <= 32768; }
+
 fastav_status_t launch_skinny_linear(const void* x, const void* const* w_seg, const int* seg_rows, int n_seg,
                                      const void* w2, void* y, int64_t ldy, int B, int n, int k, int epilogue,
-                                     hipStream_t s) {
+                                     hipStream_t s, const float* norm_x, const void* norm_g, float norm_eps) {
   if (B == 0 || n == 0) return FASTAV_OK;
   if (!skinny_linear_supported(B, n, k, FASTAV_BF16, ldy)) return fail(FASTAV_EUNSUPPORTED, "skinny linear: unsupported shape");
-  if (((uintptr_t)x | (uintptr_t)y) % 16) return fail(FASTAV_EINVAL, "skinny linear: x and y must be 16-byte aligned");
+  if (((uintptr_t)x | (uintptr_t)y | (uintptr_t)norm_x | (uintptr_t)norm_g) % 16)
+    return fail(FASTAV_EINVAL, "skinny linear: x, y and the norm inputs must be 16-byte aligned");
+  if (norm_x && (!norm_g || epilogue == FASTAV_EPI_RESADD || !skinny_norm_supported(B, k)))
+    return fail(FASTAV_EINVAL, "skinny linear: bad fused-norm arguments");
   SkinnyArgs a;
+  a.xres = norm_x; a.g = (const bf16_t*)norm_g; a.eps = norm_eps;
   a.x = (const bf16_t*)x; a.w2 = (const bf16_t*)w2; a.y = y; a.ldy = ldy; a.B = B; a.N = n; a.K = k;
   int end = 0;
   for (int i = 0; i < 3; ++i) {
@@ -139,17 +204,18 @@ fastav_status_t launch_skinny_linear(const void* x, const void* const* w_seg, co
   // few row blocks (narrow outputs): eight waves split K, which doubles the loads in flight per CU
   const bool wide = (n / 16 < 3 * 256) && (k % 256 == 0);
   const dim3 grid((unsigned)(n / 16));
-  if (epilogue == FASTAV_EPI_SWIGLU) {
-    if (!w2 || ((uintptr_t)w2 % 16)) return fail(FASTAV_EINVAL, "skinny linear: SwiGLU needs a 16-byte aligned up matrix");
-    if (wide) hipLaunchKernelGGL((k_skinny_linear<FASTAV_EPI_SWIGLU, 8>), grid, dim3(512), 0, s, a);
-    else hipLaunchKernelGGL((k_skinny_linear<FASTAV_EPI_SWIGLU, 4>), grid, dim3(256), 0, s, a);
-  } else if (epilogue == FASTAV_EPI_RESADD) {
-    if (wide) hipLaunchKernelGGL((k_skinny_linear<FASTAV_EPI_RESADD, 8>), grid, dim3(512), 0, s, a);
-    else hipLaunchKernelGGL((k_skinny_linear<FASTAV_EPI_RESADD, 4>), grid, dim3(256), 0, s, a);
-  } else {
-    if (wide) hipLaunchKernelGGL((k_skinny_linear<FASTAV_EPI_STORE, 8>), grid, dim3(512), 0, s, a);
-    else hipLaunchKernelGGL((k_skinny_linear<FASTAV_EPI_STORE, 4>), grid, dim3(256), 0, s, a);
-  }
+  if (epilogue == FASTAV_EPI_SWIGLU && (!w2 || ((uintptr_t)w2 % 16)))
+    return fail(FASTAV_EINVAL, "skinny linear: SwiGLU needs a 16-byte aligned up matrix");
+  const size_t shmem = norm_x ? (size_t)B * k * 2 : 0;
+#define FASTAV_SKINNY(EPI, NORM)                                                                          \
+  do {                                                                                                    \
+    if (wide) hipLaunchKernelGGL((k_skinny_linear<EPI, 8, NORM>), grid, dim3(512), shmem, s, a);          \
+    else hipLaunchKernelGGL((k_skinny_linear<EPI, 4, NORM>), grid, dim3(256), shmem, s, a);               \
+  } while (0)
+  if (epilogue == FASTAV_EPI_SWIGLU) { if (norm_x) FASTAV_SKINNY(FASTAV_EPI_SWIGLU, true); else FASTAV_SKINNY(FASTAV_EPI_SWIGLU, false); }
+  else if (epilogue == FASTAV_EPI_RESADD) FASTAV_SKINNY(FASTAV_EPI_RESADD, false);
+  else { if (norm_x) FASTAV_SKINNY(FASTAV_EPI_STORE, true); else FASTAV_SKINNY(FASTAV_EPI_STORE, false); }
+#undef FASTAV_SKINNY
   return check_launch("skinny_linear");
 }
 
