@@ -53,6 +53,8 @@ class Prune:
     layer: int
     kind: int                    # GLOBAL or FINE
     keep_ratio: float
+    selector: int = 0            # which tokens go (Tables 2-3): 0 = the paper's rule for this kind
+    seed: int = 0                # keys the draws of the random selector
 
 
 @dataclass

@@ -42,6 +42,13 @@ implements it):
       audio" and "first 4 frames" when k is chosen accordingly).
   R10 n_last > 1 averages the last n_last causal rows (each sums to 1 over its own
       visible keys).
+  R11 the ablation strategies of Tables 2-3 are named by what they REMOVE:
+      low attentive = lowest Eq. 4 scores (the fine rule), top attentive = highest
+      Eq. 4 scores, low informative = latest positions (the global rule, R9), top
+      informative = earliest positions (the mirror image: the tokens rollout
+      concentrates on), random = lowest values of a counter-based uniform draw per
+      (seed, layer, sample, original position).  Protected tokens stay in all of
+      them, so every strategy keeps the same count ("FLOPs constant").
 
 Pins (tests/test_oracle_pins.py): brute-force loops on tiny inputs, library
 special cases (torch SDPA / rms_norm / silu, numpy stable argsort), closed forms
@@ -49,7 +56,9 @@ special cases (torch SDPA / rms_norm / silu, numpy stable argsort), closed forms
 sum to 1, keep ratio 1.0 is the identity, RoPE relative-position property,
 batched == per-sample; a decode step on unpruned caches equals the last row of a
 prefill one token longer; cache order does not matter; rollout rows sum to 1, alpha = 0
-gives the identity, uniform attention has a closed form), and the paper's printed
+gives the identity, uniform attention has a closed form; the ablation selectors against
+sorted brute force, mirror symmetry and complement identities, the random draw against the
+inverse of its mixing function and uniformity statistics), and the paper's printed
 FLOPs column of Table 4 for the schedule semantics.  Parity unpinned: the absolute hidden-state values for random
 weights (the paper prints no worked numeric example).
 """
@@ -62,6 +71,8 @@ import numpy as np
 
 TEXT, VIDEO, AUDIO = 0, 1, 2
 GLOBAL, FINE = 0, 1
+# Which tokens a prune step removes (Tables 2-3, reading R11).  DEFAULT: GLOBAL -> LOW_INFORMATIVE, FINE -> LOW_ATTENTIVE.
+DEFAULT, LOW_ATTENTIVE, TOP_ATTENTIVE, LOW_INFORMATIVE, TOP_INFORMATIVE, RANDOM = 0, 1, 2, 3, 4, 5
 
 
 # --------------------------------------------------------------------------- schedule
@@ -145,6 +156,65 @@ def global_keep(prot: np.ndarray, k: int) -> np.ndarray:
     keep = np.concatenate([np.nonzero(prot)[0], cand[: k - n_prot]])
     keep.sort()
     return keep.astype(np.int64)
+
+
+def latest_keep(prot: np.ndarray, k: int) -> np.ndarray:
+    """Indices kept when the EARLIEST candidates are removed ("top informative", Table 2; reading R11):
+    every protected token plus the latest candidates by position."""
+    prot = np.asarray(prot, dtype=bool)
+    n = prot.shape[0]
+    n_prot = int(prot.sum())
+    if not (n_prot <= k <= n):
+        raise ValueError("k must satisfy n_protected <= k <= n")
+    cand = np.nonzero(~prot)[0]
+    keep = np.concatenate([np.nonzero(prot)[0], cand[len(cand) - (k - n_prot):]])
+    keep.sort()
+    return keep.astype(np.int64)
+
+
+def mix32(h) -> np.ndarray:
+    """The 32-bit avalanche mix (xor-shift 16, multiply, xor-shift 13, multiply, xor-shift 16) that ends the
+    published MurmurHash3 hash; a bijection on 32-bit words."""
+    h = np.asarray(h, dtype=np.uint64) & np.uint64(0xFFFFFFFF)
+    h ^= h >> np.uint64(16)
+    h = (h * np.uint64(0x85EBCA6B)) & np.uint64(0xFFFFFFFF)
+    h ^= h >> np.uint64(13)
+    h = (h * np.uint64(0xC2B2AE35)) & np.uint64(0xFFFFFFFF)
+    h ^= h >> np.uint64(16)
+    return h
+
+
+def random_scores(seed: int, layer: int, sample: int, pos: np.ndarray) -> np.ndarray:
+    """Uniform fp32 draws in [0, 1) for the "random" strategy of Tables 2-3 (reading R11): a counter-based
+    generator keyed by (seed, layer, sample, original position), so the draw of a token does not depend on
+    what was pruned before.  word = mix32(mix32(mix32(seed + G*(layer+1)) + G*(sample+1)) + pos), G = 0x9E3779B9;
+    the draw is the word's top 24 bits times 2**-24 (exact in fp32)."""
+    G, M = 0x9E3779B9, 0xFFFFFFFF
+    h = mix32((int(seed) + G * (int(layer) + 1)) & M)
+    h = mix32((int(h) + G * (int(sample) + 1)) & M)
+    w = mix32((np.asarray(pos, dtype=np.uint64) + np.uint64(int(h))) & np.uint64(M))
+    return ((w >> np.uint64(8)).astype(np.float64) * 2.0 ** -24).astype(np.float32)
+
+
+def keep_by_selector(selector: int, kind: int, prot: np.ndarray, k: int, scores=None, rand=None) -> np.ndarray:
+    """Kept indices (ascending) of one prune step under an ablation strategy of Tables 2-3 (reading R11).
+
+    ``scores``: Eq. 4 scores (attentive strategies; FINE steps only, a GLOBAL step acts before the layer's
+    attention exists); ``rand``: the uniform draws of the random strategy."""
+    if selector == DEFAULT:
+        selector = LOW_INFORMATIVE if kind == GLOBAL else LOW_ATTENTIVE
+    if selector in (LOW_ATTENTIVE, TOP_ATTENTIVE):
+        if kind != FINE:
+            raise ValueError("attentive strategies need the layer's own attention: FINE steps only")
+        s = np.asarray(scores, dtype=np.float32)
+        return select_keep(s if selector == LOW_ATTENTIVE else -s, prot, k)
+    if selector == LOW_INFORMATIVE:
+        return global_keep(prot, k)
+    if selector == TOP_INFORMATIVE:
+        return latest_keep(prot, k)
+    if selector == RANDOM:
+        return select_keep(np.asarray(rand, dtype=np.float32), prot, k)
+    raise ValueError("unknown selector")
 
 
 # --------------------------------------------------------------------------- layer math
@@ -237,11 +307,13 @@ def layer_finish(x: np.ndarray, attn: np.ndarray, W: Dict[str, np.ndarray], m) -
 
 
 def prefill_sample(m, weights, x: np.ndarray, spans: Sequence[Tuple[int, int]], prunes, n_last: int = 1,
-                   dtype=np.float64, keep_kv: bool = True, trace: bool = False) -> Dict:
+                   dtype=np.float64, keep_kv: bool = True, trace: bool = False, sample_index: int = 0) -> Dict:
     """Pruned prefill of ONE sample (Fig. 3; Section 2.2).
 
     ``weights``: a sequence of per-layer dicts, or a callable ``layer -> dict`` (so big models need not
-    be resident).  ``prunes``: objects with ``layer``, ``kind`` (GLOBAL/FINE), ``keep_ratio``.
+    be resident).  ``prunes``: objects with ``layer``, ``kind`` (GLOBAL/FINE), ``keep_ratio`` and optionally
+    ``selector`` / ``seed`` (the ablation strategies of Tables 2-3, reading R11; ``sample_index`` keys the
+    random strategy's draws).
     Returns x_out [n_final, d], kept_pos [n_final] (original positions), per-layer K/V (post-RoPE, of
     the tokens that survive that layer), and for every prune its scores / kept indices / counts."""
     get_w = weights if callable(weights) else (lambda l: weights[l])
@@ -258,7 +330,9 @@ def prefill_sample(m, weights, x: np.ndarray, spans: Sequence[Tuple[int, int]], 
         for p in here:
             if p.kind == GLOBAL:                                            # reading R7: acts on the layer input
                 k_keep = keep_count(x.shape[0], p.keep_ratio, int(prot.sum()))
-                keep = global_keep(prot, k_keep)
+                sel = getattr(p, "selector", DEFAULT)
+                rand = random_scores(getattr(p, "seed", 0), l, sample_index, pos) if sel == RANDOM else None
+                keep = keep_by_selector(sel, GLOBAL, prot, k_keep, None, rand)
                 out["prunes"].append({"layer": l, "kind": GLOBAL, "n_in": x.shape[0], "k": k_keep,
                                       "keep": keep, "pos_in": pos.copy(), "scores": None})
                 x, pos, prot = x[keep], pos[keep], prot[keep]
@@ -271,7 +345,9 @@ def prefill_sample(m, weights, x: np.ndarray, spans: Sequence[Tuple[int, int]], 
             if p.kind == FINE:
                 s = last_query_scores(q, k, n_last)
                 k_keep = keep_count(n, p.keep_ratio, int(prot.sum()))
-                keep = select_keep(s.astype(np.float32), prot, k_keep)
+                sel = getattr(p, "selector", DEFAULT)
+                rand = random_scores(getattr(p, "seed", 0), l, sample_index, pos) if sel == RANDOM else None
+                keep = keep_by_selector(sel, FINE, prot, k_keep, s.astype(np.float32), rand)
                 out["prunes"].append({"layer": l, "kind": FINE, "n_in": n, "k": k_keep, "keep": keep,
                                       "pos_in": pos.copy(), "scores": s})
         x_new = layer_finish(x, attn, W, m)
@@ -291,10 +367,10 @@ def prefill_sample(m, weights, x: np.ndarray, spans: Sequence[Tuple[int, int]], 
 def prefill(workload, weights, x: np.ndarray, dtype=np.float64, keep_kv: bool = True, trace: bool = False) -> List[Dict]:
     """Batched pruned prefill: samples never interact, so the batch is a loop over samples."""
     outs, row = [], 0
-    for spans in workload.samples:
+    for b, spans in enumerate(workload.samples):
         n = sum(l for _, l in spans)
         outs.append(prefill_sample(workload.model, weights, x[row:row + n], spans, workload.prunes,
-                                   workload.n_last, dtype, keep_kv, trace))
+                                   workload.n_last, dtype, keep_kv, trace, b))
         row += n
     return outs
 

@@ -420,3 +420,126 @@ def test_rollout_matches_explicit_products_and_closed_forms():
     R1 = orc.attention_rollout(m, flat, x, 1.0)
     np.testing.assert_allclose(R1[0], U, rtol=1e-12)
     np.testing.assert_allclose(R1[2], U @ U @ U, rtol=1e-11)
+
+
+# ---------------------------------------------------------------- ablation selectors (Tables 2-3)
+def _unmix32(h: int) -> int:
+    """Inverse of the 32-bit avalanche mix, from the algebra alone: an xor-shift by s >= 11 undoes itself in at
+    most three applications, an odd multiplier has an inverse modulo 2**32."""
+    M = 0xFFFFFFFF
+    h ^= h >> 16
+    h = (h * pow(0xC2B2AE35, -1, 1 << 32)) & M
+    h ^= (h >> 13) ^ (h >> 26)
+    h = (h * pow(0x85EBCA6B, -1, 1 << 32)) & M
+    h ^= h >> 16
+    return h
+
+
+def test_mix32_is_the_bijection_its_inverse_undoes():
+    rng = np.random.default_rng(5)
+    xs = np.concatenate([np.arange(0, 4096, dtype=np.uint64), rng.integers(0, 1 << 32, 4096, dtype=np.uint64),
+                         np.array([0xFFFFFFFF, 0x80000000, 0x7FFFFFFF], dtype=np.uint64)])
+    ys = orc.mix32(xs)
+    assert int(orc.mix32(0)) == 0                                   # every step maps 0 to 0
+    assert ys.max() <= 0xFFFFFFFF and len(set(ys.tolist())) == len(set(xs.tolist()))
+    assert [_unmix32(int(y)) for y in ys] == [int(x) for x in xs]
+    # avalanche: flipping one input bit flips about half of the output bits
+    flips = [bin(int(orc.mix32(int(x) ^ (1 << b))) ^ int(y)).count("1") for x, y in zip(xs[:512], ys[:512]) for b in (0, 13, 31)]
+    assert 14.5 < np.mean(flips) < 17.5
+
+
+def test_random_scores_are_uniform_counter_based_draws():
+    pos = np.arange(20000)
+    u = orc.random_scores(7, 3, 1, pos)
+    assert u.dtype == np.float32 and u.min() >= 0.0 and u.max() < 1.0
+    assert np.array_equal(u * 2.0 ** 24, np.floor(u * 2.0 ** 24))    # 24-bit fractions
+    assert abs(u.mean() - 0.5) < 0.01 and abs(u.var() - 1.0 / 12.0) < 0.004
+    hist = np.bincount((u * 16).astype(int), minlength=16)
+    assert (((hist - 1250.0) ** 2) / 1250.0).sum() < 45.0             # chi-square, 15 dof (p ~ 1e-4)
+    assert abs(np.corrcoef(u[:-1], u[1:])[0, 1]) < 0.03               # neighbouring counters uncorrelated
+    # counter-based: a token's draw depends on its own position only, not on which others are present
+    sub = np.array([5, 17, 400, 19999])
+    assert np.array_equal(orc.random_scores(7, 3, 1, sub), u[sub])
+    # every key component matters
+    for other in (orc.random_scores(8, 3, 1, pos), orc.random_scores(7, 4, 1, pos), orc.random_scores(7, 3, 2, pos)):
+        assert (other == u).mean() < 0.001 and abs(np.corrcoef(other, u)[0, 1]) < 0.03
+
+
+@pytest.mark.parametrize("n", [1, 2, 13, 64, 257])
+def test_selectors_against_sorted_brute_force(n):
+    rng = np.random.default_rng(300 + n)
+    s = fi.random_scores(n, 500 + n, "softmax")
+    prot = rng.random(n) < 0.25
+    n_prot = int(prot.sum())
+    cand = [j for j in range(n) if not prot[j]]
+    r = orc.random_scores(11, 2, 0, np.arange(n))
+    for k in sorted({n_prot, n, (n_prot + n) // 2, min(n, n_prot + 1)}):
+        c = k - n_prot
+        want = {
+            orc.LOW_ATTENTIVE: sorted(cand, key=lambda j: (-float(s[j]), j))[:c],
+            orc.TOP_ATTENTIVE: sorted(cand, key=lambda j: (float(s[j]), j))[:c],
+            orc.LOW_INFORMATIVE: cand[:c],
+            orc.TOP_INFORMATIVE: cand[len(cand) - c:],
+            orc.RANDOM: sorted(cand, key=lambda j: (-float(r[j]), j))[:c],
+        }
+        for sel, chosen in want.items():
+            got = orc.keep_by_selector(sel, orc.FINE if sel in (orc.LOW_ATTENTIVE, orc.TOP_ATTENTIVE) else orc.GLOBAL,
+                                       prot, k, s, r)
+            assert got.tolist() == sorted([j for j in range(n) if prot[j]] + chosen), (sel, k)
+            assert len(got) == k                                        # every strategy keeps the same count
+    # defaults are the paper's own rules
+    k = (n_prot + n) // 2
+    assert np.array_equal(orc.keep_by_selector(orc.DEFAULT, orc.GLOBAL, prot, k), orc.global_keep(prot, k))
+    assert np.array_equal(orc.keep_by_selector(orc.DEFAULT, orc.FINE, prot, k, s), orc.select_keep(s, prot, k))
+
+
+def test_selector_symmetries():
+    rng = np.random.default_rng(9)
+    n = 90
+    prot = rng.random(n) < 0.2
+    n_prot, n_cand = int(prot.sum()), int((~prot).sum())
+    s = rng.permutation(n).astype(np.float32)                          # distinct scores: no ties
+    for c in (0, 1, n_cand // 3, n_cand):
+        lo = orc.keep_by_selector(orc.LOW_ATTENTIVE, orc.FINE, prot, n_prot + c, s)
+        hi = orc.keep_by_selector(orc.TOP_ATTENTIVE, orc.FINE, prot, n_prot + n_cand - c, s)
+        # keeping the c best and keeping the n_cand - c worst split the candidates between them
+        both = np.intersect1d(lo, hi)
+        assert np.array_equal(both, np.nonzero(prot)[0]) and len(np.union1d(lo, hi)) == n
+        # top informative is low informative on the reversed sequence
+        early = orc.keep_by_selector(orc.LOW_INFORMATIVE, orc.GLOBAL, prot, n_prot + c)
+        late_rev = orc.keep_by_selector(orc.TOP_INFORMATIVE, orc.GLOBAL, prot[::-1], n_prot + c)
+        assert np.array_equal(np.sort(n - 1 - late_rev), early)
+    with pytest.raises(ValueError):
+        orc.keep_by_selector(orc.TOP_ATTENTIVE, orc.GLOBAL, prot, n_prot + 1, s)
+
+
+def test_prefill_with_ablation_selectors_keeps_counts_and_rules():
+    m, w, weights, x = _tiny()
+    base = orc.prefill(w, weights, x)[0]
+    n_prot = 7
+    for sel_g, sel_f in [(orc.TOP_INFORMATIVE, orc.TOP_ATTENTIVE), (orc.RANDOM, orc.RANDOM), (orc.LOW_INFORMATIVE, orc.LOW_ATTENTIVE)]:
+        prunes = [fi.Prune(p.layer, p.kind, p.keep_ratio, sel_g if p.kind == fi.GLOBAL else sel_f, 123) for p in w.prunes]
+        wv = fi.Workload("tv", m, w.samples, prunes, seed=w.seed)
+        out = orc.prefill(wv, weights, x)[0]
+        assert out["n_per_layer"] == base["n_per_layer"]               # same FLOPs for every strategy
+        kp = out["kept_pos"]
+        assert set(range(3)) <= set(kp) and set(range(37, 41)) <= set(kp)
+        g = out["prunes"][0]
+        if sel_g == orc.TOP_INFORMATIVE:
+            assert g["keep"].tolist() == list(range(3)) + list(range(37 - 18, 37)) + list(range(37, 41))
+            f = out["prunes"][1]                                       # removed = the highest-scored candidates
+            removed = np.setdiff1d(np.arange(f["n_in"]), f["keep"])
+            kept_cand = [j for j in f["keep"] if 3 <= f["pos_in"][j] < 37]
+            assert f["scores"][removed].min() >= f["scores"][kept_cand].max()
+        elif sel_g == orc.RANDOM:
+            r = orc.random_scores(123, 1, 0, g["pos_in"])
+            removed = np.setdiff1d(np.arange(g["n_in"]), g["keep"])
+            kept_cand = [j for j in g["keep"] if 3 <= j < 37]
+            assert r[removed].max() <= r[kept_cand].min()
+            f = out["prunes"][2]                                       # draws are keyed by ORIGINAL positions
+            r = orc.random_scores(123, 3, 0, f["pos_in"])
+            removed = np.setdiff1d(np.arange(f["n_in"]), f["keep"])
+            kept_cand = [j for j in f["keep"] if 3 <= f["pos_in"][j] < 37]
+            assert r[removed].max() <= r[kept_cand].min()
+        else:
+            assert np.array_equal(out["x_out"], base["x_out"])         # explicit names of the defaults
