@@ -46,6 +46,22 @@ typedef enum {
 typedef enum { FASTAV_TEXT = 0, FASTAV_VIDEO = 1, FASTAV_AUDIO = 2 } fastav_modality_t; /* TEXT is never pruned */
 typedef enum { FASTAV_GLOBAL = 0, FASTAV_FINE = 1 } fastav_prune_kind_t;
 typedef enum { FASTAV_BF16 = 0, FASTAV_F32 = 1 } fastav_dtype_t;
+/* Which tokens a prune step removes: the strategies compared in Tables 2 and 3 (Section 3.2, "Global pruning
+ * strategy", "Fine pruning strategy").  Protected tokens stay under every strategy and the kept count depends on
+ * keep_ratio alone, so all strategies of a schedule cost the same FLOPs.
+ *   DEFAULT          the paper's own rule for the step's kind: GLOBAL -> LOW_INFORMATIVE, FINE -> LOW_ATTENTIVE
+ *   LOW_ATTENTIVE    lowest Eq. 4 scores go (FINE steps only: a GLOBAL step acts before the layer's attention)
+ *   TOP_ATTENTIVE    highest Eq. 4 scores go (FINE steps only); equal scores: the lower index stays
+ *   LOW_INFORMATIVE  latest positions go, the rollout-guided rule (GLOBAL steps only)
+ *   TOP_INFORMATIVE  earliest positions go, its mirror image (GLOBAL steps only)
+ *   RANDOM           candidates with the lowest draw go; the draw of a token is the top 24 bits, as a fraction in
+ *                    [0, 1), of mix(mix(mix(seed + G (layer + 1)) + G (sample + 1)) + position id), G = 0x9E3779B9,
+ *                    mix = the 32-bit finishing mix of MurmurHash3 (h ^= h >> 16; h *= 0x85EBCA6B; h ^= h >> 13;
+ *                    h *= 0xC2B2AE35; h ^= h >> 16); position id = the token's position in the original sample */
+typedef enum {
+  FASTAV_SEL_DEFAULT = 0, FASTAV_SEL_LOW_ATTENTIVE = 1, FASTAV_SEL_TOP_ATTENTIVE = 2, FASTAV_SEL_LOW_INFORMATIVE = 3,
+  FASTAV_SEL_TOP_INFORMATIVE = 4, FASTAV_SEL_RANDOM = 5
+} fastav_selector_t;
 
 #define FASTAV_MAX_N_LAST 8     /* most last-query rows Eq. 4 may be averaged over */
 #define FASTAV_MAX_PRUNES 128
@@ -58,8 +74,10 @@ typedef struct { int32_t start, len, modality; } fastav_span_t;
 
 /* One prune step.  layer is 0-based.  GLOBAL acts on the input of that layer; FINE uses that layer's own
  * attention and shrinks the sequence from its output projection on.  keep_ratio = 1 - P in (0, 1].
- * The array passed to fastav_prefill is sorted by (layer, kind); at most one of each kind per layer. */
-typedef struct { int32_t layer, kind; double keep_ratio; } fastav_prune_t;
+ * The array passed to fastav_prefill is sorted by (layer, kind); at most one of each kind per layer.
+ * selector: a fastav_selector_t (0 = the paper's rule); seed: keys the draws of FASTAV_SEL_RANDOM.  A selector
+ * that does not fit the kind is FASTAV_EINVAL. */
+typedef struct { int32_t layer, kind; double keep_ratio; int32_t selector; uint32_t seed; } fastav_prune_t;
 
 typedef struct {
   int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, mlp_dim;
@@ -96,7 +114,8 @@ typedef struct {
                                   T_l counts the tokens that survive layer l (a FINE layer's K/V are
                                   compacted).  Entries may be NULL. */
   float* const* prune_scores_out;   /* optional host array [n_prunes] of dev pointers (entries may be NULL):
-                                       for a FINE prune, the Eq. 4 scores of the tokens entering it, packed */
+                                       for a FINE prune with an attentive selector, the Eq. 4 scores of the tokens
+                                       entering it, packed (other prunes leave the buffer untouched) */
   int32_t* const* prune_keep_idx_out; /* optional host array [n_prunes] of dev pointers (entries may be NULL):
                                        packed row indices (into the layout entering the prune) that survive */
   float* const* layer_x_out;   /* optional host array [n_layers] of dev pointers (entries may be NULL):

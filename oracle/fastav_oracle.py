@@ -42,7 +42,7 @@ implements it):
       audio" and "first 4 frames" when k is chosen accordingly).
   R10 n_last > 1 averages the last n_last causal rows (each sums to 1 over its own
       visible keys).
-  R11 the ablation strategies of Tables 2-3 are named by what they REMOVE:
+  R17 the ablation strategies of Tables 2-3 are named by what they REMOVE:
       low attentive = lowest Eq. 4 scores (the fine rule), top attentive = highest
       Eq. 4 scores, low informative = latest positions (the global rule, R9), top
       informative = earliest positions (the mirror image: the tokens rollout
@@ -71,7 +71,7 @@ import numpy as np
 
 TEXT, VIDEO, AUDIO = 0, 1, 2
 GLOBAL, FINE = 0, 1
-# Which tokens a prune step removes (Tables 2-3, reading R11).  DEFAULT: GLOBAL -> LOW_INFORMATIVE, FINE -> LOW_ATTENTIVE.
+# Which tokens a prune step removes (Tables 2-3, reading R17).  DEFAULT: GLOBAL -> LOW_INFORMATIVE, FINE -> LOW_ATTENTIVE.
 DEFAULT, LOW_ATTENTIVE, TOP_ATTENTIVE, LOW_INFORMATIVE, TOP_INFORMATIVE, RANDOM = 0, 1, 2, 3, 4, 5
 
 
@@ -159,7 +159,7 @@ def global_keep(prot: np.ndarray, k: int) -> np.ndarray:
 
 
 def latest_keep(prot: np.ndarray, k: int) -> np.ndarray:
-    """Indices kept when the EARLIEST candidates are removed ("top informative", Table 2; reading R11):
+    """Indices kept when the EARLIEST candidates are removed ("top informative", Table 2; reading R17):
     every protected token plus the latest candidates by position."""
     prot = np.asarray(prot, dtype=bool)
     n = prot.shape[0]
@@ -185,7 +185,7 @@ def mix32(h) -> np.ndarray:
 
 
 def random_scores(seed: int, layer: int, sample: int, pos: np.ndarray) -> np.ndarray:
-    """Uniform fp32 draws in [0, 1) for the "random" strategy of Tables 2-3 (reading R11): a counter-based
+    """Uniform fp32 draws in [0, 1) for the "random" strategy of Tables 2-3 (reading R17): a counter-based
     generator keyed by (seed, layer, sample, original position), so the draw of a token does not depend on
     what was pruned before.  word = mix32(mix32(mix32(seed + G*(layer+1)) + G*(sample+1)) + pos), G = 0x9E3779B9;
     the draw is the word's top 24 bits times 2**-24 (exact in fp32)."""
@@ -197,7 +197,7 @@ def random_scores(seed: int, layer: int, sample: int, pos: np.ndarray) -> np.nda
 
 
 def keep_by_selector(selector: int, kind: int, prot: np.ndarray, k: int, scores=None, rand=None) -> np.ndarray:
-    """Kept indices (ascending) of one prune step under an ablation strategy of Tables 2-3 (reading R11).
+    """Kept indices (ascending) of one prune step under an ablation strategy of Tables 2-3 (reading R17).
 
     ``scores``: Eq. 4 scores (attentive strategies; FINE steps only, a GLOBAL step acts before the layer's
     attention exists); ``rand``: the uniform draws of the random strategy."""
@@ -312,7 +312,7 @@ def prefill_sample(m, weights, x: np.ndarray, spans: Sequence[Tuple[int, int]], 
 
     ``weights``: a sequence of per-layer dicts, or a callable ``layer -> dict`` (so big models need not
     be resident).  ``prunes``: objects with ``layer``, ``kind`` (GLOBAL/FINE), ``keep_ratio`` and optionally
-    ``selector`` / ``seed`` (the ablation strategies of Tables 2-3, reading R11; ``sample_index`` keys the
+    ``selector`` / ``seed`` (the ablation strategies of Tables 2-3, reading R17; ``sample_index`` keys the
     random strategy's draws).
     Returns x_out [n_final, d], kept_pos [n_final] (original positions), per-layer K/V (post-RoPE, of
     the tokens that survive that layer), and for every prune its scores / kept indices / counts."""
@@ -333,7 +333,7 @@ def prefill_sample(m, weights, x: np.ndarray, spans: Sequence[Tuple[int, int]], 
                 sel = getattr(p, "selector", DEFAULT)
                 rand = random_scores(getattr(p, "seed", 0), l, sample_index, pos) if sel == RANDOM else None
                 keep = keep_by_selector(sel, GLOBAL, prot, k_keep, None, rand)
-                out["prunes"].append({"layer": l, "kind": GLOBAL, "n_in": x.shape[0], "k": k_keep,
+                out["prunes"].append({"layer": l, "kind": GLOBAL, "n_in": x.shape[0], "k": k_keep, "selector": sel,
                                       "keep": keep, "pos_in": pos.copy(), "scores": None})
                 x, pos, prot = x[keep], pos[keep], prot[keep]
         n = x.shape[0]
@@ -348,7 +348,7 @@ def prefill_sample(m, weights, x: np.ndarray, spans: Sequence[Tuple[int, int]], 
                 sel = getattr(p, "selector", DEFAULT)
                 rand = random_scores(getattr(p, "seed", 0), l, sample_index, pos) if sel == RANDOM else None
                 keep = keep_by_selector(sel, FINE, prot, k_keep, s.astype(np.float32), rand)
-                out["prunes"].append({"layer": l, "kind": FINE, "n_in": n, "k": k_keep, "keep": keep,
+                out["prunes"].append({"layer": l, "kind": FINE, "n_in": n, "k": k_keep, "keep": keep, "selector": sel,
                                       "pos_in": pos.copy(), "scores": s})
         x_new = layer_finish(x, attn, W, m)
         if trace:

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(HERE, "libfastav.so")
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, 1, 2, 3, 4
 TEXT, VIDEO, AUDIO = 0, 1, 2
 GLOBAL, FINE = 0, 1
+SEL_DEFAULT, SEL_LOW_ATTENTIVE, SEL_TOP_ATTENTIVE, SEL_LOW_INFORMATIVE, SEL_TOP_INFORMATIVE, SEL_RANDOM = range(6)
 BF16, F32 = 0, 1
 EPI_STORE, EPI_RESADD, EPI_SWIGLU = 0, 1, 2
 MAX_N_LAST, MAX_PRUNES, MAX_GATHER_TENSORS = 8, 128, 8
@@ -35,7 +36,8 @@ class Span(C.Structure):
 
 
 class Prune(C.Structure):
-    _fields_ = [("layer", C.c_int32), ("kind", C.c_int32), ("keep_ratio", C.c_double)]
+    _fields_ = [("layer", C.c_int32), ("kind", C.c_int32), ("keep_ratio", C.c_double), ("selector", C.c_int32),
+                ("seed", C.c_uint32)]
 
 
 class Model(C.Structure):
@@ -159,7 +161,7 @@ def make_model(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, mlp_dim, rope_
 def _prune_array(prunes: Sequence) -> "C.Array":
     arr = (Prune * max(1, len(prunes)))()
     for i, p in enumerate(prunes):
-        arr[i] = Prune(int(p[0]), int(p[1]), float(p[2]))
+        arr[i] = Prune(int(p[0]), int(p[1]), float(p[2]), int(p[3]) if len(p) > 3 else 0, int(p[4]) if len(p) > 4 else 0)
     return arr
 
 
@@ -243,7 +245,8 @@ class Decoder:
     def fastav_prefill(self, x: torch.Tensor, cu_seqlens, spans, span_offsets, prunes: Sequence, n_last: int = 1,
                        want_kv: bool = False, want_trace: bool = False, want_layers: bool = False,
                        outputs: Optional[Dict] = None) -> Dict:
-        """Runs fastav_prefill on the current stream.  ``prunes``: sequence of (layer, kind, keep_ratio).
+        """Runs fastav_prefill on the current stream.  ``prunes``: sequence of (layer, kind, keep_ratio[, selector
+        [, seed]]).
         Output tensors are allocated here (or reused from ``outputs``, the dict a previous call returned)."""
         m = self.model
         hb = _HostBatch(x.data_ptr(), cu_seqlens, spans, span_offsets)

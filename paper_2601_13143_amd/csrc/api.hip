@@ -172,6 +172,11 @@ static fastav_status_t check_prunes(const fastav_prune_t* prunes, int n_prunes, 
     const fastav_prune_t& p = prunes[i];
     if (p.layer < 0 || p.layer >= n_layers) return fail(FASTAV_EINVAL, "prune %d: layer %d out of range", i, p.layer);
     if (p.kind != FASTAV_GLOBAL && p.kind != FASTAV_FINE) return fail(FASTAV_EINVAL, "prune %d: bad kind", i);
+    if (p.selector < FASTAV_SEL_DEFAULT || p.selector > FASTAV_SEL_RANDOM) return fail(FASTAV_EINVAL, "prune %d: bad selector", i);
+    if (p.kind == FASTAV_GLOBAL && (p.selector == FASTAV_SEL_LOW_ATTENTIVE || p.selector == FASTAV_SEL_TOP_ATTENTIVE))
+      return fail(FASTAV_EINVAL, "prune %d: attentive selectors need the layer's own attention (FINE steps only)", i);
+    if (p.kind == FASTAV_FINE && (p.selector == FASTAV_SEL_LOW_INFORMATIVE || p.selector == FASTAV_SEL_TOP_INFORMATIVE))
+      return fail(FASTAV_EINVAL, "prune %d: positional selectors belong to GLOBAL steps", i);
     if (!(p.keep_ratio > 0.0 && p.keep_ratio <= 1.0)) return fail(FASTAV_EINVAL, "prune %d: keep_ratio must be in (0,1]", i);
     if (i > 0) {
       const fastav_prune_t& q = prunes[i - 1];
@@ -426,8 +431,12 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
       const int32_t* cu_in = cu_dev + (size_t)stage * (B + 1);
       const int32_t* cu_nx = cu_dev + (size_t)(stage + 1) * (B + 1);
       int32_t* kidx = (out->prune_keep_idx_out && out->prune_keep_idx_out[pi]) ? out->prune_keep_idx_out[pi] : keep_idx_ws;
+      const fastav_prune_t& pr = prunes[pi];
+      const SelectRule rule = pr.selector == FASTAV_SEL_RANDOM ? SelectRule{kSelRandom, select_random_key(pr.seed, l), pos[cur]}
+                            : pr.selector == FASTAV_SEL_TOP_INFORMATIVE ? SelectRule{kSelLatest, 0, nullptr}
+                                                                        : SelectRule{kSelEarliest, 0, nullptr};
       FASTAV_TRY(launch_select(nullptr, prot[cur], cu_in, cu_nx, B, maxlen_stage[stage], kidx,
-                               1.0 * T_stage[stage] + 4.0 * T_stage[stage + 1], s));
+                               (rule.order == kSelRandom ? 5.0 : 1.0) * T_stage[stage] + 4.0 * T_stage[stage + 1], s, rule));
       GatherTensor g[3] = {{resid[cur], resid[cur ^ 1], (int64_t)m.hidden * 4, 0},
                            {pos[cur], pos[cur ^ 1], 4, 0},
                            {prot[cur], prot[cur ^ 1], 1, 0}};
@@ -437,7 +446,8 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
     const int64_t Tl = T_stage[stage];
     const int32_t* cu_l = cu_dev + (size_t)stage * (B + 1);
     const bool fine = pi < n_prunes && prunes[pi].layer == l && prunes[pi].kind == FASTAV_FINE;
-    const bool side = fine && n_last == 1;
+    const bool fine_scored = fine && prunes[pi].selector != FASTAV_SEL_RANDOM;   // Eq. 4 is needed
+    const bool side = fine_scored && n_last == 1;
 
     FASTAV_TRY(launch_rmsnorm(resid[cur], W.g_attn, hn, Tl, m.hidden, m.rms_eps, m.dtype, s));
     {
@@ -457,7 +467,13 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
     if (fine) {
       // ---- FINE prune: Eq. 4 scores of the last query row(s), top-k, compaction of everything later work reads
       float* sc = (out->prune_scores_out && out->prune_scores_out[pi]) ? out->prune_scores_out[pi] : scores_ws;
-      if (side) {
+      const fastav_prune_t& pr = prunes[pi];
+      const SelectRule rule = pr.selector == FASTAV_SEL_RANDOM ? SelectRule{kSelRandom, select_random_key(pr.seed, l), pos[cur]}
+                            : pr.selector == FASTAV_SEL_TOP_ATTENTIVE ? SelectRule{kSelLowScore, 0, nullptr}
+                                                                      : SelectRule{kSelHighScore, 0, nullptr};
+      if (!fine_scored) {
+        // random strategy: no scores
+      } else if (side) {
         FASTAV_TRY(launch_score_finalize(logits, ml, nullptr, cu_l, B, Tl, maxlen_stage[stage], m.n_q_heads, 1, sc, s));
       } else {
         FASTAV_TRY(launch_score_logits(qkv, qkv_stride, kptr, qkv_stride, cu_l, B, Tl, maxlen_stage[stage], m.n_q_heads,
@@ -467,7 +483,7 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
       const int32_t* cu_nx = cu_dev + (size_t)(stage + 1) * (B + 1);
       int32_t* kidx = (out->prune_keep_idx_out && out->prune_keep_idx_out[pi]) ? out->prune_keep_idx_out[pi] : keep_idx_ws;
       FASTAV_TRY(launch_select(sc, prot[cur], cu_l, cu_nx, B, maxlen_stage[stage], kidx,
-                               5.0 * Tl + 4.0 * T_stage[stage + 1], s));
+                               5.0 * Tl + 4.0 * T_stage[stage + 1], s, rule));
       GatherTensor g[6] = {{resid[cur], resid[cur ^ 1], (int64_t)m.hidden * 4, 0},
                            {attn[0], attn[1], (int64_t)qd * (int64_t)es, 0},
                            {pos[cur], pos[cur ^ 1], 4, 0},
@@ -568,7 +584,8 @@ fastav_status_t fastav_select_gather(const float* scores, const uint8_t* protect
   FASTAV_TRY(upload_small(cu_dev, cu_seqlens, (size_t)(batch + 1) * 4, s));
   FASTAV_TRY(upload_small(cu_seqlens_out, cu_out.data(), (size_t)(batch + 1) * 4, s));
   FASTAV_TRY(launch_select(scores, protected_mask, cu_dev, cu_seqlens_out, batch, max_len, keep_idx_out,
-                           (scores ? 5.0 : 1.0) * cu_seqlens[batch] + 4.0 * cu_out[batch], s));
+                           (scores ? 5.0 : 1.0) * cu_seqlens[batch] + 4.0 * cu_out[batch], s,
+                           SelectRule{scores ? kSelHighScore : kSelEarliest, 0, nullptr}));
   return launch_gather(g, n_tensors, keep_idx_out, cu_out[batch], s);
 }
 

@@ -91,9 +91,26 @@ fastav_status_t launch_score_finalize(const float* logits, const float* ml, cons
                                       int batch, int64_t T, int max_seqlen, int Hq, int n_last, float* scores,
                                       hipStream_t s);
 
-// Selection + compaction.  keep_idx/cu_out as in fastav_select_gather; scores == nullptr -> positional.
+// How the select kernel ranks the candidates of a sample (larger rank = kept first; equal ranks -> lower index).
+// The strategies compared in Tables 2-3 of the paper are these five orders.
+enum SelectOrder {
+  kSelHighScore = 0,   // by score, highest first (removes the low-attentive tokens: the fine rule)
+  kSelLowScore = 1,    // by negated score (removes the top-attentive tokens)
+  kSelEarliest = 2,    // by position, earliest first (removes the latest tokens: the global rule)
+  kSelLatest = 3,      // by position, latest first
+  kSelRandom = 4       // by a counter-based uniform draw per (key, sample, position id)
+};
+struct SelectRule {
+  int order;
+  uint32_t key;        // kSelRandom: mix32(seed + G * (layer + 1)), prepared on the host
+  const int32_t* pos;  // kSelRandom: position id of every packed row (nullptr -> index inside the sample)
+};
+uint32_t select_random_key(uint32_t seed, int layer);
+
+// Selection + compaction.  keep_idx/cu_out as in fastav_select_gather; scores are read by the two score orders only.
 fastav_status_t launch_select(const float* scores, const uint8_t* prot, const int32_t* cu, const int32_t* cu_out,
-                              int batch, int max_seqlen, int32_t* keep_idx, double bytes_hint, hipStream_t s);
+                              int batch, int max_seqlen, int32_t* keep_idx, double bytes_hint, hipStream_t s,
+                              SelectRule rule);
 // src_stride_bytes == 0 means rows are packed (stride = row_bytes); row_bytes == 0 skips the tensor.
 struct GatherTensor { const void* src; void* dst; int64_t row_bytes; int64_t src_stride_bytes; };
 fastav_status_t launch_gather(const GatherTensor* t, int n_tensors, const int32_t* keep_idx, int64_t n_rows,

@@ -1,5 +1,6 @@
 // Top-k selection and compaction for the prune step ("tokens with the lowest P% scores are removed",
-// Section 2.2 of the paper; global pruning keeps the earliest positions instead).
+// Section 2.2 of the paper; global pruning keeps the earliest positions instead; the other strategies of
+// Tables 2-3 - top attentive, top informative, random - are further orders of the same kernel).
 //
 //   k_select  one 1024-thread workgroup per sample.  The sample's order-preserving 32-bit keys live in LDS;
 //             four 8-bit MSB-first radix passes (per-wave LDS histograms, so that the narrow exponent range
@@ -46,9 +47,33 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* wave_tot, int& t
   return base + inc - v;
 }
 
-// Key of candidate j (unprotected row): by score, or by position (earlier = larger) when scores == nullptr.
-__device__ __forceinline__ uint32_t cand_key(const float* scores, int row0, int n, int j) {
-  return scores ? score_key(scores[row0 + j]) : (uint32_t)(n - j);   // n - j >= 1
+// 32-bit avalanche mix (xor-shift 16, multiply, xor-shift 13, multiply, xor-shift 16): the finishing step of the
+// published MurmurHash3 hash, a bijection on 32-bit words.
+__host__ __device__ __forceinline__ uint32_t mix32(uint32_t h) {
+  h ^= h >> 16; h *= 0x85EBCA6Bu;
+  h ^= h >> 13; h *= 0xC2B2AE35u;
+  h ^= h >> 16;
+  return h;
+}
+constexpr uint32_t kGolden = 0x9E3779B9u;
+
+uint32_t select_random_key(uint32_t seed, int layer) { return mix32(seed + kGolden * (uint32_t)(layer + 1)); }
+
+// Key of candidate j (unprotected row) of sample b under the rule's order; never 0.
+// Random order: the draw is the top 24 bits of mix32(mix32(key + G (b + 1)) + position id) as a fraction in
+// [0, 1), ranked like a score, so that a token's draw does not depend on what was pruned before it.
+__device__ __forceinline__ uint32_t cand_key(const SelectRule& r, const float* scores, uint32_t sample_key, int row0,
+                                             int n, int j) {
+  switch (r.order) {
+    case kSelHighScore: return score_key(scores[row0 + j]);
+    case kSelLowScore: return score_key(-scores[row0 + j]);
+    case kSelEarliest: return (uint32_t)(n - j);                        // n - j >= 1
+    case kSelLatest: return (uint32_t)(j + 1);
+    default: {
+      const uint32_t p = r.pos ? (uint32_t)r.pos[row0 + j] : (uint32_t)j;
+      return score_key((float)(mix32(sample_key + p) >> 8) * 0x1p-24f);
+    }
+  }
 }
 
 template <bool KEYS_IN_LDS>
@@ -56,7 +81,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
                                                         const uint8_t* __restrict__ prot,
                                                         const int32_t* __restrict__ cu,
                                                         const int32_t* __restrict__ cu_out,
-                                                        int32_t* __restrict__ keep_idx) {
+                                                        int32_t* __restrict__ keep_idx, SelectRule rule) {
   extern __shared__ uint32_t keys[];                      // [n] when KEYS_IN_LDS; key 0 = protected (never a candidate)
   __shared__ int hist[kSelWaves][256];
   __shared__ int wave_tot[kSelWaves];
@@ -68,13 +93,14 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
   const int out0 = cu_out[b], k_keep = cu_out[b + 1] - out0;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (n <= 0) return;
+  const uint32_t sample_key = mix32(rule.key + kGolden * (uint32_t)(b + 1));
 
   // ---- load keys, count protected rows
   int my_prot = 0;
   for (int j = tid; j < n; j += kSelThreads) {
     const bool p = prot[row0 + j] != 0;
     my_prot += p ? 1 : 0;
-    if (KEYS_IN_LDS) keys[j] = p ? 0u : cand_key(scores, row0, n, j);
+    if (KEYS_IN_LDS) keys[j] = p ? 0u : cand_key(rule, scores, sample_key, row0, n, j);
   }
   int n_prot;
   block_exclusive_scan(my_prot, wave_tot, n_prot);
@@ -94,7 +120,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
       for (int j = tid; j < n; j += kSelThreads) {
         uint32_t key;
         if (KEYS_IN_LDS) key = keys[j];
-        else key = prot[row0 + j] ? 0u : cand_key(scores, row0, n, j);
+        else key = prot[row0 + j] ? 0u : cand_key(rule, scores, sample_key, row0, n, j);
         if (key != 0u && (key & mask) == prefix) atomicAdd(&hist[wave][(key >> shift) & 255u], 1);
       }
       __syncthreads();
@@ -148,7 +174,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
   for (int j = j_lo; j < j_hi; ++j) {
     uint32_t key;
     if (KEYS_IN_LDS) key = keys[j];
-    else key = prot[row0 + j] ? 0u : cand_key(scores, row0, n, j);
+    else key = prot[row0 + j] ? 0u : cand_key(rule, scores, sample_key, row0, n, j);
     eq_cnt += (key != 0u && key == prefix) ? 1 : 0;
   }
   int dummy;
@@ -159,7 +185,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
     for (int j = j_lo; j < j_hi; ++j) {
       uint32_t key;
       if (KEYS_IN_LDS) key = keys[j];
-      else key = prot[row0 + j] ? 0u : cand_key(scores, row0, n, j);
+      else key = prot[row0 + j] ? 0u : cand_key(rule, scores, sample_key, row0, n, j);
       bool kp;
       if (key == 0u) kp = true;                            // protected
       else if (take_all) kp = true;
@@ -176,7 +202,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
     for (int j = j_lo; j < j_hi; ++j) {
       uint32_t key;
       if (KEYS_IN_LDS) key = keys[j];
-      else key = prot[row0 + j] ? 0u : cand_key(scores, row0, n, j);
+      else key = prot[row0 + j] ? 0u : cand_key(rule, scores, sample_key, row0, n, j);
       bool kp;
       if (key == 0u) kp = true;
       else if (take_all) kp = true;
@@ -193,8 +219,10 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
 }
 
 fastav_status_t launch_select(const float* scores, const uint8_t* prot, const int32_t* cu, const int32_t* cu_out,
-                              int batch, int max_seqlen, int32_t* keep_idx, double bytes_hint, hipStream_t s) {
+                              int batch, int max_seqlen, int32_t* keep_idx, double bytes_hint, hipStream_t s,
+                              SelectRule rule) {
   if (batch == 0 || max_seqlen == 0) return FASTAV_OK;
+  if ((rule.order == kSelHighScore || rule.order == kSelLowScore) && !scores) return fail(FASTAV_EINVAL, "select: this order needs scores");
   ProfScope prof(FASTAV_PROF_SELECT, bytes_hint, s);
   if (max_seqlen <= kSelLdsKeys) {
     const size_t shmem = (size_t)max_seqlen * sizeof(uint32_t);
@@ -203,9 +231,9 @@ fastav_status_t launch_select(const float* scores, const uint8_t* prot, const in
                                          kSelLdsKeys * (int)sizeof(uint32_t));
       if (e != hipSuccess) return fail(FASTAV_EHIP, "select: hipFuncSetAttribute: %s", hipGetErrorString(e));
     }
-    hipLaunchKernelGGL(k_select<true>, dim3((unsigned)batch), dim3(kSelThreads), shmem, s, scores, prot, cu, cu_out, keep_idx);
+    hipLaunchKernelGGL(k_select<true>, dim3((unsigned)batch), dim3(kSelThreads), shmem, s, scores, prot, cu, cu_out, keep_idx, rule);
   } else {
-    hipLaunchKernelGGL(k_select<false>, dim3((unsigned)batch), dim3(kSelThreads), 0, s, scores, prot, cu, cu_out, keep_idx);
+    hipLaunchKernelGGL(k_select<false>, dim3((unsigned)batch), dim3(kSelThreads), 0, s, scores, prot, cu, cu_out, keep_idx, rule);
   }
   return check_launch("select");
 }

@@ -65,7 +65,7 @@ def make_decoder(m: fi.Model, weights):
 
 
 def prune_tuples(w: fi.Workload):
-    return [(p.layer, p.kind, p.keep_ratio) for p in w.prunes]
+    return [(p.layer, p.kind, p.keep_ratio, p.selector, p.seed) for p in w.prunes]
 
 
 def make_decoder_streamed(m: fi.Model, seed: int, threads: int = 8):

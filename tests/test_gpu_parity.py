@@ -277,10 +277,13 @@ def _check_prefill(w: fi.Workload, out, ref, x_scale_from_ref=True):
             assert set(np.nonzero(prot0)[0].tolist()) <= got_set, "a protected token was pruned"
             diff = (got_set ^ want_pos) - inherited
             if diff:
-                assert pr["kind"] == fi.FINE, "a global prune is positional and must match exactly"
+                sel = pr.get("selector", orc.DEFAULT)
+                assert pr["kind"] == fi.FINE and sel in (orc.DEFAULT, orc.LOW_ATTENTIVE, orc.TOP_ATTENTIVE), \
+                    "positional and random selections are integer work and must match exactly"
                 s_ref = pr["scores"]
                 cand_kept = [j for j in pr["keep"] if not prot0[pr["pos_in"][j]]]
-                kth = min(s_ref[j] for j in cand_kept) if cand_kept else 0.0
+                edge = max if sel == orc.TOP_ATTENTIVE else min       # the kept candidate next to the cut
+                kth = edge(s_ref[j] for j in cand_kept) if cand_kept else 0.0
                 pos_to_local = {int(p): j for j, p in enumerate(pr["pos_in"])}
                 for p in diff:
                     # a token the oracle no longer holds can only be the partner of an earlier flip
@@ -291,7 +294,8 @@ def _check_prefill(w: fi.Workload, out, ref, x_scale_from_ref=True):
             stats["flips_per_prune"].append((b, i, len(diff) // 2))
             stats["flipped"] += (len(diff) + 1) // 2
             inherited |= (got_set ^ want_pos)
-            if pr["kind"] == fi.FINE and out["prune_scores"][i] is not None and not inherited:
+            if pr["kind"] == fi.FINE and out["prune_scores"][i] is not None and not inherited \
+                    and pr.get("selector", orc.DEFAULT) != orc.RANDOM:
                 g = host(out["prune_scores"][i])[cu_in[b]:cu_in[b + 1]]
                 n = len(g)
                 lim = 2e-2 if dtype == "bf16" else 1e-4

@@ -58,6 +58,11 @@ def test_schedule_matches_oracle(cfg):
         finals.append(cur)
     assert tin.tolist() == want_in.tolist()
     assert fl.tolist() == finals
+    # the ablation selectors of Tables 2-3 change which tokens go, never how many
+    for sel_g, sel_f in [(fa.SEL_TOP_INFORMATIVE, fa.SEL_TOP_ATTENTIVE), (fa.SEL_RANDOM, fa.SEL_RANDOM)]:
+        alt = [(p.layer, p.kind, p.keep_ratio, sel_g if p.kind == fi.GLOBAL else sel_f, 99) for p in w.prunes]
+        tin2, tout2, fl2 = fa.fastav_schedule(fi.cu_seqlens(w), spans, offs, alt, w.n_last, w.model.n_layers)
+        assert tin2.tolist() == tin.tolist() and tout2.tolist() == tout.tolist() and fl2.tolist() == fl.tolist()
     assert tout[-1] == sum(finals) and (tout <= tin).all() and (tout[:-1] >= tin[1:]).all()
     if cfg == 3:
         assert tin[0] == 4096 and tin[14] == 2458 and tin[21] == 1721 and tin[27] == 1205 and tout[20] == 1721
@@ -94,6 +99,11 @@ def test_batch_and_prune_validation():
     _expect(B.EINVAL, sched, [0, 8], ok_spans, ok_off, [(1, fi.FINE, 0.5), (0, fi.FINE, 0.5)], 1, 2)   # unsorted
     _expect(B.EINVAL, sched, [0, 8], ok_spans, ok_off, [(1, fi.FINE, 0.5), (1, fi.FINE, 0.5)], 1, 2)   # duplicate
     _expect(B.EINVAL, sched, [0, 8], ok_spans, ok_off, [(1, fi.FINE, 0.5), (1, fi.GLOBAL, 0.5)], 1, 2)  # global after fine
+    _expect(B.EINVAL, sched, [0, 8], ok_spans, ok_off, [(1, fi.FINE, 0.5, 6)], 1, 2)      # selector out of range
+    _expect(B.EINVAL, sched, [0, 8], ok_spans, ok_off, [(1, fi.FINE, 0.5, -1)], 1, 2)
+    _expect(B.EINVAL, sched, [0, 8], ok_spans, ok_off, [(1, fi.GLOBAL, 0.5, fa.SEL_TOP_ATTENTIVE)], 1, 2)    # no attention yet
+    _expect(B.EINVAL, sched, [0, 8], ok_spans, ok_off, [(1, fi.GLOBAL, 0.5, fa.SEL_LOW_ATTENTIVE)], 1, 2)
+    _expect(B.EINVAL, sched, [0, 8], ok_spans, ok_off, [(1, fi.FINE, 0.5, fa.SEL_TOP_INFORMATIVE)], 1, 2)    # positional on FINE
     _expect(B.EINVAL, sched, [0, 8], ok_spans, ok_off, [], 0, 2)                          # n_last < 1
     _expect(B.EINVAL, sched, [0, 8], ok_spans, ok_off, [], B.MAX_N_LAST + 1, 2)
     tin, tout, fl = sched([0, 8], ok_spans, ok_off, [(1, fi.GLOBAL, 0.5), (1, fi.FINE, 0.75)], 1, 2)
