@@ -42,6 +42,9 @@ implements it):
       audio" and "first 4 frames" when k is chosen accordingly).
   R10 n_last > 1 averages the last n_last causal rows (each sums to 1 over its own
       visible keys).
+  R18 the rollout threshold of the global-pruning analysis: a token's influence is
+      its column mean in R^l (all rows), measured in uniform shares 1/n; a sample's
+      cut-off is one past the last video/audio position that reaches the threshold.
   R17 the ablation strategies of Tables 2-3 are named by what they REMOVE:
       low attentive = lowest Eq. 4 scores (the fine rule), top attentive = highest
       Eq. 4 scores, low informative = latest positions (the global rule, R9), top
@@ -56,7 +59,8 @@ special cases (torch SDPA / rms_norm / silu, numpy stable argsort), closed forms
 sum to 1, keep ratio 1.0 is the identity, RoPE relative-position property,
 batched == per-sample; a decode step on unpruned caches equals the last row of a
 prefill one token longer; cache order does not matter; rollout rows sum to 1, alpha = 0
-gives the identity, uniform attention has a closed form; the ablation selectors against
+gives the identity, uniform attention has a closed form; influences of uniform causal
+attention are differences of harmonic numbers; the ablation selectors against
 sorted brute force, mirror symmetry and complement identities, the random draw against the
 inverse of its mixing function and uniformity statistics), and the paper's printed
 FLOPs column of Table 4 for the schedule semantics.  Parity unpinned: the absolute hidden-state values for random
@@ -453,6 +457,27 @@ def attention_rollout(m, weights, x: np.ndarray, alpha: float, dtype=np.float64)
         out.append(R)
         x = layer_finish(x, causal_gqa_attention(q, k, v), W, m)
     return out
+
+
+def rollout_influence(R: np.ndarray) -> np.ndarray:
+    """Influence of every input token under a rollout matrix (Section 2.2: entry [i, j] of R^l is how much input
+    token j influences token i): the mean of column j over all n rows (reading R18).  Rows of R sum to 1, so the
+    influences sum to 1 and a token with the uniform share has influence 1/n."""
+    R = np.asarray(R, dtype=np.float64)
+    return R.sum(axis=0) / R.shape[0]
+
+
+def rollout_cutoff(R: np.ndarray, prot: np.ndarray, threshold: float) -> int:
+    """Cut-off position of one sample (Section 2.2, Global pruning: a rollout threshold at the middle layer
+    removes the less influential video/audio tokens, "typically those beyond position ..."; reading R18):
+    one past the last candidate (unprotected) position whose influence is at least ``threshold`` uniform
+    shares, i.e. influence * n >= threshold; 0 when no candidate reaches it.  Positional global pruning with
+    this cut-off keeps every candidate before it."""
+    prot = np.asarray(prot, dtype=bool)
+    infl = rollout_influence(R)
+    n = infl.shape[0]
+    hit = np.nonzero((~prot) & (infl * n >= threshold))[0]
+    return int(hit[-1]) + 1 if hit.size else 0
 
 
 # --------------------------------------------------------------------------- FLOPs accounting

@@ -543,3 +543,36 @@ def test_prefill_with_ablation_selectors_keeps_counts_and_rules():
             assert r[removed].max() <= r[kept_cand].min()
         else:
             assert np.array_equal(out["x_out"], base["x_out"])         # explicit names of the defaults
+
+
+# ---------------------------------------------------------------- rollout threshold -> cut-off position
+def test_rollout_influence_and_cutoff_closed_forms():
+    n = 40
+    # one layer of uniform causal attention, alpha = 1: R[i, j] = 1/(i+1) for j <= i, so the influence of token j
+    # is (H_n - H_j)/n with H the harmonic numbers: earlier tokens are seen by more rows
+    A = np.tril(np.ones((n, n))) / np.arange(1, n + 1)[:, None]
+    R = orc.rollout_step(np.eye(n), A, 1.0)
+    H = np.concatenate([[0.0], np.cumsum(1.0 / np.arange(1, n + 1))])
+    infl = orc.rollout_influence(R)
+    np.testing.assert_allclose(infl, (H[n] - H[:n]) / n, rtol=1e-13)
+    assert abs(infl.sum() - 1.0) < 1e-13 and (np.diff(infl) < 0).all()
+    # brute-force column means
+    want = [sum(R[i][j] for i in range(n)) / n for j in range(n)]
+    np.testing.assert_allclose(infl, want, rtol=1e-13)
+    prot = np.zeros(n, dtype=bool); prot[:3] = True; prot[-5:] = True
+    for thr in (0.25, 0.5, 1.0, 2.0, 4.0):
+        # influences decrease with j: the cut-off is the number of leading positions with H_n - H_j >= thr,
+        # clipped to the candidates [3, n-5)
+        lead = sum(1 for j in range(n) if H[n] - H[j] >= thr)
+        want_c = min(lead, n - 5) if lead > 3 else 0
+        assert orc.rollout_cutoff(R, prot, thr) == want_c, thr
+    # alpha = 0: R = I, every token has exactly the uniform share
+    I = orc.rollout_step(np.eye(n), A, 0.0)
+    np.testing.assert_allclose(orc.rollout_influence(I), 1.0 / n, rtol=1e-15)
+    assert orc.rollout_cutoff(I, prot, 1.0) == n - 5 and orc.rollout_cutoff(I, prot, 1.0 + 1e-9) == 0
+    # a late influential candidate moves the cut-off past it; a protected one does not
+    R2 = R.copy(); R2[:, 30] += 1.0
+    assert orc.rollout_cutoff(R2, prot, 4.0) == 31
+    R3 = R.copy(); R3[:, n - 2] += 1.0
+    assert orc.rollout_cutoff(R3, prot, 4.0) == orc.rollout_cutoff(R, prot, 4.0)
+    assert orc.rollout_cutoff(R, np.ones(n, dtype=bool), 0.0) == 0        # no candidates at all
