@@ -292,6 +292,18 @@ fastav_status_t fastav_attention_map(const fastav_model_t* model, const void* q,
 fastav_status_t fastav_rollout_workspace_bytes(fastav_handle_t h, int32_t n, size_t* out);
 fastav_status_t fastav_rollout(fastav_handle_t h, const void* x, int32_t n, float alpha, int32_t upto_layers,
                                float* rt_out, void* workspace, size_t workspace_bytes, void* stream);
+/* fastav_rollout_cutoff: the threshold step of the analysis (Section 2.2, "Global pruning": a rollout threshold
+ * at the middle layer marks the less influential video/audio tokens, those beyond some position).
+ * rt: device fp32 [n, n], the transposed rollout as fastav_rollout writes it (16-byte aligned, n a multiple of 4).
+ * protected_mask: device uint8 [n], nonzero = never a candidate (text tokens, the last query positions).
+ * influence_out: device fp32 [n] receives the influence of every input token = the mean over all n rows i of
+ * R[i][j]; the influences sum to 1, so 1/n is the uniform share.  cutoff_out: device int32 [1] receives one past
+ * the last candidate position j with influence_out[j] * n >= threshold (compared in fp32), 0 if there is none:
+ * positional global pruning with that many leading positions keeps every candidate the threshold passes.
+ * The statistic over a set of samples (the paper looks at 100) is the caller's mean or median of the cut-offs.
+ * Errors: FASTAV_EINVAL (NULL pointer, n not a positive multiple of 4, negative or NaN threshold). */
+fastav_status_t fastav_rollout_cutoff(const float* rt, int32_t n, const uint8_t* protected_mask, float threshold,
+                                      float* influence_out, int32_t* cutoff_out, void* stream);
 
 typedef enum {
   FASTAV_PROF_LINEAR_STORE = 0, FASTAV_PROF_LINEAR_RESADD = 1, FASTAV_PROF_LINEAR_SWIGLU = 2,

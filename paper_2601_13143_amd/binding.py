@@ -85,6 +85,7 @@ _SIGS = {
     "fastav_rollout_workspace_bytes": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_size_t)]),
     "fastav_rollout": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
                                  C.c_void_p]),
+    "fastav_rollout_cutoff": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]),
     "fastav_create": (C.c_int, [C.POINTER(Model), C.POINTER(C.c_void_p)]),
     "fastav_destroy": (None, [C.c_void_p]),
     "fastav_set_weights": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(LayerWeights)]),
@@ -344,6 +345,22 @@ class Decoder:
         rt = torch.empty((n, n), dtype=torch.float32, device=x.device)
         _check(lib().fastav_rollout(self._h, x.data_ptr(), n, alpha, L, rt.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
         return rt.t()
+
+
+def fastav_rollout_cutoff(r: torch.Tensor, protected_mask: torch.Tensor, threshold: float):
+    """``r``: the fp32 [n, n] view fastav_rollout returned (or any tensor whose transpose is contiguous);
+    ``protected_mask``: uint8 [n] on the device.  -> (influence fp32 [n], cutoff int32 [1]), both on the device."""
+    rt = r.t()
+    n = rt.shape[0]
+    if rt.dtype != torch.float32 or not rt.is_contiguous() or rt.shape[1] != n:
+        raise ValueError("r must be the transposed view of a contiguous fp32 [n, n] tensor")
+    if protected_mask.dtype != torch.uint8 or protected_mask.numel() != n or not protected_mask.is_contiguous():
+        raise ValueError("protected_mask must be a contiguous uint8 [n] tensor")
+    infl = torch.empty(n, dtype=torch.float32, device=rt.device)
+    cut = torch.empty(1, dtype=torch.int32, device=rt.device)
+    _check(lib().fastav_rollout_cutoff(rt.data_ptr(), n, protected_mask.data_ptr(), threshold, infl.data_ptr(),
+                                       cut.data_ptr(), _stream()))
+    return infl, cut
 
 
 def fastav_attention_map(model: Model, q: torch.Tensor, k: torch.Tensor) -> torch.Tensor:

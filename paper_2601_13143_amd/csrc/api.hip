@@ -65,6 +65,8 @@ fastav_status_t launch_attention_map(const void* q, int64_t q_stride, const void
                                      int Hkv, int dh, float* stats, void* a_out, hipStream_t s);
 fastav_status_t launch_iota(int32_t* p, int n, hipStream_t s);
 fastav_status_t launch_rollout_init(float* rt, void* rt16, int n, hipStream_t s);
+fastav_status_t launch_rollout_cutoff(const float* rt, int n, const uint8_t* prot, float threshold, float* influence,
+                                      int32_t* cutoff, hipStream_t s);
 fastav_status_t launch_rollout_step(float* rt, void* rt16, const void* a16, float* c, int n, float alpha,
                                     void* linear_ws, size_t linear_ws_bytes, hipStream_t s);
 
@@ -840,6 +842,15 @@ fastav_status_t fastav_rollout(fastav_handle_t h, const void* x, int32_t n, floa
     FASTAV_TRY(launch_linear(hmlp, W.w_down, nullptr, resid, n, m.hidden, m.mlp_dim, FASTAV_EPI_RESADD, m.dtype, base + ws.gemm, ws.gemm_bytes, s));
   }
   return FASTAV_OK;
+}
+
+fastav_status_t fastav_rollout_cutoff(const float* rt, int32_t n, const uint8_t* protected_mask, float threshold,
+                                      float* influence_out, int32_t* cutoff_out, void* stream) {
+  if (!rt || !protected_mask || !influence_out || !cutoff_out) return fail(FASTAV_EINVAL, "a pointer argument is NULL");
+  if (n < 4 || n % 4) return fail(FASTAV_EINVAL, "n must be a positive multiple of 4");
+  if (!(threshold >= 0.f)) return fail(FASTAV_EINVAL, "threshold must be >= 0");
+  if ((uintptr_t)rt % 16) return fail(FASTAV_EINVAL, "rt must be 16-byte aligned");
+  return launch_rollout_cutoff(rt, n, protected_mask, threshold, influence_out, cutoff_out, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -231,4 +231,49 @@ fastav_status_t launch_rollout_step(float* rt, void* rt16, const void* a16, floa
   return check_launch("rollout_step");
 }
 
+// ---- rollout threshold -> cut-off position (Section 2.2, Global pruning) -------------------------------------
+// influence[j] = (1/n) sum_i R[i][j]: the mean of row j of the transposed product.  One wave per row.
+__global__ __launch_bounds__(256) void k_rollout_influence(const float* __restrict__ rt, int n, float* __restrict__ influence) {
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= n) return;
+  const f32x4_t* p = (const f32x4_t*)(rt + (int64_t)row * n);
+  float s0 = 0.f, s1 = 0.f;
+  int i = lane;
+  for (; i + 64 < n / 4; i += 128) {
+    const f32x4_t a = p[i], b = p[i + 64];
+    s0 += (a[0] + a[1]) + (a[2] + a[3]);
+    s1 += (b[0] + b[1]) + (b[2] + b[3]);
+  }
+  if (i < n / 4) { const f32x4_t a = p[i]; s0 += (a[0] + a[1]) + (a[2] + a[3]); }
+  float t = s0 + s1;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o, kWave);
+  if (lane == 0) influence[row] = t / (float)n;
+}
+// cutoff = 1 + the last unprotected position whose influence reaches `threshold` uniform shares (influence * n >=
+// threshold, in fp32), 0 if there is none.  One workgroup.
+__global__ __launch_bounds__(1024) void k_rollout_cutoff(const float* __restrict__ influence, const uint8_t* __restrict__ prot,
+                                                         int n, float threshold, int32_t* __restrict__ cutoff) {
+  __shared__ int wave_best[16];
+  int best = 0;
+  for (int j = threadIdx.x; j < n; j += 1024)
+    if (!prot[j] && influence[j] * (float)n >= threshold) best = j + 1;     // j ascends: the last hit stays
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) { const int t = __shfl_xor(best, o, kWave); best = t > best ? t : best; }
+  if ((threadIdx.x & 63) == 0) wave_best[threadIdx.x >> 6] = best;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int b = 0;
+    for (int w = 0; w < 16; ++w) b = wave_best[w] > b ? wave_best[w] : b;
+    cutoff[0] = b;
+  }
+}
+fastav_status_t launch_rollout_cutoff(const float* rt, int n, const uint8_t* prot, float threshold, float* influence,
+                                      int32_t* cutoff, hipStream_t s) {
+  if (n % 4) return fail(FASTAV_EINVAL, "rollout: n must be a multiple of 4");
+  if (n > 0) hipLaunchKernelGGL(k_rollout_influence, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, s, rt, n, influence);
+  hipLaunchKernelGGL(k_rollout_cutoff, dim3(1), dim3(1024), 0, s, (const float*)influence, prot, n, threshold, cutoff);
+  return check_launch("rollout_cutoff");
+}
+
 }  // namespace fastav

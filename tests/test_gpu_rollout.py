@@ -66,3 +66,56 @@ def test_rollout_is_deterministic_and_rejects_bad_arguments():
         dec.fastav_rollout(dev(x, "bf16"), 0.5, 3)             # more layers than the model has
     with pytest.raises(fa.FastavError):
         dec.fastav_rollout(dev(x[:254], "bf16"), 0.5)          # n not a multiple of 4
+
+
+def _cutoff_from(infl32: np.ndarray, prot: np.ndarray, thr: float) -> int:
+    """The integer decision on given fp32 influences, in the precision the library compares in."""
+    hit = np.nonzero((~prot) & (infl32.astype(np.float32) * np.float32(len(infl32)) >= np.float32(thr)))[0]
+    return int(hit[-1]) + 1 if hit.size else 0
+
+
+@pytest.mark.parametrize("n", [4, 132, 1028, 4100])
+def test_rollout_influence_and_cutoff_on_given_matrices(n):
+    """Column means and the threshold -> cut-off position on identical fp32 rollout matrices (a lower-triangular
+    row-stochastic matrix with early columns favoured and a few late outliers)."""
+    rng = np.random.default_rng(n)
+    R = np.tril(rng.random((n, n)) * np.exp(-np.arange(n) / (0.3 * n))[None, :] + 1e-4)
+    for j in rng.integers(n // 2, n, 3):
+        R[:, j] *= 6.0
+    R = (R / R.sum(axis=1, keepdims=True)).astype(np.float32)
+    prot = np.zeros(n, dtype=bool)
+    prot[: max(1, n // 50)] = True; prot[-max(1, n // 40):] = True
+    r_dev = torch.from_numpy(np.ascontiguousarray(R.T)).cuda().t()       # the layout fastav_rollout returns
+    p_dev = torch.from_numpy(prot.astype(np.uint8)).cuda()
+    want = orc.rollout_influence(R)
+    for thr in (0.0, 0.5, 1.0, 2.0, 5.0, 1e9):
+        infl, cut = fa.fastav_rollout_cutoff(r_dev, p_dev, thr)
+        g = infl.cpu().numpy()
+        np.testing.assert_allclose(g, want, rtol=2e-5, atol=1e-9)
+        assert abs(g.sum() - 1.0) < 1e-4
+        c = int(cut.cpu()[0])
+        assert c == _cutoff_from(g, prot, thr)                            # integer work on the same values: exact
+        margin = np.min(np.abs(want[~prot] * n - thr)) if (~prot).any() else 1.0
+        if margin > 1e-4 * max(1.0, thr):                                 # no influence sits on the threshold
+            assert c == orc.rollout_cutoff(R, prot, thr), (thr, c)
+    assert int(fa.fastav_rollout_cutoff(r_dev, torch.ones_like(p_dev), 0.0)[1].cpu()[0]) == 0   # no candidates
+
+
+def test_rollout_cutoff_after_a_rollout_and_bad_arguments():
+    m, w, weights, x = _small()
+    dec = make_decoder(m, weights)
+    r = dec.fastav_rollout(dev(x, "bf16"), 0.5, 3)
+    prot = orc.protected_mask(w.samples[0], 1)
+    infl, cut = fa.fastav_rollout_cutoff(r, torch.from_numpy(prot.astype(np.uint8)).cuda(), 1.0)
+    got_r = host(r)
+    np.testing.assert_allclose(infl.cpu().numpy(), orc.rollout_influence(got_r), rtol=2e-5, atol=1e-9)
+    assert int(cut.cpu()[0]) == _cutoff_from(infl.cpu().numpy(), prot, 1.0)
+    want = orc.attention_rollout(m, weights, x, 0.5)[2]
+    assert rel_l2(infl.cpu().numpy(), orc.rollout_influence(want)) <= 1e-2
+    lib = fa.lib()
+    ok = (r.t().data_ptr(), 256, torch.zeros(256, dtype=torch.uint8, device="cuda").data_ptr())
+    assert lib.fastav_rollout_cutoff(None, 256, ok[2], 1.0, infl.data_ptr(), cut.data_ptr(), None) == 1
+    assert lib.fastav_rollout_cutoff(ok[0], 255, ok[2], 1.0, infl.data_ptr(), cut.data_ptr(), None) == 1
+    assert lib.fastav_rollout_cutoff(ok[0], 0, ok[2], 1.0, infl.data_ptr(), cut.data_ptr(), None) == 1
+    assert lib.fastav_rollout_cutoff(ok[0], 256, ok[2], -1.0, infl.data_ptr(), cut.data_ptr(), None) == 1
+    assert lib.fastav_rollout_cutoff(ok[0], 256, ok[2], float("nan"), infl.data_ptr(), cut.data_ptr(), None) == 1
