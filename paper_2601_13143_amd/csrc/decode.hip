@@ -15,10 +15,9 @@
 //                    streams) runs once.  Plain (cached) loads measured faster than non-temporal ones.
 //
 //   k_decode_attn    single-query grouped-query attention over [cache prefix | generated so far | the new
-//                    token itself] for one (sample, KV head, key split): K and V chunks of 64 keys are staged
-//                    in LDS with coalesced 16-byte loads; one wave per query head of the group computes its 64
-//                    logits (lane = key), updates the running (max, sum) with wave reductions and accumulates
-//                    P V with lane = two output dims.  k_decode_merge combines the splits' (max, sum, o).
+//                    token itself] for one (sample, KV head, key split): logits of all heads of the group on
+//                    the matrix cores with the keys read from global memory in operand layout, P V on the
+//                    vector units straight from the V rows.  k_decode_merge combines the splits' (max, sum, o).
 #include "common.hpp"
 
 namespace fastav {
@@ -232,20 +231,37 @@ struct DecodeAttnArgs {
   const bf16_t* v_gen;
   int gen_len, gen_cap;
   int Hq, Hkv, splits, chunk; // chunk = keys per split (multiple of 64)
-  float scale;
-  float* part;                // [B, Hq, splits, DH + 2] fp32: o (unnormalised), max, sum
+  float scale_log2;           // log2(e) / sqrt(head_dim): logits live in the base-2 domain
+  float* part;                // [B, Hkv, splits, G, DH + 2] fp32: o (unnormalised), max (base-2 domain), sum
 };
 
-template <int DH>
+// One workgroup per (key split, KV head, sample); its four waves take the split's 64-key chunks in turn.
+// Per chunk a wave
+//   * reads the 64 keys straight from global memory in matrix-core operand layout (lane = key row x 16-byte
+//     dim chunk) and the query heads of the group as the other operand (heads padded to 16 columns): the
+//     logits of all heads of the group come out of DH/32 v_mfma_f32_16x16x32_bf16 per 16 keys, lane = head,
+//     four keys each;
+//   * updates the running (max, sum) of every head (in-lane over its keys, two shuffles across the lane
+//     groups), writes the 64 x G probabilities to LDS;
+//   * accumulates P V with lane = (key subgroup, 8 output dims): a V row is one 16-byte load per lane, the
+//     G probabilities of its key one broadcast LDS read, G x 8 FMAs.
+// Nothing is staged through LDS but the probabilities, and the waves never wait for each other until the
+// end, where their (max, sum, o) are combined and written as the split's partial; k_decode_merge combines the
+// splits.  (Merging in the same launch by the workgroup that finishes last was measured: the device-scope
+// release every workgroup then needs writes back its L2 and costs more than the second launch.)
+template <int DH, int GP>
 __global__ __launch_bounds__(256) void k_decode_attn(DecodeAttnArgs a) {
-  constexpr int CK = 64;                              // keys per staged chunk
-  constexpr int KROW = DH + 8;                        // padded K row (elements): 16-byte reads of 16 rows spread over the banks
-  __shared__ __attribute__((aligned(16))) bf16_t ks[CK * KROW];
-  __shared__ __attribute__((aligned(16))) bf16_t vs[CK * DH];
-  __shared__ float qs[8][DH];
-  __shared__ float ps[8][CK];
+  constexpr int CK = 64;                              // keys per chunk
+  constexpr int STEPS = DH / 32;                      // matrix instructions per 16-key tile
+  constexpr int SEGS = DH / 8;                        // lanes (16-byte segments) per V row
+  constexpr int KPI = 64 / SEGS;                      // keys one wave-wide V load covers
+  constexpr int NIT = CK / KPI;
+  constexpr int PD = DH + 2;
+  __shared__ __attribute__((aligned(16))) float ps[4][CK][GP];
+  __shared__ __attribute__((aligned(16))) float red_o[4][GP][DH];     // the four waves' outputs
+  __shared__ float red_m[4][GP], red_l[4][GP];
   const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
-  const int G = a.Hq / a.Hkv;                         // <= 8 (checked by the launcher)
+  const int G = a.Hq / a.Hkv;                         // <= GP (checked by the launcher)
   const int kd = a.Hkv * DH;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -253,115 +269,202 @@ __global__ __launch_bounds__(256) void k_decode_attn(DecodeAttnArgs a) {
   const int n_tot = n_pre + a.gen_len + 1;
   const int j_begin = split * a.chunk;
   const int j_end = (j_begin + a.chunk < n_tot) ? j_begin + a.chunk : n_tot;
-
-  for (int i = tid; i < G * DH; i += 256) qs[i / DH][i % DH] = (float)a.q[(int64_t)b * a.q_stride + (g * G) * DH + i];
+  const int head = lane & 15, lg = lane >> 4;         // logits: lane = (head column, lane group)
+  const int seg = lane % SEGS, kq = lane / SEGS;      // P V: lane = (8 output dims, key subgroup)
 
   // row j of the unified key list: prefix, then generated, then the token itself
-  auto krow = [&](int j) -> const bf16_t* {
+  auto krow = [&](int j) __attribute__((always_inline)) -> const bf16_t* {
     if (j < n_pre) return a.k_prefix + (int64_t)(p0 + j) * kd + g * DH;
     if (j < n_pre + a.gen_len) return a.k_gen + ((int64_t)b * a.gen_cap + (j - n_pre)) * kd + g * DH;
     return a.k_self + (int64_t)b * a.q_stride + g * DH;
   };
-  auto vrow = [&](int j) -> const bf16_t* {
+  auto vrow = [&](int j) __attribute__((always_inline)) -> const bf16_t* {
     if (j < n_pre) return a.v_prefix + (int64_t)(p0 + j) * kd + g * DH;
     if (j < n_pre + a.gen_len) return a.v_gen + ((int64_t)b * a.gen_cap + (j - n_pre)) * kd + g * DH;
     return a.v_self + (int64_t)b * a.q_stride + g * DH;
   };
 
-  constexpr int NP = 2;                               // head passes: waves 0..3 serve heads 0..3, then 4..7
-  constexpr int DPL = DH / 64;                        // output dims per lane
-  float m_run[NP], l_run[NP], o[NP][DPL];
+  bf16x8_t qf[STEPS];
 #pragma unroll
-  for (int p = 0; p < NP; ++p) {
-    m_run[p] = -INFINITY; l_run[p] = 0.f;
-#pragma unroll
-    for (int d = 0; d < DPL; ++d) o[p][d] = 0.f;
+  for (int st = 0; st < STEPS; ++st) {
+    bf16x8_t z = {0, 0, 0, 0, 0, 0, 0, 0};
+    qf[st] = head < G ? *(const bf16x8_t*)(a.q + (int64_t)b * a.q_stride + (g * G + head) * DH + lg * 8 + 32 * st) : z;
   }
+  float m_run = -INFINITY, l_part = 0.f;              // per head (column): max over all lane groups, this lane's share of the sum
+  float acc[GP][8];
+#pragma unroll
+  for (int h = 0; h < GP; ++h)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
 
-  for (int j0 = j_begin; j0 < j_end; j0 += CK) {
-    __syncthreads();                                  // previous chunk fully consumed (and qs written)
-    constexpr int VPR = DH / 8;                       // 16-byte vectors per row
-    for (int i = tid; i < CK * VPR; i += 256) {
-      const int r = i / VPR, c = i % VPR;
-      const int j = (j0 + r < j_end) ? j0 + r : j_end - 1;       // tail rows repeat the last key (masked below)
-      *(bf16x8_t*)(ks + r * KROW + c * 8) = *(const bf16x8_t*)(krow(j) + c * 8);
-      *(bf16x8_t*)(vs + r * DH + c * 8) = *(const bf16x8_t*)(vrow(j) + c * 8);
+  for (int c0 = j_begin + wave * CK; c0 < j_end; c0 += 4 * CK) {
+    bf16x8_t kf[4][STEPS], vf[NIT];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      int j = c0 + t * 16 + head;                     // here `head` is the key row of the A operand
+      j = j < j_end ? j : j_end - 1;                  // rows past the end repeat the last key (masked below)
+      const bf16_t* kr = krow(j) + lg * 8;
+#pragma unroll
+      for (int st = 0; st < STEPS; ++st) kf[t][st] = *(const bf16x8_t*)(kr + 32 * st);
     }
-    __syncthreads();
 #pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      const int hs = p * 4 + wave;                    // head inside the group (wave-uniform)
-      if (hs < G) {
-        // logits: lane = key
-        float z = 0.f;
-        const bf16_t* kr = ks + lane * KROW;
+    for (int it = 0; it < NIT; ++it) {
+      int j = c0 + it * KPI + kq;
+      j = j < j_end ? j : j_end - 1;
+      vf[it] = *(const bf16x8_t*)(vrow(j) + seg * 8);
+    }
+    f32x4v sc[4];
+    float mx = -INFINITY;
 #pragma unroll
-        for (int c = 0; c < VPR; ++c) {
-          const bf16x8_t kv = *(const bf16x8_t*)(kr + c * 8);
+    for (int t = 0; t < 4; ++t) {
+      f32x4v c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int e = 0; e < 8; ++e) z = fmaf(qs[hs][c * 8 + e], (float)kv[e], z);
-        }
-        z = (j0 + lane < j_end) ? z * a.scale : -INFINITY;
-        const float m_new = fmaxf(m_run[p], wave_max(z));         // finite: every chunk holds at least one key
-        const float alpha = __expf(m_run[p] - m_new);
-        const float pr = __expf(z - m_new);
-        l_run[p] = l_run[p] * alpha + wave_sum(pr);
-        m_run[p] = m_new;
-        ps[hs][lane] = pr;
-        // P V: lane = DPL consecutive output dims; a wave's own writes to ps are visible to it after the
-        // LDS counter wait the compiler places before the reads
-        __builtin_amdgcn_wave_barrier();
-        float acc[DPL];
+      for (int st = 0; st < STEPS; ++st) c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t][st], qf[st], c, 0, 0, 0);
 #pragma unroll
-        for (int d = 0; d < DPL; ++d) acc[d] = 0.f;
-        for (int jj = 0; jj < CK; ++jj) {
-          const float pj = ps[hs][jj];
+      for (int r = 0; r < 4; ++r) {
+        c[r] = (c0 + t * 16 + lg * 4 + r < j_end) ? c[r] * a.scale_log2 : -INFINITY;
+        mx = fmaxf(mx, c[r]);
+      }
+      sc[t] = c;
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));        // finite: key c0 exists
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);      // exp2(-inf) = 0 on the first chunk
+    float psum = 0.f;
 #pragma unroll
-          for (int d = 0; d < DPL; ++d) acc[d] = fmaf(pj, (float)vs[jj * DH + lane * DPL + d], acc[d]);
-        }
+    for (int t = 0; t < 4; ++t)
 #pragma unroll
-        for (int d = 0; d < DPL; ++d) o[p][d] = o[p][d] * alpha + acc[d];
+      for (int r = 0; r < 4; ++r) {
+        const float pr = __builtin_amdgcn_exp2f(sc[t][r] - m_new);
+        psum += pr;
+        if (head < GP) ps[wave][t * 16 + lg * 4 + r][head] = pr;
+      }
+    l_part = l_part * alpha + psum;
+    m_run = m_new;
+    // the wave's own LDS writes are visible to its other lanes after the LDS counter wait below
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+#pragma unroll
+    for (int h = 0; h < GP; ++h) {
+      const float ah = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(alpha), h));          // lane h holds head h
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[h][e] *= ah;
+    }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      float pv[GP];
+#pragma unroll
+      for (int h4 = 0; h4 < GP; h4 += 4) {
+        const f32x4v t4 = *(const f32x4v*)&ps[wave][it * KPI + kq][h4];
+        pv[h4] = t4[0]; pv[h4 + 1] = t4[1]; pv[h4 + 2] = t4[2]; pv[h4 + 3] = t4[3];
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float v = (float)vf[it][e];
+#pragma unroll
+        for (int h = 0; h < GP; ++h) acc[h][e] = fmaf(pv[h], v, acc[h][e]);
       }
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();                  // all reads of ps done before the next chunk rewrites it
   }
+
+  // ---- combine inside the wave: the sum over lane groups, the outputs over key subgroups
+  l_part += __shfl_xor(l_part, 16, kWave);
+  l_part += __shfl_xor(l_part, 32, kWave);
 #pragma unroll
-  for (int p = 0; p < NP; ++p) {
-    const int hs = p * 4 + wave;
-    if (hs < G) {
-      float* out = a.part + (((int64_t)b * a.Hq + g * G + hs) * a.splits + split) * (DH + 2);
+  for (int h = 0; h < GP; ++h)
 #pragma unroll
-      for (int d = 0; d < DPL; ++d) out[lane * DPL + d] = o[p][d];
-      if (lane == 0) { out[DH] = m_run[p]; out[DH + 1] = l_run[p]; }
+    for (int e = 0; e < 8; ++e) {
+      float v = acc[h][e];
+#pragma unroll
+      for (int o = SEGS; o < 64; o <<= 1) v += __shfl_xor(v, o, kWave);
+      acc[h][e] = v;
+    }
+  if (kq == 0) {
+#pragma unroll
+    for (int h = 0; h < GP; ++h) {
+      f32x4v lo = {acc[h][0], acc[h][1], acc[h][2], acc[h][3]}, hi = {acc[h][4], acc[h][5], acc[h][6], acc[h][7]};
+      *(f32x4v*)&red_o[wave][h][seg * 8] = lo;
+      *(f32x4v*)&red_o[wave][h][seg * 8 + 4] = hi;
     }
   }
-}
-
-// One wave per (sample, head).  Lane s first holds split s's (max, sum): the global max and every split's
-// weight come from two wave reductions; then the lanes turn to the output dims and add the splits' partial
-// outputs in split order (independent, coalesced loads).  splits <= 64.
-template <int DH>
-__global__ __launch_bounds__(64) void k_decode_merge(const float* __restrict__ part, int splits, int Hq,
-                                                     bf16_t* __restrict__ out, int64_t out_stride) {
-  constexpr int DPL = DH / 64;
-  const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
-  const float* p = part + ((int64_t)b * Hq + h) * splits * (DH + 2);
-  const float ms = lane < splits ? p[lane * (DH + 2) + DH] : -INFINITY;      // -inf: a split past this sample's keys
-  const float ls = lane < splits ? p[lane * (DH + 2) + DH + 1] : 0.f;
-  const float m = wave_max(ms);
-  const float wgt = (ms == -INFINITY) ? 0.f : __expf(ms - m);
-  const float inv = 1.0f / wave_sum(wgt * ls);
-  float o[DPL];
+  if (lane < GP) { red_m[wave][lane] = m_run; red_l[wave][lane] = l_part; }
+  __syncthreads();
+  // ---- combine the four waves, write the split's partial: thread = (head, dim)
+  float* part = a.part + (((int64_t)b * a.Hkv + g) * a.splits + split) * (int64_t)(G * PD);
+  for (int i = tid; i < G * DH; i += 256) {
+    const int h = i / DH, d = i % DH;
+    float M = red_m[0][h];
 #pragma unroll
-  for (int d = 0; d < DPL; ++d) o[d] = 0.f;
-  for (int s = 0; s < splits; ++s) {
-    const float w = __shfl(wgt, s, kWave);
+    for (int w = 1; w < 4; ++w) M = fmaxf(M, red_m[w][h]);
+    float o = 0.f, l = 0.f;
 #pragma unroll
-    for (int d = 0; d < DPL; ++d) o[d] = fmaf(w, p[s * (DH + 2) + lane * DPL + d], o[d]);
+    for (int w = 0; w < 4; ++w) {
+      const float mw = red_m[w][h];
+      const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
+      o = fmaf(f, red_o[w][h][d], o);
+      l = fmaf(f, red_l[w][h], l);
+    }
+    part[h * PD + d] = o;
+    if (d == 0) { part[h * PD + DH] = M; part[h * PD + DH + 1] = l; }
   }
-#pragma unroll
-  for (int d = 0; d < DPL; ++d) out[(int64_t)b * out_stride + h * DH + lane * DPL + d] = (bf16_t)(o[d] * inv);
 }
 
+// Merge of the splits' partials: one workgroup per (query head, sample), no loop-carried waits.  Every wave
+// loads the splits' (max, sum) with lane = split and gets the global max and the weights from two wave
+// reductions; thread = (split group, 4 output dims) has the weighted outputs of its splits in flight at the same
+// time (independent 8-byte loads, out-of-range splits clamped and weighted 0), and the groups are summed through
+// LDS.  splits <= 64.
+template <int DH>
+__global__ __launch_bounds__(256) void k_decode_merge(const float* __restrict__ part_all, int splits, int Hq, int Hkv,
+                                                      bf16_t* __restrict__ out, int64_t out_stride) {
+  constexpr int PD = DH + 2;
+  constexpr int QUADS = DH / 4;                       // 32 or 16 column quads
+  constexpr int NSG = 256 / QUADS;                    // 8 or 16 split groups
+  constexpr int NK = 64 / NSG;                        // splits per thread
+  __shared__ __attribute__((aligned(16))) float red_o[NSG][DH];
+  const int hq = blockIdx.x, b = blockIdx.y;
+  const int G = Hq / Hkv, g = hq / G, h = hq % G;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // partial of (split sp, head h): pall + sp * G * PD
+  const float* pall = part_all + (((int64_t)b * Hkv + g) * splits * G + h) * (int64_t)PD;
+  const int c = tid % QUADS, sg = tid / QUADS;
+  float2 lo[NK], hi[NK];
+#pragma unroll
+  for (int k = 0; k < NK; ++k) {
+    int sp = sg + k * NSG;
+    sp = sp < splits ? sp : splits - 1;
+    // rows are PD = DH + 2 floats apart: 8-byte aligned, so two 8-byte loads per quad
+    lo[k] = *(const float2*)(pall + (int64_t)sp * G * PD + c * 4);
+    hi[k] = *(const float2*)(pall + (int64_t)sp * G * PD + c * 4 + 2);
+  }
+  const float ms = lane < splits ? pall[(int64_t)lane * G * PD + DH] : -INFINITY;   // -inf: a split past this sample's keys
+  const float ls = lane < splits ? pall[(int64_t)lane * G * PD + DH + 1] : 0.f;
+  const float M = wave_max(ms);                       // finite: split 0 always holds a key
+  const float wgt = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - M);
+  const float inv = 1.0f / wave_sum(wgt * ls);
+  f32x4v o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int k = 0; k < NK; ++k) {
+    const int sp = sg + k * NSG;                      // < 64: lane sp of this wave holds its weight (0 beyond splits)
+    const float f = __shfl(wgt, sp, kWave);
+    o[0] = fmaf(f, lo[k].x, o[0]); o[1] = fmaf(f, lo[k].y, o[1]);
+    o[2] = fmaf(f, hi[k].x, o[2]); o[3] = fmaf(f, hi[k].y, o[3]);
+  }
+  *(f32x4v*)&red_o[sg][c * 4] = o;
+  __syncthreads();
+  if (tid < DH) {
+    float t = 0.f;
+#pragma unroll
+    for (int q = 0; q < NSG; ++q) t += red_o[q][tid];
+    out[(int64_t)b * out_stride + hq * DH + tid] = (bf16_t)(t * inv);
+  }
+}
+
+// partials [B, Hkv, splits, G, dh + 2] fp32
 size_t decode_attn_workspace_bytes(int batch, int Hq, int dh, int max_splits) {
   return align_up((size_t)batch * Hq * max_splits * (dh + 2) * sizeof(float), 256);
 }
@@ -386,7 +489,7 @@ fastav_status_t launch_decode_attention(const void* q, const void* k_self, const
   if (Hq % Hkv || Hq / Hkv > 8) return fail(FASTAV_EUNSUPPORTED, "decode attention: at most 8 query heads per KV head");
   if (gen_len > 0 && (!k_gen || !v_gen)) return fail(FASTAV_EINVAL, "decode attention: gen_len > 0 needs the generated-token caches");
   if (q_stride % 8 || ((uintptr_t)q | (uintptr_t)k_self | (uintptr_t)v_self | (uintptr_t)k_prefix | (uintptr_t)v_prefix |
-                        (uintptr_t)k_gen | (uintptr_t)v_gen) % 16)
+                        (uintptr_t)k_gen | (uintptr_t)v_gen) % 16 || ((Hkv * dh) % 8))
     return fail(FASTAV_EINVAL, "decode attention: operands must be 16-byte aligned");
   DecodeAttnArgs a;
   a.q = (const bf16_t*)q; a.k_self = (const bf16_t*)k_self; a.v_self = (const bf16_t*)v_self; a.q_stride = q_stride;
@@ -396,19 +499,25 @@ fastav_status_t launch_decode_attention(const void* q, const void* k_self, const
   const int max_keys = max_prefix + gen_len + 1;
   a.splits = decode_attn_splits(batch, Hkv, max_keys);
   a.chunk = (int)(ceil_div(ceil_div(max_keys, a.splits), 64) * 64);
-  a.scale = 1.0f / sqrtf((float)dh);
+  a.scale_log2 = 1.4426950408889634f / sqrtf((float)dh);
   a.part = part;
-  if (decode_attn_workspace_bytes(batch, Hq, dh, a.splits) > part_bytes)
+  if ((size_t)batch * Hq * a.splits * (dh + 2) * sizeof(float) > part_bytes)
     return fail(FASTAV_EINVAL, "decode attention: workspace too small");
   ProfScope prof(FASTAV_PROF_ATTENTION, bytes_hint, s);
   const dim3 grid((unsigned)a.splits, (unsigned)Hkv, (unsigned)batch);
-  if (dh == 128) {
-    hipLaunchKernelGGL(k_decode_attn<128>, grid, dim3(256), 0, s, a);
-    hipLaunchKernelGGL(k_decode_merge<128>, dim3((unsigned)Hq, (unsigned)batch), dim3(64), 0, s, part, a.splits, Hq, (bf16_t*)out, out_stride);
-  } else {
-    hipLaunchKernelGGL(k_decode_attn<64>, grid, dim3(256), 0, s, a);
-    hipLaunchKernelGGL(k_decode_merge<64>, dim3((unsigned)Hq, (unsigned)batch), dim3(64), 0, s, part, a.splits, Hq, (bf16_t*)out, out_stride);
-  }
+  const int G = Hq / Hkv;
+  const dim3 mgrid((unsigned)Hq, (unsigned)batch);
+#define FASTAV_DECODE_ATTN(DH_, GP_)                                                                              \
+  do {                                                                                                            \
+    hipLaunchKernelGGL((k_decode_attn<DH_, GP_>), grid, dim3(256), 0, s, a);                                      \
+    hipLaunchKernelGGL((k_decode_merge<DH_>), mgrid, dim3(256), 0, s, (const float*)part, a.splits, Hq, Hkv,      \
+                       (bf16_t*)out, out_stride);                                                                 \
+  } while (0)
+  if (dh == 128 && G <= 4) FASTAV_DECODE_ATTN(128, 4);
+  else if (dh == 128) FASTAV_DECODE_ATTN(128, 8);
+  else if (G <= 4) FASTAV_DECODE_ATTN(64, 4);
+  else FASTAV_DECODE_ATTN(64, 8);
+#undef FASTAV_DECODE_ATTN
   return check_launch("decode_attention");
 }
 
