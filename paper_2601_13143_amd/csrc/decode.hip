@@ -85,31 +85,69 @@ __global__ __launch_bounds__(64 * NW) void k_skinny_linear(SkinnyArgs a) {
     preloaded = true;
   }
   if (NORM) {
-    // wave w reduces the rows w, w + NW, ...; then all threads write the normalised rows, rounded the way
-    // k_rmsnorm rounds them
-    for (int b = wave; b < a.B; b += NW) {
-      const f32x4v* xr = (const f32x4v*)(a.xres + (int64_t)b * a.K);
-      float ss = 0.f;
-      for (int i = lane; i < a.K / 4; i += 64) {
-        const f32x4v v = xr[i];
-        ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-      }
-      ss = wave_sum(ss);
-      if (lane == 0) rs[b] = 1.0f / sqrtf(ss / (float)a.K + a.eps);
-    }
-    lds_barrier();
+    constexpr int NT = 64 * NW, R1 = 4;                         // one row in registers: up to R1 quads per thread
     const int per_row = a.K / 4;
-    for (int i = tid; i < a.B * per_row; i += 64 * NW) {
-      const int b = i / per_row, c = i % per_row;
-      const f32x4v v = ((const f32x4v*)(a.xres + (int64_t)b * a.K))[c];
-      const bf16x4_t gv = ((const bf16x4_t*)a.g)[c];
-      const float r = rs[b];
-      bf16x4_t o;
+    if (a.B == 1 && per_row <= R1 * NT) {
+      // a single row: every thread keeps its quads, the row is read once
+      __shared__ float wsum[NW];
+      f32x4v v[R1];
+      bf16x4_t gv[R1];
+      float ss = 0.f;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) o[e] = (bf16_t)(v[e] * r * (float)gv[e]);
-      ((bf16x4_t*)(xs + b * a.K))[c] = o;
+      for (int it = 0; it < R1; ++it) {
+        const int i = tid + it * NT;
+        if (i < per_row) {
+          v[it] = ((const f32x4v*)a.xres)[i];
+          gv[it] = ((const bf16x4_t*)a.g)[i];
+        }
+      }
+#pragma unroll
+      for (int it = 0; it < R1; ++it)
+        if (tid + it * NT < per_row) ss += v[it][0] * v[it][0] + v[it][1] * v[it][1] + v[it][2] * v[it][2] + v[it][3] * v[it][3];
+      ss = wave_sum(ss);
+      if (lane == 0) wsum[wave] = ss;
+      lds_barrier();
+      float tot = 0.f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) tot += wsum[w];              // fixed order: the same value in every thread
+      const float r = 1.0f / sqrtf(tot / (float)a.K + a.eps);
+#pragma unroll
+      for (int it = 0; it < R1; ++it) {
+        const int i = tid + it * NT;
+        if (i < per_row) {
+          bf16x4_t o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (bf16_t)(v[it][e] * r * (float)gv[it][e]);
+          ((bf16x4_t*)xs)[i] = o;
+        }
+      }
+      lds_barrier();
+    } else {
+      // wave w reduces the rows w, w + NW, ...; then all threads write the normalised rows, rounded the way
+      // k_rmsnorm rounds them
+      for (int b = wave; b < a.B; b += NW) {
+        const f32x4v* xr = (const f32x4v*)(a.xres + (int64_t)b * a.K);
+        float ss = 0.f;
+        for (int i = lane; i < a.K / 4; i += 64) {
+          const f32x4v v = xr[i];
+          ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+        }
+        ss = wave_sum(ss);
+        if (lane == 0) rs[b] = 1.0f / sqrtf(ss / (float)a.K + a.eps);
+      }
+      lds_barrier();
+      for (int i = tid; i < a.B * per_row; i += NT) {
+        const int b = i / per_row, c = i % per_row;
+        const f32x4v v = ((const f32x4v*)(a.xres + (int64_t)b * a.K))[c];
+        const bf16x4_t gv = ((const bf16x4_t*)a.g)[c];
+        const float r = rs[b];
+        bf16x4_t o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (bf16_t)(v[e] * r * (float)gv[e]);
+        ((bf16x4_t*)(xs + b * a.K))[c] = o;
+      }
+      lds_barrier();
     }
-    lds_barrier();
   }
 
   for (; s + NW * (U - 1) < steps; s += NW * U) {
@@ -200,8 +238,9 @@ fastav_status_t launch_skinny_linear(const void* x, const void* const* w_seg, co
                    : (epilogue == FASTAV_EPI_RESADD ? FASTAV_PROF_LINEAR_RESADD : FASTAV_PROF_LINEAR_STORE);
   // the work figure of a decode GEMV is its weight bytes (HBM-bound), not flops
   ProfScope prof(kind, (double)n * k * 2.0 * (epilogue == FASTAV_EPI_SWIGLU ? 2.0 : 1.0), s);
-  // few row blocks (narrow outputs): eight waves split K, which doubles the loads in flight per CU
-  const bool wide = (n / 16 < 3 * 256) && (k % 256 == 0);
+  // eight waves split K where its length allows: twice the loads in flight per workgroup (measured faster for
+  // every projection of the 7B shape, also the wide gate/up one)
+  const bool wide = k % 256 == 0;
   const dim3 grid((unsigned)(n / 16));
   if (epilogue == FASTAV_EPI_SWIGLU && (!w2 || ((uintptr_t)w2 % 16)))
     return fail(FASTAV_EINVAL, "skinny linear: SwiGLU needs a 16-byte aligned up matrix");

@@ -12,6 +12,8 @@
 namespace fastav {
 
 constexpr int kScoreChunk = 128;   // keys per workgroup
+constexpr int kFinalizeKeys = 1024; // keys per workgroup of the finalize kernel (a multiple of 256)
+constexpr int kFinalizeBatch = 8;   // 16-byte logits loads in flight per lane
 
 template <typename T> struct Vec16;
 template <> struct Vec16<bf16_t> { typedef bf16x8_t type; static constexpr int n = 8; };
@@ -261,8 +263,21 @@ __global__ __launch_bounds__(256) void k_score_finalize(const float* __restrict_
   extern __shared__ float mls[];                           // [n_rows*Hq][2] : (m, 1/l)
   const int b = blockIdx.y;
   const int row0 = cu[b], n = cu[b + 1] - row0;
-  if ((int)(blockIdx.x * 256) >= n) return;
+  if ((int)(blockIdx.x * kFinalizeKeys) >= n + 3) return;
   const int n_rows = n_last < n ? n_last : n;
+  const int P = n_rows * Hq;
+  // vector path: a thread owns four consecutive positions of the packed token axis, aligned to 16 bytes there (a
+  // sample may start anywhere, so the quad may hang over the sample's ends: those lanes of it are dropped).  The
+  // first kFinalizeBatch planes are requested before the (max, sum) merge below, which does not depend on them.
+  const bool vec = (T_total & 3) == 0;
+  const int64_t q0 = (int64_t)(row0 & ~3) + (int64_t)blockIdx.x * kFinalizeKeys + threadIdx.x * 4;
+  const bool mine = vec && q0 < row0 + n;
+  f32x4_t L[kFinalizeBatch];
+  if (mine) {
+#pragma unroll
+    for (int u = 0; u < kFinalizeBatch; ++u)
+      if (u < P) L[u] = *(const f32x4_t*)(logits + q0 + (int64_t)u * T_total);
+  }
   if (ml_in) {
     for (int idx = threadIdx.x; idx < n_rows * Hq; idx += 256) {
       const int rl = idx / Hq, h = idx % Hq;
@@ -271,43 +286,82 @@ __global__ __launch_bounds__(256) void k_score_finalize(const float* __restrict_
     }
   } else {
     // merge the per-chunk (max, sum-exp) partials: eight lanes per (row, head) pair, strided over the chunks,
-    // 32 pairs per pass of the workgroup (every workgroup of a sample repeats this small merge, so it is laid
-    // out for few dependent steps: independent loads, then two 8-lane butterflies)
+    // 32 pairs per pass of the workgroup.  Every workgroup of a sample repeats this small merge, so it is laid
+    // out for few dependent steps: eight independent 8-byte loads per lane and round, merged online, then one
+    // 8-lane butterfly.
     const int nc = (n + kScoreChunk - 1) / kScoreChunk;
     const int sub = threadIdx.x & 7;
     for (int base = 0; base < n_rows * Hq; base += 32) {
       const int idx = base + (threadIdx.x >> 3);
       const bool live = idx < n_rows * Hq;
       const int rl = live ? idx / Hq : 0, h = live ? idx % Hq : 0;
-      const float* p = partials + (((int64_t)rl * Hq + h) * n_chunk_slots + row0 / kScoreChunk + b) * 2;
-      float m = -INFINITY;
-      if (live) for (int c = sub; c < nc; c += 8) m = fmaxf(m, p[2 * c]);
+      const float2* p = (const float2*)(partials + (((int64_t)rl * Hq + h) * n_chunk_slots + row0 / kScoreChunk + b) * 2);
+      float m = -INFINITY, l = 0.f;
+      for (int c0 = 0; c0 < nc; c0 += 64) {
+        float2 v[8];
 #pragma unroll
-      for (int o = 1; o < 8; o <<= 1) m = fmaxf(m, __shfl_xor(m, o, kWave));
-      float l = 0.f;
-      if (live) for (int c = sub; c < nc; c += 8) { const float mc = p[2 * c]; if (mc > -INFINITY) l += p[2 * c + 1] * expf(mc - m); }
+        for (int u = 0; u < 8; ++u) {
+          const int c = c0 + sub + 8 * u;
+          v[u] = (live && c < nc) ? p[c] : make_float2(-INFINITY, 0.f);
+        }
+        float mb = m;
 #pragma unroll
-      for (int o = 1; o < 8; o <<= 1) l += __shfl_xor(l, o, kWave);
+        for (int u = 0; u < 8; ++u) mb = fmaxf(mb, v[u].x);
+        if (mb > -INFINITY) {
+          l *= expf(m - mb);
+#pragma unroll
+          for (int u = 0; u < 8; ++u) if (v[u].x > -INFINITY) l += v[u].y * expf(v[u].x - mb);
+          m = mb;
+        }
+      }
+#pragma unroll
+      for (int o = 1; o < 8; o <<= 1) {
+        const float m2 = __shfl_xor(m, o, kWave), l2 = __shfl_xor(l, o, kWave);
+        const float mn = fmaxf(m, m2);
+        const float ms = (mn == -INFINITY) ? 0.f : mn;
+        l = l * expf(m - ms) + l2 * expf(m2 - ms);
+        m = mn;
+      }
       if (live && sub == 0) { mls[2 * idx] = m; mls[2 * idx + 1] = 1.0f / l; }
     }
   }
   __syncthreads();
-  const int j = blockIdx.x * 256 + threadIdx.x;
-  if (j >= n) return;
-  // eight loads in flight per lane; the terms are added in index order, as a plain loop would
-  const int P = n_rows * Hq;
-  const float* lp = logits + row0 + j;                            // idx = rl*Hq + h selects the plane
-  float s = 0.f;
-  int idx = 0;
-  for (; idx + 8 <= P; idx += 8) {
-    float L[8];
+  if (vec) {
+    if (!mine) return;
+    const float* lp = logits + q0;                                // idx = rl*Hq + h selects the plane
+    f32x4_t s = {0.f, 0.f, 0.f, 0.f};                             // the terms are added in index order
+    for (int idx = 0; idx < P; idx += kFinalizeBatch) {
+      if (idx > 0) {
 #pragma unroll
-    for (int u = 0; u < 8; ++u) L[u] = lp[(int64_t)(idx + u) * T_total];
+        for (int u = 0; u < kFinalizeBatch; ++u)
+          if (idx + u < P) L[u] = *(const f32x4_t*)(lp + (int64_t)(idx + u) * T_total);
+      }
 #pragma unroll
-    for (int u = 0; u < 8; ++u) s += expf(L[u] - mls[2 * (idx + u)]) * mls[2 * (idx + u) + 1];
+      for (int u = 0; u < kFinalizeBatch; ++u) {
+        if (idx + u < P) {
+          const float m = mls[2 * (idx + u)], il = mls[2 * (idx + u) + 1];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) s[e] += expf(L[u][e] - m) * il;
+        }
+      }
+    }
+    if (q0 >= row0 && q0 + 3 < row0 + n && ((uintptr_t)scores & 15) == 0) {
+      *(f32x4_t*)(scores + q0) = s / (float)P;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (q0 + e >= row0 && q0 + e < row0 + n) scores[q0 + e] = s[e] / (float)P;
+    }
+    return;
   }
-  for (; idx < P; ++idx) s += expf(lp[(int64_t)idx * T_total] - mls[2 * idx]) * mls[2 * idx + 1];
-  scores[row0 + j] = s / (float)P;
+  for (int it = 0; it < kFinalizeKeys / 256; ++it) {
+    const int j = blockIdx.x * kFinalizeKeys + it * 256 + threadIdx.x;
+    if (j >= n) return;
+    const float* lp = logits + row0 + j;
+    float s = 0.f;
+    for (int idx = 0; idx < P; ++idx) s += expf(lp[(int64_t)idx * T_total] - mls[2 * idx]) * mls[2 * idx + 1];
+    scores[row0 + j] = s / (float)P;
+  }
 }
 
 // Chunk slots of the whole packed batch: sample b's chunks start at slot cu[b]/chunk + b.
@@ -353,6 +407,8 @@ fastav_status_t launch_score_logits(const void* q, int64_t q_stride, const void*
   if (dtype == FASTAV_BF16 && G * n_last <= 64 && q_stride % 8 == 0 && k_stride % 8 == 0 &&
       (((uintptr_t)q | (uintptr_t)k) % 16) == 0) {
     const int wpg = Hkv < 8 ? Hkv : 8;                            // waves (KV heads) per workgroup
+    // one 128-key chunk per workgroup, chunks in launch order: neighbouring workgroups stream neighbouring
+    // memory (letting a workgroup walk chunks a stride apart measured 10 % slower)
     const dim3 grid_m(grid.x, grid.y, (unsigned)((Hkv + wpg - 1) / wpg));
 #define FASTAV_SCORE_MFMA(DHH, NBB)                                                                                      \
   hipLaunchKernelGGL((k_score_logits_mfma<DHH, NBB>), grid_m, dim3(64 * wpg), 0, s, (const bf16_t*)q, q_stride, (const bf16_t*)k, \
@@ -378,7 +434,8 @@ fastav_status_t launch_score_finalize(const float* logits, const float* ml, cons
                                       hipStream_t s) {
   if (batch == 0 || max_seqlen == 0) return FASTAV_OK;
   ProfScope prof(FASTAV_PROF_SCORE, 4.0 * n_last * Hq * T + 4.0 * T, s);
-  dim3 grid((unsigned)ceil_div(max_seqlen, 256), (unsigned)batch);
+  // + 3: a sample that starts off a 16-byte boundary needs up to three more positions
+  dim3 grid((unsigned)ceil_div(max_seqlen + 3, kFinalizeKeys), (unsigned)batch);
   const size_t shmem = (size_t)n_last * Hq * 2 * sizeof(float);
   hipLaunchKernelGGL(k_score_finalize, grid, dim3(256), shmem, s, logits, ml, partials, chunk_slots(T, batch), cu, Hq,
                      n_last, T, scores);
