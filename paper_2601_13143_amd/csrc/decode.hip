@@ -202,6 +202,129 @@ __global__ __launch_bounds__(64 * NW) void k_skinny_linear(SkinnyArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------------------- one-row GEMV
+// Y[n] = sum_k X[k] W[n, k] for a single input row (the paper's latency case: one sample generates one token).
+// With one row there is nothing for the matrix cores to reuse, so the kernel is laid out purely for the weight
+// stream: a wave owns two consecutive weight rows and reads them as whole 1 KB runs (lane = 16-byte chunk), eight
+// to sixteen loads in flight per lane; a workgroup's eight waves cover 16 rows = one contiguous slab.  The input
+// row sits in LDS as bf16 (normalised there when NORM, exactly as k_skinny_linear does it), each 16-byte chunk of
+// it is read once per pair of rows and multiplied with v_dot2_f32_bf16 into fp32 sums, which the wave reduces at
+// the end.  K % 512 == 0.
+__device__ __forceinline__ float dot8(bf16x8_t w, bf16x8_t x, float acc) {
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(w, w, 0, 1), __builtin_shufflevector(x, x, 0, 1), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(w, w, 2, 3), __builtin_shufflevector(x, x, 2, 3), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(w, w, 4, 5), __builtin_shufflevector(x, x, 4, 5), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(w, w, 6, 7), __builtin_shufflevector(x, x, 6, 7), acc, false);
+  return acc;
+}
+
+template <int EPI, bool NORM>
+__global__ __launch_bounds__(512) void k_gemv_rows(SkinnyArgs a) {
+  constexpr int NW = 8, NT = 64 * NW;
+  constexpr int UB = (EPI == FASTAV_EPI_SWIGLU) ? 4 : 8;        // chunks per row and batch: 16 loads in flight per lane
+  extern __shared__ __attribute__((aligned(16))) bf16_t xs[];   // [K] the input row
+  __shared__ float wsum[NW];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n0 = blockIdx.x * 16;
+  const bf16_t* wbase = a.w[0];
+  int seg0 = 0;
+  if (EPI != FASTAV_EPI_SWIGLU) {
+    if (n0 >= a.seg_end[0]) { wbase = a.w[1]; seg0 = a.seg_end[0]; }
+    if (n0 >= a.seg_end[1]) { wbase = a.w[2]; seg0 = a.seg_end[1]; }
+  }
+  const int cpr = a.K / 8;                                      // 16-byte chunks per row
+  const int per_lane = cpr / 64;
+  const int64_t row = (int64_t)(n0 - seg0) + 2 * wave;          // this wave's rows: row, row + 1
+  const bf16x8_t* w0 = (const bf16x8_t*)(wbase + row * a.K) + lane;
+  const bf16x8_t* u0 = (EPI == FASTAV_EPI_SWIGLU) ? (const bf16x8_t*)(a.w2 + row * a.K) + lane : nullptr;
+  bf16x8_t f0[UB], f1[UB], g0[UB], g1[UB];
+  auto load_batch = [&](int c) __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      if (c + u < per_lane) {                                   // uniform
+        f0[u] = w0[(c + u) * 64];
+        f1[u] = w0[(c + u) * 64 + cpr];
+        if (EPI == FASTAV_EPI_SWIGLU) { g0[u] = u0[(c + u) * 64]; g1[u] = u0[(c + u) * 64 + cpr]; }
+      }
+    }
+  };
+  load_batch(0);                                                // in flight across the prologue (its barriers wait on LDS only)
+  if (NORM) {
+    // every thread keeps its quads of the row in registers: the row is read once
+    constexpr int R1 = 4;                                       // K <= 4 * R1 * NT = 8192
+    const int per_row = a.K / 4;
+    f32x4v v[R1];
+    bf16x4_t gv[R1];
+    float ss = 0.f;
+#pragma unroll
+    for (int it = 0; it < R1; ++it) {
+      const int i = tid + it * NT;
+      if (i < per_row) { v[it] = ((const f32x4v*)a.xres)[i]; gv[it] = ((const bf16x4_t*)a.g)[i]; }
+    }
+#pragma unroll
+    for (int it = 0; it < R1; ++it)
+      if (tid + it * NT < per_row) ss += v[it][0] * v[it][0] + v[it][1] * v[it][1] + v[it][2] * v[it][2] + v[it][3] * v[it][3];
+    ss = wave_sum(ss);
+    if (lane == 0) wsum[wave] = ss;
+    lds_barrier();
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) tot += wsum[w];                // fixed order: the same value in every thread
+    const float r = 1.0f / sqrtf(tot / (float)a.K + a.eps);
+#pragma unroll
+    for (int it = 0; it < R1; ++it) {
+      const int i = tid + it * NT;
+      if (i < per_row) {
+        bf16x4_t o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (bf16_t)(v[it][e] * r * (float)gv[it][e]);
+        ((bf16x4_t*)xs)[i] = o;
+      }
+    }
+  } else {
+    for (int i = tid; i < cpr; i += NT) ((bf16x8_t*)xs)[i] = ((const bf16x8_t*)a.x)[i];
+  }
+  lds_barrier();
+
+  float acc0 = 0.f, acc1 = 0.f, acc0u = 0.f, acc1u = 0.f;
+  for (int c = 0; c < per_lane; c += UB) {
+    if (c > 0) load_batch(c);
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      if (c + u < per_lane) {
+        const bf16x8_t xv = ((const bf16x8_t*)xs)[(c + u) * 64 + lane];
+        acc0 = dot8(f0[u], xv, acc0);
+        acc1 = dot8(f1[u], xv, acc1);
+        if (EPI == FASTAV_EPI_SWIGLU) { acc0u = dot8(g0[u], xv, acc0u); acc1u = dot8(g1[u], xv, acc1u); }
+      }
+    }
+  }
+  acc0 = wave_sum(acc0);
+  acc1 = wave_sum(acc1);
+  if (EPI == FASTAV_EPI_SWIGLU) { acc0u = wave_sum(acc0u); acc1u = wave_sum(acc1u); }
+  if (lane != 0) return;
+  const int n = n0 + 2 * wave;
+  if (EPI == FASTAV_EPI_RESADD) {
+    float2* yp = (float2*)((float*)a.y + n);
+    float2 y = *yp;
+    y.x += acc0; y.y += acc1;
+    *yp = y;
+  } else {
+    if (EPI == FASTAV_EPI_SWIGLU) {
+      acc0 = acc0 / (1.0f + __expf(-acc0)) * acc0u;
+      acc1 = acc1 / (1.0f + __expf(-acc1)) * acc1u;
+    }
+    bf16x2_t o;
+    o[0] = (bf16_t)acc0; o[1] = (bf16_t)acc1;
+    *(bf16x2_t*)((bf16_t*)a.y + n) = o;
+  }
+}
+
+bool gemv_rows_supported(int B, int n, int k, bool norm) {
+  return B == 1 && n % 16 == 0 && k % 512 == 0 && k <= 32768 && (!norm || k <= 8192);
+}
+
 bool skinny_linear_supported(int64_t m, int n, int k, int dtype, int64_t ldy) {
   return dtype == FASTAV_BF16 && m >= 1 && m <= 16 && n % 16 == 0 && k % 128 == 0 && ldy % 4 == 0;
 }
@@ -234,16 +357,32 @@ fastav_status_t launch_skinny_linear(const void* x, const void* const* w_seg, co
     a.seg_end[i] = i < n_seg ? end : 0x7FFFFFFF;
   }
   if (end != n) return fail(FASTAV_EINVAL, "skinny linear: segments do not add up to n");
+  if (epilogue == FASTAV_EPI_SWIGLU && (!w2 || ((uintptr_t)w2 % 16)))
+    return fail(FASTAV_EINVAL, "skinny linear: SwiGLU needs a 16-byte aligned up matrix");
   const int kind = epilogue == FASTAV_EPI_SWIGLU ? FASTAV_PROF_LINEAR_SWIGLU
                    : (epilogue == FASTAV_EPI_RESADD ? FASTAV_PROF_LINEAR_RESADD : FASTAV_PROF_LINEAR_STORE);
   // the work figure of a decode GEMV is its weight bytes (HBM-bound), not flops
   ProfScope prof(kind, (double)n * k * 2.0 * (epilogue == FASTAV_EPI_SWIGLU ? 2.0 : 1.0), s);
+  if (gemv_rows_supported(B, n, k, norm_x != nullptr)) {
+    const size_t lds = (size_t)k * 2;
+#define FASTAV_GEMV(EPI, NORM)                                                                                  \
+  do {                                                                                                          \
+    if (lds > 32 * 1024) {                                                                                      \
+      hipError_t e = hipFuncSetAttribute((const void*)k_gemv_rows<EPI, NORM>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024); \
+      if (e != hipSuccess) return fail(FASTAV_EHIP, "gemv: hipFuncSetAttribute: %s", hipGetErrorString(e));     \
+    }                                                                                                           \
+    hipLaunchKernelGGL((k_gemv_rows<EPI, NORM>), dim3((unsigned)(n / 16)), dim3(512), lds, s, a);               \
+  } while (0)
+    if (epilogue == FASTAV_EPI_SWIGLU) { if (norm_x) FASTAV_GEMV(FASTAV_EPI_SWIGLU, true); else FASTAV_GEMV(FASTAV_EPI_SWIGLU, false); }
+    else if (epilogue == FASTAV_EPI_RESADD) FASTAV_GEMV(FASTAV_EPI_RESADD, false);
+    else { if (norm_x) FASTAV_GEMV(FASTAV_EPI_STORE, true); else FASTAV_GEMV(FASTAV_EPI_STORE, false); }
+#undef FASTAV_GEMV
+    return check_launch("gemv_rows");
+  }
   // eight waves split K where its length allows: twice the loads in flight per workgroup (measured faster for
   // every projection of the 7B shape, also the wide gate/up one)
   const bool wide = k % 256 == 0;
   const dim3 grid((unsigned)(n / 16));
-  if (epilogue == FASTAV_EPI_SWIGLU && (!w2 || ((uintptr_t)w2 % 16)))
-    return fail(FASTAV_EINVAL, "skinny linear: SwiGLU needs a 16-byte aligned up matrix");
   const size_t shmem = norm_x ? (size_t)B * k * 2 : 0;
 #define FASTAV_SKINNY(EPI, NORM)                                                                          \
   do {                                                                                                    \
