@@ -51,7 +51,9 @@ bool skinny_norm_supported(int B, int k);
 fastav_status_t launch_skinny_linear(const void* x, const void* const* w_seg, const int* seg_rows, int n_seg,
                                      const void* w2, void* y, int64_t ldy, int B, int n, int k, int epilogue,
                                      hipStream_t s, const float* norm_x = nullptr, const void* norm_g = nullptr,
-                                     float norm_eps = 0.f);
+                                     float norm_eps = 0.f, const int32_t* rope_pos = nullptr, int rope_rows = 0,
+                                     int rope_dh = 0, float rope_base = 0.f);
+bool gemv_rows_fuses_rope(int B, int n, int k, bool norm, int rope_rows, int dh);
 size_t decode_attn_workspace_bytes(int batch, int Hq, int dh, int max_splits);
 fastav_status_t launch_decode_attention(const void* q, const void* k_self, const void* v_self, int64_t q_stride,
                                         const void* k_prefix, const void* v_prefix, const int32_t* cu_prefix,
@@ -706,10 +708,14 @@ fastav_status_t fastav_decode_step(fastav_handle_t h, const fastav_decode_in_t* 
     if (!fuse_norm) FASTAV_TRY(launch_rmsnorm(x, W.g_attn, hn, B, m.hidden, m.rms_eps, m.dtype, s));
     const void* seg[3] = {W.wq, W.wk, W.wv};
     const int rows[3] = {qd, kd, kd};
+    // a single sample: the projection kernel rotates the query and key heads itself (they lead the row)
+    const bool fuse_rope = gemv_rows_fuses_rope(B, qkvd, m.hidden, fuse_norm, qd + kd, m.head_dim);
     FASTAV_TRY(launch_skinny_linear(hn, seg, rows, 3, nullptr, qkv, qkvd, B, qkvd, m.hidden, FASTAV_EPI_STORE, s,
-                                    fuse_norm ? x : nullptr, W.g_attn, m.rms_eps));
+                                    fuse_norm ? x : nullptr, W.g_attn, m.rms_eps, fuse_rope ? in->pos_new : nullptr,
+                                    qd + kd, m.head_dim, m.rope_base));
     // the key heads follow the query heads in the row: one launch rotates both
-    FASTAV_TRY(launch_rope(qkv, qkvd, in->pos_new, B, m.n_q_heads + m.n_kv_heads, m.head_dim, m.rope_base, m.dtype, s));
+    if (!fuse_rope)
+      FASTAV_TRY(launch_rope(qkv, qkvd, in->pos_new, B, m.n_q_heads + m.n_kv_heads, m.head_dim, m.rope_base, m.dtype, s));
     const void* kg = in->k_gen ? in->k_gen[l] : nullptr;
     const void* vg = in->v_gen ? in->v_gen[l] : nullptr;
     // bytes the attention step has to move: the caches once (upper bound: the longest sample for all)

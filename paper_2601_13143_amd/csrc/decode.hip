@@ -45,6 +45,11 @@ struct SkinnyArgs {
   const float* xres;          // [B, K] fp32
   const bf16_t* g;            // [K] gain
   float eps;
+  // ROPE kernels (one-row GEMV, store epilogue): output features below rope_rows are heads of dh features each,
+  // rotated at position pos[0] (rotate-half pairs (i, i + dh/2), angle pos * base^(-2i/dh)) before they are stored
+  const int32_t* pos;
+  int rope_rows, dh;
+  double rope_coef;           // -log2(base) * 2 / dh
 };
 
 template <int EPI, int NW, bool NORM>
@@ -218,24 +223,34 @@ __device__ __forceinline__ float dot8(bf16x8_t w, bf16x8_t x, float acc) {
   return acc;
 }
 
-template <int EPI, bool NORM>
+template <int EPI, bool NORM, bool ROPE>
 __global__ __launch_bounds__(512) void k_gemv_rows(SkinnyArgs a) {
   constexpr int NW = 8, NT = 64 * NW;
-  constexpr int UB = (EPI == FASTAV_EPI_SWIGLU) ? 4 : 8;        // chunks per row and batch: 16 loads in flight per lane
+  constexpr int UB = 4;                                         // chunks per row and batch: 8 or 16 (SwiGLU) loads in flight per lane
   extern __shared__ __attribute__((aligned(16))) bf16_t xs[];   // [K] the input row
   __shared__ float wsum[NW];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n0 = blockIdx.x * 16;
+  // this wave's two output features: neighbours, or - where the rotation is fused - the pair (i, i + dh/2) of a
+  // head, so that the wave holds both halves of the rotation (a workgroup then covers 8 + 8 features of one head)
+  const bool rot = ROPE && n0 < a.rope_rows;
+  int n_lo = n0 + 2 * wave, dn = 1;
+  if (rot) {
+    const int wph = a.dh / 16;                                  // workgroups per head
+    n_lo = (blockIdx.x / wph) * a.dh + (blockIdx.x % wph) * 8 + wave;
+    dn = a.dh / 2;
+  }
   const bf16_t* wbase = a.w[0];
   int seg0 = 0;
-  if (EPI != FASTAV_EPI_SWIGLU) {
-    if (n0 >= a.seg_end[0]) { wbase = a.w[1]; seg0 = a.seg_end[0]; }
-    if (n0 >= a.seg_end[1]) { wbase = a.w[2]; seg0 = a.seg_end[1]; }
+  if (EPI != FASTAV_EPI_SWIGLU) {                               // both features lie in one segment (whole heads)
+    if (n_lo >= a.seg_end[0]) { wbase = a.w[1]; seg0 = a.seg_end[0]; }
+    if (n_lo >= a.seg_end[1]) { wbase = a.w[2]; seg0 = a.seg_end[1]; }
   }
   const int cpr = a.K / 8;                                      // 16-byte chunks per row
   const int per_lane = cpr / 64;
-  const int64_t row = (int64_t)(n0 - seg0) + 2 * wave;          // this wave's rows: row, row + 1
+  const int64_t row = (int64_t)(n_lo - seg0);                   // this wave's rows: row, row + dn
+  const int64_t cdn = (int64_t)dn * cpr;
   const bf16x8_t* w0 = (const bf16x8_t*)(wbase + row * a.K) + lane;
   const bf16x8_t* u0 = (EPI == FASTAV_EPI_SWIGLU) ? (const bf16x8_t*)(a.w2 + row * a.K) + lane : nullptr;
   bf16x8_t f0[UB], f1[UB], g0[UB], g1[UB];
@@ -244,12 +259,19 @@ __global__ __launch_bounds__(512) void k_gemv_rows(SkinnyArgs a) {
     for (int u = 0; u < UB; ++u) {
       if (c + u < per_lane) {                                   // uniform
         f0[u] = w0[(c + u) * 64];
-        f1[u] = w0[(c + u) * 64 + cpr];
-        if (EPI == FASTAV_EPI_SWIGLU) { g0[u] = u0[(c + u) * 64]; g1[u] = u0[(c + u) * 64 + cpr]; }
+        f1[u] = w0[(c + u) * 64 + cdn];
+        if (EPI == FASTAV_EPI_SWIGLU) { g0[u] = u0[(c + u) * 64]; g1[u] = u0[(c + u) * 64 + cdn]; }
       }
     }
   };
   load_batch(0);                                                // in flight across the prologue (its barriers wait on LDS only)
+  float rc = 1.f, rs_ = 0.f;
+  if (rot) {                                                    // angle in fp64, as the stand-alone rotation evaluates it
+    const double ang = (double)a.pos[0] * exp2((double)(n_lo % a.dh) * a.rope_coef);
+    double sd, cd;
+    sincos(ang, &sd, &cd);
+    rc = (float)cd; rs_ = (float)sd;
+  }
   if (NORM) {
     // every thread keeps its quads of the row in registers: the row is read once
     constexpr int R1 = 4;                                       // K <= 4 * R1 * NT = 8192
@@ -304,12 +326,14 @@ __global__ __launch_bounds__(512) void k_gemv_rows(SkinnyArgs a) {
   acc1 = wave_sum(acc1);
   if (EPI == FASTAV_EPI_SWIGLU) { acc0u = wave_sum(acc0u); acc1u = wave_sum(acc1u); }
   if (lane != 0) return;
-  const int n = n0 + 2 * wave;
   if (EPI == FASTAV_EPI_RESADD) {
-    float2* yp = (float2*)((float*)a.y + n);
+    float2* yp = (float2*)((float*)a.y + n_lo);
     float2 y = *yp;
     y.x += acc0; y.y += acc1;
     *yp = y;
+  } else if (rot) {
+    ((bf16_t*)a.y)[n_lo] = (bf16_t)(acc0 * rc - acc1 * rs_);
+    ((bf16_t*)a.y)[n_lo + dn] = (bf16_t)(acc1 * rc + acc0 * rs_);
   } else {
     if (EPI == FASTAV_EPI_SWIGLU) {
       acc0 = acc0 / (1.0f + __expf(-acc0)) * acc0u;
@@ -317,12 +341,16 @@ __global__ __launch_bounds__(512) void k_gemv_rows(SkinnyArgs a) {
     }
     bf16x2_t o;
     o[0] = (bf16_t)acc0; o[1] = (bf16_t)acc1;
-    *(bf16x2_t*)((bf16_t*)a.y + n) = o;
+    *(bf16x2_t*)((bf16_t*)a.y + n_lo) = o;
   }
 }
 
 bool gemv_rows_supported(int B, int n, int k, bool norm) {
   return B == 1 && n % 16 == 0 && k % 512 == 0 && k <= 32768 && (!norm || k <= 8192);
+}
+// The one-row GEMV can rotate the heads it produces (see SkinnyArgs): the caller then skips the rope launch.
+bool gemv_rows_fuses_rope(int B, int n, int k, bool norm, int rope_rows, int dh) {
+  return gemv_rows_supported(B, n, k, norm) && dh % 16 == 0 && rope_rows % dh == 0 && rope_rows <= n;
 }
 
 bool skinny_linear_supported(int64_t m, int n, int k, int dtype, int64_t ldy) {
@@ -335,8 +363,11 @@ bool skinny_norm_supported(int B, int k) { return (int64_t)B * k <= 32768; }
 
 fastav_status_t launch_skinny_linear(const void* x, const void* const* w_seg, const int* seg_rows, int n_seg,
                                      const void* w2, void* y, int64_t ldy, int B, int n, int k, int epilogue,
-                                     hipStream_t s, const float* norm_x, const void* norm_g, float norm_eps) {
+                                     hipStream_t s, const float* norm_x, const void* norm_g, float norm_eps,
+                                     const int32_t* rope_pos, int rope_rows, int rope_dh, float rope_base) {
   if (B == 0 || n == 0) return FASTAV_OK;
+  if (rope_pos && (epilogue != FASTAV_EPI_STORE || !gemv_rows_fuses_rope(B, n, k, norm_x != nullptr, rope_rows, rope_dh)))
+    return fail(FASTAV_EINVAL, "skinny linear: the fused rotation needs the one-row store kernel and whole heads");
   if (!skinny_linear_supported(B, n, k, FASTAV_BF16, ldy)) return fail(FASTAV_EUNSUPPORTED, "skinny linear: unsupported shape");
   if (((uintptr_t)x | (uintptr_t)y | (uintptr_t)norm_x | (uintptr_t)norm_g) % 16)
     return fail(FASTAV_EINVAL, "skinny linear: x, y and the norm inputs must be 16-byte aligned");
@@ -344,6 +375,8 @@ fastav_status_t launch_skinny_linear(const void* x, const void* const* w_seg, co
     return fail(FASTAV_EINVAL, "skinny linear: bad fused-norm arguments");
   SkinnyArgs a;
   a.xres = norm_x; a.g = (const bf16_t*)norm_g; a.eps = norm_eps;
+  a.pos = rope_pos; a.rope_rows = rope_pos ? rope_rows : 0; a.dh = rope_pos ? rope_dh : 16;
+  a.rope_coef = rope_pos ? -log2((double)rope_base) * 2.0 / (double)rope_dh : 0.0;
   a.x = (const bf16_t*)x; a.w2 = (const bf16_t*)w2; a.y = y; a.ldy = ldy; a.B = B; a.N = n; a.K = k;
   int end = 0;
   for (int i = 0; i < 3; ++i) {
@@ -365,17 +398,18 @@ fastav_status_t launch_skinny_linear(const void* x, const void* const* w_seg, co
   ProfScope prof(kind, (double)n * k * 2.0 * (epilogue == FASTAV_EPI_SWIGLU ? 2.0 : 1.0), s);
   if (gemv_rows_supported(B, n, k, norm_x != nullptr)) {
     const size_t lds = (size_t)k * 2;
-#define FASTAV_GEMV(EPI, NORM)                                                                                  \
+#define FASTAV_GEMV(EPI, NORM, ROPE)                                                                            \
   do {                                                                                                          \
     if (lds > 32 * 1024) {                                                                                      \
-      hipError_t e = hipFuncSetAttribute((const void*)k_gemv_rows<EPI, NORM>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024); \
+      hipError_t e = hipFuncSetAttribute((const void*)k_gemv_rows<EPI, NORM, ROPE>, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024); \
       if (e != hipSuccess) return fail(FASTAV_EHIP, "gemv: hipFuncSetAttribute: %s", hipGetErrorString(e));     \
     }                                                                                                           \
-    hipLaunchKernelGGL((k_gemv_rows<EPI, NORM>), dim3((unsigned)(n / 16)), dim3(512), lds, s, a);               \
+    hipLaunchKernelGGL((k_gemv_rows<EPI, NORM, ROPE>), dim3((unsigned)(n / 16)), dim3(512), lds, s, a);         \
   } while (0)
-    if (epilogue == FASTAV_EPI_SWIGLU) { if (norm_x) FASTAV_GEMV(FASTAV_EPI_SWIGLU, true); else FASTAV_GEMV(FASTAV_EPI_SWIGLU, false); }
-    else if (epilogue == FASTAV_EPI_RESADD) FASTAV_GEMV(FASTAV_EPI_RESADD, false);
-    else { if (norm_x) FASTAV_GEMV(FASTAV_EPI_STORE, true); else FASTAV_GEMV(FASTAV_EPI_STORE, false); }
+    if (epilogue == FASTAV_EPI_SWIGLU) { if (norm_x) FASTAV_GEMV(FASTAV_EPI_SWIGLU, true, false); else FASTAV_GEMV(FASTAV_EPI_SWIGLU, false, false); }
+    else if (epilogue == FASTAV_EPI_RESADD) FASTAV_GEMV(FASTAV_EPI_RESADD, false, false);
+    else if (rope_pos) { if (norm_x) FASTAV_GEMV(FASTAV_EPI_STORE, true, true); else FASTAV_GEMV(FASTAV_EPI_STORE, false, true); }
+    else { if (norm_x) FASTAV_GEMV(FASTAV_EPI_STORE, true, false); else FASTAV_GEMV(FASTAV_EPI_STORE, false, false); }
 #undef FASTAV_GEMV
     return check_launch("gemv_rows");
   }
