@@ -34,9 +34,12 @@ def _skinny_case(B, N, K, epi, seed):
 
 
 @pytest.mark.parametrize("epi", [fa.EPI_STORE, fa.EPI_RESADD, fa.EPI_SWIGLU])
-@pytest.mark.parametrize("B,N,K", [(1, 256, 128), (3, 4096, 512), (8, 6144, 4096), (16, 1024, 14336), (5, 3584, 3584)])
+@pytest.mark.parametrize("B,N,K", [(1, 256, 128), (3, 4096, 512), (8, 6144, 4096), (16, 1024, 14336), (5, 3584, 3584),
+                                   (1, 4096, 3584), (1, 1024, 18944), (1, 272, 512), (1, 4096, 4096), (2, 512, 4096)])
 def test_decode_linear_few_rows(B, N, K, epi):
-    """Linear layers of a decode step: 1-16 rows against weight matrices of the model's shapes."""
+    """Linear layers of a decode step: 1-16 rows against weight matrices of the model's shapes.  A single row with
+    K a multiple of 512 takes the one-row kernel (7, 37, 1 and 8 chunks per lane: whole and ragged batches of loads),
+    everything else the matrix-core one."""
     got, want = _skinny_case(B, N, K, epi, B + N + K + epi)
     assert_close(got, want, "bf16", what=f"skinny linear {B}x{N}x{K} epi {epi}")
 
@@ -173,10 +176,12 @@ def test_decode_step_7b_layer_shape():
     assert_close(host(r["x_out"]), want, "bf16", scale=float(np.sqrt(np.mean(want ** 2))), what="7B-shape decode step")
 
 
-@pytest.mark.parametrize("hq,hkv,dh,batch", [(28, 4, 128, 3), (8, 8, 64, 16), (16, 2, 64, 5)])
+@pytest.mark.parametrize("hq,hkv,dh,batch", [(28, 4, 128, 3), (8, 8, 64, 16), (16, 2, 64, 5), (28, 4, 128, 1), (16, 16, 64, 1),
+                                             (16, 2, 64, 1)])
 def test_decode_step_head_layouts(hq, hkv, dh, batch):
-    """Seven and eight query heads per KV head (two head passes), one query head per KV head, head_dim 64,
-    a full batch of 16: ragged unpruned caches written by the oracle, two layers."""
+    """Seven and eight query heads per KV head, one query head per KV head, head_dim 64, a full batch of 16, and
+    single samples (the one-row projections with the rotation folded in): ragged caches written by the oracle,
+    two layers."""
     m = fi.Model(2, hq * dh // 2 if hq * dh >= 1024 else 512, hq, hkv, dh, 1024, 1.0e4, 1e-6, "bf16")
     rng = np.random.default_rng(hq + batch)
     lens1 = rng.integers(70, 330, size=batch)
