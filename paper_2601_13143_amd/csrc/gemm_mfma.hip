@@ -51,6 +51,15 @@ constexpr int kEpiResAtomic = 101; // internal epilogue: residual update through
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_byte_addr) {
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_byte_addr) : "memory");
 }
+// The same with the address split into a wave-uniform base (SGPR pair) and a 32-bit lane offset: no vector
+// arithmetic per copy.
+__device__ __forceinline__ void dma16_sbase(const void* base, uint32_t voff, uint32_t lds_byte_addr) {
+  // the base is wave-uniform by contract; say so, or the register allocator may leave it in VGPRs
+  const uint64_t u = (uint64_t)(uintptr_t)base;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+  const void* sbase = (const void*)(uintptr_t)(((uint64_t)hi << 32) | lo);
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(sbase), "s"(lds_byte_addr) : "memory");
+}
 template <int N> __device__ __forceinline__ void dma_wait_keep() {   // until at most N copies are in flight
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
@@ -110,47 +119,47 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 4 && NST == 3) ? 2 : 1) v
     if (n0 >= g.seg_end[0]) { wbase = g.W[1]; seg_start = g.seg_end[0]; }
     if (n0 >= g.seg_end[1]) { wbase = g.W[2]; seg_start = g.seg_end[1]; }
   }
-  auto b_row_ptr = [&](int brow) -> const bf16_t* {
-    if (EPI == FASTAV_EPI_SWIGLU) {
-      const int blk = brow >> 5;
-      const bf16_t* wsel = (blk & 1) ? g.W2 : g.W[0];
-      return wsel + (int64_t)(n0 + (blk >> 1) * 32 + (brow & 31)) * K + kt0 * 32;
-    }
-    return wbase + (int64_t)(n0 - seg_start + brow) * K + kt0 * 32;
-  };
-  auto a_row_ptr = [&](int arow) -> const bf16_t* {
-    int row = m0 + arow;
-    row = row < g.M ? row : g.M - 1;                    // clamp: stay inside A, the epilogue masks the row
-    return g.A + (int64_t)row * K + kt0 * 32;
-  };
 
-  // ---- this wave's copies: instruction i covers tile rows [(i*NW + wave)*16, +16)
+  // ---- this wave's copies: instruction i covers tile rows [(i*NW + wave)*16, +16).  The vector ALU also issues
+  // the matrix instructions, so the main loop is written to need none: a copy's address is a wave-uniform base in
+  // SGPRs (advanced along K with scalar adds) plus one constant 32-bit lane offset, and an operand fragment's LDS
+  // address is one constant lane offset plus an immediate (the ring slot is a compile-time constant: the stage
+  // loop is unrolled over the ring).
   const int drow = lane >> 2, dpos = lane & 3;          // row inside the 16-row group, 16-byte slot inside the row
-  const bf16_t* a_src[A_D];
-  const bf16_t* b_src[B_D];
+  const bf16_t* a_sb = g.A + (int64_t)m0 * K + kt0 * 32;
+  const bf16_t* b_sb[B_D];
+  uint32_t a_vo[A_D], b_vo[B_D];                        // lane offsets in bytes (at most 255 rows of K elements)
   uint32_t a_dst[A_D], b_dst[B_D];                      // LDS byte address of the 16-row group in stage 0
   const uint32_t a_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)A4;
   const uint32_t b_base = a_base + (uint32_t)NST * BM * 64u;
 #pragma unroll
   for (int i = 0; i < A_D; ++i) {
     const int r0 = (i * NW + wave_u) * 16, row = r0 + drow;
-    a_src[i] = a_row_ptr(row) + ((dpos ^ ((row >> 2) & 3)) * 8);
+    int grow = m0 + row;
+    grow = grow < g.M ? grow : g.M - 1;                 // clamp: stay inside A, the epilogue masks the row
+    a_vo[i] = (uint32_t)(((int64_t)(grow - m0) * K + (dpos ^ ((row >> 2) & 3)) * 8) * 2);
     a_dst[i] = a_base + (uint32_t)r0 * 64u;
   }
 #pragma unroll
   for (int i = 0; i < B_D; ++i) {
     const int r0 = (i * NW + wave_u) * 16, row = r0 + drow;
-    b_src[i] = b_row_ptr(row) + ((dpos ^ ((row >> 2) & 3)) * 8);
+    if (EPI == FASTAV_EPI_SWIGLU) {
+      const int blk = r0 >> 5;                          // the 16 rows of a copy lie inside one 32-row block
+      b_sb[i] = ((blk & 1) ? g.W2 : g.W[0]) + (int64_t)(n0 + (blk >> 1) * 32) * K + kt0 * 32;
+      b_vo[i] = (uint32_t)(((int64_t)(row & 31) * K + (dpos ^ ((row >> 2) & 3)) * 8) * 2);
+    } else {
+      b_sb[i] = wbase + (int64_t)(n0 - seg_start) * K + kt0 * 32;
+      b_vo[i] = (uint32_t)(((int64_t)row * K + (dpos ^ ((row >> 2) & 3)) * 8) * 2);
+    }
     b_dst[i] = b_base + (uint32_t)r0 * 64u;
   }
-  // copy number c (0 .. D-1: A's first) of stage t.  Past the last stage the copy is re-aimed at the last
-  // stage (into a ring slot nobody reads any more): a branch-free loop body matters more than the few
+  // copy number c (0 .. D-1: A's first) of stage t into ring slot dslot.  Past the last stage the copy is re-aimed
+  // at the last stage (into a ring slot nobody reads any more): a branch-free loop body matters more than the few
   // redundant copies per workgroup.
-  auto dma_one = [&](int t, int c) {
+  auto dma_one = [&](int t, int c, uint32_t dslot) __attribute__((always_inline)) {
     const int koff = (t < KT ? t : KT - 1) * 32;
-    const uint32_t slot = (uint32_t)t % (uint32_t)NST;
-    if (c < A_D) dma16(a_src[c < A_D ? c : 0] + koff, a_dst[c < A_D ? c : 0] + slot * (BM * 64u));
-    else dma16(b_src[c >= A_D ? c - A_D : 0] + koff, b_dst[c >= A_D ? c - A_D : 0] + slot * (BN * 64u));
+    if (c < A_D) dma16_sbase(a_sb + koff, a_vo[c < A_D ? c : 0], a_dst[c < A_D ? c : 0] + dslot * (BM * 64u));
+    else dma16_sbase(b_sb[c >= A_D ? c - A_D : 0] + koff, b_vo[c >= A_D ? c - A_D : 0], b_dst[c >= A_D ? c - A_D : 0] + dslot * (BN * 64u));
   };
 
   f32x16_t acc[TM][TN];
@@ -163,47 +172,64 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 4 && NST == 3) ? 2 : 1) v
 
   const int frow = lane & 31, fch = lane >> 5;          // operand fragment: row in block, which 8-wide k chunk
   bf16x8_t af[2][TM], bfr[2][TN];                       // operand fragments of two k-slices
-  auto frags = [&](int buf, int slot, int kk) {
-    const bf16x8_t* Asb = A4 + slot * BM * 4;
-    const bf16x8_t* Bsb = B4 + slot * BN * 4;
+  // this lane's fragment positions inside a ring slot (16-byte units) for the two k-halves of a stage; block i of
+  // the wave tile adds 32 rows = 128 units (the swizzle term depends on row bits 2-3 only)
+  int a_fu[2], b_fu[2];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) af[buf][i] = Asb[swz4(wm * WTM + i * 32 + frow, kk * 2 + fch)];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) bfr[buf][j] = Bsb[swz4(wn * WTN + j * 32 + frow, kk * 2 + fch)];
-  };
-  // One k-slice: NMF MFMAs in D/2 groups, one copy of stage t_copy fenced in after each group.
-  auto slice = [&](int buf, int t_copy, int c0) {
+  for (int kk = 0; kk < 2; ++kk) {
+    a_fu[kk] = swz4(wm * WTM + frow, kk * 2 + fch);
+    b_fu[kk] = NST * BM * 4 + swz4(wn * WTN + frow, kk * 2 + fch);
+  }
+  // One k-slice: NMF MFMAs in D/2 groups, one copy of stage t_copy fenced in after each group.  The operand
+  // fragments of the NEXT k-slice (ring slot nslot, half nkk) are read into the other register buffer one at a
+  // time, each right after an MFMA of this slice: the LDS reads are spread evenly over the slice instead of
+  // arriving in a burst, and a wave never stands between its reads and its first MFMA.
+  auto slice = [&](int buf, int t_copy, int c0, uint32_t dslot, uint32_t nslot, int nkk) __attribute__((always_inline)) {
 #pragma unroll
     for (int grp = 0; grp < D / 2; ++grp) {
 #pragma unroll
       for (int q = grp * NMF / (D / 2); q < (grp + 1) * NMF / (D / 2); ++q) {     // MFMAs between two copies
         const int i = q / TN, j = q % TN;
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
+        if (q < TM) af[buf ^ 1][q] = lds[a_fu[nkk] + (int)nslot * BM * 4 + q * 128];
+        else if (q < TM + TN) bfr[buf ^ 1][q - TM] = lds[b_fu[nkk] + (int)nslot * BN * 4 + (q - TM) * 128];
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // one MFMA ...
+        if (q < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // ... then one LDS read
       }
       __builtin_amdgcn_sched_barrier(0);
-      dma_one(t_copy, c0 + grp);
+      dma_one(t_copy, c0 + grp, dslot);
       __builtin_amdgcn_sched_barrier(0);
     }
+  };
+  static_assert(NMF >= TM + TN, "a slice has fewer MFMAs than the next slice has fragments");
+  // stage t lives in ring slot `slot`; the copies issued meanwhile (stage t+NST-1) go to the slot before it
+  auto stage = [&](int t, uint32_t slot) __attribute__((always_inline)) {
+    const uint32_t dslot = (slot + NST - 1) % NST, nslot = (slot + 1) % NST;
+    // the ring slot of stage t+NST-1 held stage t-1, which nobody reads after the previous barrier
+    slice(0, t + NST - 1, 0, dslot, slot, 1);
+    dma_wait_keep<(NST - 3) * D + D / 2>();              // stage t+1 has landed (this wave's share)
+    __syncthreads();
+    slice(1, t + NST - 1, D / 2, dslot, nslot, 0);       // (after the last stage: a harmless read of an idle slot)
   };
 
   // ---- prologue: NST-1 stages in flight, the first one landed and published
 #pragma unroll
   for (int t = 0; t < NST - 1; ++t)
 #pragma unroll
-    for (int c = 0; c < D; ++c) dma_one(t, c);
+    for (int c = 0; c < D; ++c) dma_one(t, c, (uint32_t)t);
   dma_wait_keep<(NST - 2) * D>();
   __syncthreads();
-  frags(0, 0, 0);
+#pragma unroll
+  for (int i = 0; i < TM; ++i) af[0][i] = lds[a_fu[0] + i * 128];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) bfr[0][j] = lds[b_fu[0] + j * 128];
 
-  for (int t = 0; t < KT; ++t) {
-    // the ring slot of stage t+NST-1 held stage t-1, which nobody reads after the previous barrier
-    frags(1, (uint32_t)t % (uint32_t)NST, 1);
-    slice(0, t + NST - 1, 0);
-    dma_wait_keep<(NST - 3) * D + D / 2>();              // stage t+1 has landed (this wave's share)
-    __syncthreads();
-    frags(0, (uint32_t)(t + 1) % (uint32_t)NST, 0);                          // (after the last stage: a harmless read of an idle slot)
-    slice(1, t + NST - 1, D / 2);
+  int t = 0;
+  for (; t + NST <= KT; t += NST) {                      // t is a multiple of NST here: slots are literals
+#pragma unroll
+    for (int u = 0; u < NST; ++u) stage(t + u, (uint32_t)u);
   }
+  for (; t < KT; ++t) stage(t, (uint32_t)t % (uint32_t)NST);
   dma_wait_keep<0>();
 
   // ---- epilogue.  Accumulator register r of a 32x32 block: column = lane % 32,

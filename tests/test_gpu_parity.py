@@ -165,7 +165,8 @@ LINEAR_SHAPES = [("f32", 100, 688, 256), ("f32", 37, 256, 688), ("bf16", 100, 20
                  ("bf16", 2100, 6144, 256), ("bf16", 4000, 2048, 192),
                  ("bf16", 1205, 4096, 2048),      # < 1 round of big tiles: split-K for the residual epilogue
                  ("bf16", 2458, 2048, 1536),      # 80 big tiles -> split 3
-                 ("bf16", 3000, 8192, 256),       # 384 big tiles = 1.5 rounds: big tiles + small-tile tail columns
+                 ("bf16", 3000, 8192, 256),       # 384 big tiles = 1.5 rounds
+                 ("bf16", 2458, 4608, 192),       # SwiGLU: 360 big tiles = 1.4 rounds
                  ("bf16", 1721, 2816, 320),       # 77 tiles; SwiGLU has 154
                  ("bf16", 8200, 4096, 256)]       # 33 x 16 = 528 big tiles: several rounds (hardware-add residual epilogue)
 
