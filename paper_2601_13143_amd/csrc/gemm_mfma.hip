@@ -66,6 +66,52 @@ template <int N> __device__ __forceinline__ void dma_wait_keep() {   // until at
 
 __device__ __forceinline__ int swz4(int row, int chunk) { return row * 4 + (chunk ^ ((row >> 2) & 3)); }   // 16-byte units
 
+// Epilogue shared by the GEMM kernels.  Accumulator register r of a 32x32 block: column = lane % 32,
+// row = (r / 4) * 8 + (lane / 32) * 4 + r % 4.
+template <int EPI, int TM, int TN, int WTM, int WTN>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, f32x16_t (&acc)[TM][TN], int m0, int n0, int wm, int wn, int lane) {
+  const int ecol = lane & 31, erow0 = (lane >> 5) * 4;
+  if (EPI == FASTAV_EPI_SWIGLU) {
+    bf16_t* C = (bf16_t*)g.C;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; j += 2) {
+        const int col = n0 + (wn * TN / 2 + j / 2) * 32 + ecol;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = m0 + wm * WTM + i * 32 + (r >> 2) * 8 + erow0 + (r & 3);
+          if (row < g.M) {
+            const float gt = acc[i][j][r], up = acc[i][j + 1][r];
+            C[(int64_t)row * g.ldc + col] = (bf16_t)(gt / (1.0f + __expf(-gt)) * up);
+          }
+        }
+      }
+  } else {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int col = n0 + wn * WTN + j * 32 + ecol;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = m0 + wm * WTM + i * 32 + (r >> 2) * 8 + erow0 + (r & 3);
+          if (row < g.M) {
+            if (EPI == FASTAV_EPI_STORE) ((bf16_t*)g.C)[(int64_t)row * g.ldc + col] = (bf16_t)acc[i][j][r];
+            else if (EPI == kEpiPartial) g.partial[((int64_t)blockIdx.y * g.M + row) * g.N + col] = acc[i][j][r];
+            else if (EPI == kEpiResAtomic) {
+              // Residual update as a fire-and-forget hardware add at the L2: no read round trip holds the
+              // wave, so the next tile's main loop on this CU overlaps the drain.  Each element receives
+              // exactly one addend per launch, so the result is that of a read-modify-write.
+              unsafeAtomicAdd(&((float*)g.C)[(int64_t)row * g.ldc + col], acc[i][j][r]);
+            }
+            else ((float*)g.C)[(int64_t)row * g.ldc + col] += acc[i][j][r];
+          }
+        }
+      }
+  }
+}
+
 // NST = LDS ring depth in stages of 32 k (copies run NST-1 stages ahead).  A 256 x 128 tile with 4 waves and
 // NST = 3 lets two workgroups share a CU (one computes while the other sits in its prologue, epilogue or at a
 // barrier); it measured 15 % slower than one 8-wave 256 x 256 workgroup with NST = 4 on every shape of the 7B
@@ -232,48 +278,190 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 4 && NST == 3) ? 2 : 1) v
   for (; t < KT; ++t) stage(t, (uint32_t)t % (uint32_t)NST);
   dma_wait_keep<0>();
 
-  // ---- epilogue.  Accumulator register r of a 32x32 block: column = lane % 32,
-  //      row = (r / 4) * 8 + (lane / 32) * 4 + r % 4.
-  const int ecol = lane & 31, erow0 = (lane >> 5) * 4;
-  if (EPI == FASTAV_EPI_SWIGLU) {
-    bf16_t* C = (bf16_t*)g.C;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; j += 2) {
-        const int col = n0 + (wn * TN / 2 + j / 2) * 32 + ecol;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = m0 + wm * WTM + i * 32 + (r >> 2) * 8 + erow0 + (r & 3);
-          if (row < g.M) {
-            const float gt = acc[i][j][r], up = acc[i][j + 1][r];
-            C[(int64_t)row * g.ldc + col] = (bf16_t)(gt / (1.0f + __expf(-gt)) * up);
-          }
-        }
-      }
-  } else {
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wn * WTN + j * 32 + ecol;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = m0 + wm * WTM + i * 32 + (r >> 2) * 8 + erow0 + (r & 3);
-          if (row < g.M) {
-            if (EPI == FASTAV_EPI_STORE) ((bf16_t*)g.C)[(int64_t)row * g.ldc + col] = (bf16_t)acc[i][j][r];
-            else if (EPI == kEpiPartial) g.partial[((int64_t)blockIdx.y * g.M + row) * g.N + col] = acc[i][j][r];
-            else if (EPI == kEpiResAtomic) {
-              // Residual update as a fire-and-forget hardware add at the L2: no read round trip holds the
-              // wave, so the next tile's main loop on this CU overlaps the drain.  Each element receives
-              // exactly one addend per launch, so the result is that of a read-modify-write.
-              unsafeAtomicAdd(&((float*)g.C)[(int64_t)row * g.ldc + col], acc[i][j][r]);
-            }
-            else ((float*)g.C)[(int64_t)row * g.ldc + col] += acc[i][j][r];
-          }
-        }
-      }
+  gemm_epilogue<EPI, TM, TN, WTM, WTN>(g, acc, m0, n0, wm, wn, lane);
+}
+
+// The same GEMM with stages of 64 k in a double buffer.  What changes is the shape of a copy: a wave instruction
+// now reads 8 rows x 128 contiguous bytes (whole L2 lines) instead of 16 rows x 64, half as many address segments
+// per byte - the vector-memory path, not the matrix cores, is what the 32-k kernel runs out of first.  A stage is
+// (BM + BN) x 128 bytes, so only two fit in LDS; the copies of stage t+2 start as soon as the last fragments of
+// stage t have been read (one barrier per stage, placed before the stage's last k-slice) and have a full stage of
+// matrix work to land.  LDS row = 8 chunks of 16 bytes, chunk c of row r stored at position c ^ ((r >> 1) & 7):
+// the 16 lanes of a fragment read then hit 16 different bank groups.
+__device__ __forceinline__ int swz8(int row, int chunk) { return row * 8 + (chunk ^ ((row >> 1) & 7)); }   // 16-byte units
+
+template <int BM, int BN, int WM, int WN, int EPI>
+__global__ __launch_bounds__(WM * WN * 64, 1) void k_gemm_mfma_k64(GemmArgs g) {
+  constexpr int NW = WM * WN;                          // waves
+  constexpr int WTM = BM / WM, WTN = BN / WN;          // wave tile
+  constexpr int TM = WTM / 32, TN = WTN / 32;          // 32x32 blocks per wave
+  constexpr int A_D = BM / (8 * NW), B_D = BN / (8 * NW);     // copy instructions per wave and stage (8 rows each)
+  constexpr int D = A_D + B_D;
+  constexpr int NMF = TM * TN;                         // MFMAs per k-slice
+  constexpr int KS = 4;                                // k-slices of 16 per stage
+  constexpr int OUT_BN = (EPI == FASTAV_EPI_SWIGLU) ? BN / 2 : BN;
+  static_assert(A_D >= 1 && B_D >= 1 && D % 2 == 0 && NMF >= D / 2 && NMF >= TM + TN && TN % 2 == 0, "tile shape");
+  extern __shared__ bf16x8_t lds[];                    // [2][BM*8] A, then [2][BN*8] B
+
+  // ---- tile assignment (as in k_gemm_mfma)
+  const int nblk = g.tiles_m * g.tiles_n;
+  int pid = blockIdx.x;
+  {
+    const int per = nblk / 8, rem = nblk % 8, xcd = pid % 8, idx = pid / 8;
+    pid = xcd * per + (xcd < rem ? xcd : rem) + idx;
   }
+  const int kb = g.band;
+  const int band = pid / (kb * g.tiles_m);
+  const int bw = (g.tiles_n - band * kb < kb) ? g.tiles_n - band * kb : kb;   // columns in this band
+  const int inb = pid - band * kb * g.tiles_m;
+  const int tile_m = inb / bw, tile_n = band * kb + inb % bw;
+  const int m0 = tile_m * BM;
+  const int n0 = g.n_off + tile_n * OUT_BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int wm = wave / WN, wn = wave % WN;
+  const int K = g.K;
+  // stages of 64 k owned by this workgroup (all of them unless split-K)
+  const int kt_all = K / 64;
+  const int kt0 = (int)((int64_t)kt_all * blockIdx.y / g.splits);
+  const int KT = (int)((int64_t)kt_all * (blockIdx.y + 1) / g.splits) - kt0;
+
+  const bf16_t* wbase = g.W[0];
+  int seg_start = 0;
+  if (EPI != FASTAV_EPI_SWIGLU) {
+    if (n0 >= g.seg_end[0]) { wbase = g.W[1]; seg_start = g.seg_end[0]; }
+    if (n0 >= g.seg_end[1]) { wbase = g.W[2]; seg_start = g.seg_end[1]; }
+  }
+
+  // ---- this wave's copies: instruction i covers tile rows [(i*NW + wave)*8, +8), lane = (row, 16-byte chunk)
+  const int drow = lane >> 3, dpos = lane & 7;
+  const bf16_t* a_sb = g.A + (int64_t)m0 * K + kt0 * 64;
+  const bf16_t* b_sb[B_D];
+  uint32_t a_vo[A_D], b_vo[B_D];                        // lane offsets in bytes
+  uint32_t a_dst[A_D], b_dst[B_D];                      // LDS byte address of the 8-row group in slot 0
+  const uint32_t a_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
+  const uint32_t b_base = a_base + 2u * BM * 128u;
+#pragma unroll
+  for (int i = 0; i < A_D; ++i) {
+    const int r0 = (i * NW + wave_u) * 8, row = r0 + drow;
+    int grow = m0 + row;
+    grow = grow < g.M ? grow : g.M - 1;                 // clamp: stay inside A, the epilogue masks the row
+    a_vo[i] = (uint32_t)(((int64_t)(grow - m0) * K + (dpos ^ ((row >> 1) & 7)) * 8) * 2);
+    a_dst[i] = a_base + (uint32_t)r0 * 128u;
+  }
+#pragma unroll
+  for (int i = 0; i < B_D; ++i) {
+    const int r0 = (i * NW + wave_u) * 8, row = r0 + drow;
+    if (EPI == FASTAV_EPI_SWIGLU) {
+      const int blk = r0 >> 5;                          // the 8 rows of a copy lie inside one 32-row block
+      b_sb[i] = ((blk & 1) ? g.W2 : g.W[0]) + (int64_t)(n0 + (blk >> 1) * 32) * K + kt0 * 64;
+      b_vo[i] = (uint32_t)(((int64_t)(row & 31) * K + (dpos ^ ((row >> 1) & 7)) * 8) * 2);
+    } else {
+      b_sb[i] = wbase + (int64_t)(n0 - seg_start) * K + kt0 * 64;
+      b_vo[i] = (uint32_t)(((int64_t)row * K + (dpos ^ ((row >> 1) & 7)) * 8) * 2);
+    }
+    b_dst[i] = b_base + (uint32_t)r0 * 128u;
+  }
+  // copy number c (0 .. D-1: A's first) of stage t into slot t & 1; past the last stage the copy is re-aimed at
+  // the last stage (it lands in a slot nobody reads any more)
+  auto dma_one = [&](int t, int c) __attribute__((always_inline)) {
+    const int koff = (t < KT ? t : KT - 1) * 64;
+    const uint32_t slot = (uint32_t)t & 1u;
+    if (c < A_D) dma16_sbase(a_sb + koff, a_vo[c < A_D ? c : 0], a_dst[c < A_D ? c : 0] + slot * (BM * 128u));
+    else dma16_sbase(b_sb[c >= A_D ? c - A_D : 0] + koff, b_vo[c >= A_D ? c - A_D : 0], b_dst[c >= A_D ? c - A_D : 0] + slot * (BN * 128u));
+  };
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int frow = lane & 31, fch = lane >> 5;          // operand fragment: row in block, which 8-wide k chunk
+  bf16x8_t af[2][TM], bfr[2][TN];                       // operand fragments of two k-slices
+  int a_fu[KS], b_fu[KS];                               // fragment positions inside a slot (16-byte units) per k-slice
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) {
+    a_fu[kk] = swz8(wm * WTM + frow, kk * 2 + fch);
+    b_fu[kk] = 2 * BM * 8 + swz8(wn * WTN + frow, kk * 2 + fch);
+  }
+  // One k-slice: NMF MFMAs; after each of the first TM + TN of them one fragment of the next slice (slot nslot,
+  // k-slice nkk; nkk < 0: none) is read into the other register buffer; copies c0 .. c0 + D/2 - 1 of stage t_copy
+  // (t_copy < 0: none) are issued one per group of MFMAs.
+  auto slice = [&](int buf, int t_copy, int c0, uint32_t nslot, int nkk) __attribute__((always_inline)) {
+#pragma unroll
+    for (int grp = 0; grp < D / 2; ++grp) {
+#pragma unroll
+      for (int q = grp * NMF / (D / 2); q < (grp + 1) * NMF / (D / 2); ++q) {
+        const int i = q / TN, j = q % TN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
+        if (nkk >= 0) {
+          if (q < TM) af[buf ^ 1][q] = lds[a_fu[nkk < 0 ? 0 : nkk] + (int)nslot * BM * 8 + q * 256];
+          else if (q < TM + TN) bfr[buf ^ 1][q - TM] = lds[b_fu[nkk < 0 ? 0 : nkk] + (int)nslot * BN * 8 + (q - TM) * 256];
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // one MFMA ...
+        if (nkk >= 0 && q < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // ... then one LDS read
+      }
+      if (t_copy >= 0) {
+        __builtin_amdgcn_sched_barrier(0);
+        dma_one(t_copy, c0 + grp);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  };
+  // stage t in slot `slot`: three slices read the rest of the stage, then - all of this stage's fragments are in
+  // registers, stage t+1 has landed - the barrier, and the last slice reads the first fragments of stage t+1
+  // while the copies of stage t+2 start into the slot just freed.
+  auto stage = [&](int t, uint32_t slot) __attribute__((always_inline)) {
+    slice(0, t + 1, D / 2, slot, 1);                     // second half of stage t+1's copies
+    slice(1, -1, 0, slot, 2);
+    slice(0, -1, 0, slot, 3);
+    dma_wait_keep<0>();                                  // stage t+1 has landed (this wave's share)
+    asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory"); // this wave's reads of the slot are complete
+    __syncthreads();
+    slice(1, t + 2, 0, slot ^ 1u, 0);                    // first half of stage t+2's copies, into `slot`
+  };
+
+  // ---- prologue: stage 0 and the first half of stage 1 in flight, stage 0 landed and published
+#pragma unroll
+  for (int c = 0; c < D; ++c) dma_one(0, c);
+#pragma unroll
+  for (int c = 0; c < D / 2; ++c) dma_one(1, c);
+  dma_wait_keep<D / 2>();
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < TM; ++i) af[0][i] = lds[a_fu[0] + i * 256];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) bfr[0][j] = lds[b_fu[0] + j * 256];
+
+  int t = 0;
+  for (; t + 2 <= KT; t += 2) {                          // t is even here: slots are literals
+    stage(t, 0u);
+    stage(t + 1, 1u);
+  }
+  if (t < KT) stage(t, (uint32_t)t & 1u);
+  dma_wait_keep<0>();
+  gemm_epilogue<EPI, TM, TN, WTM, WTN>(g, acc, m0, n0, wm, wn, lane);
+}
+
+// Launches tile columns [col0, col0 + ncols) of the GEMM with the 64-k kernel.
+template <int BM, int BN, int WM, int WN, int EPI>
+static fastav_status_t launch_cfg_k64(GemmArgs g, int col0, int ncols, int splits, hipStream_t s) {
+  constexpr int OUT_BN = (EPI == FASTAV_EPI_SWIGLU) ? BN / 2 : BN;
+  g.tiles_m = (g.M + BM - 1) / BM;
+  g.tiles_n = ncols;
+  g.n_off = col0 * OUT_BN;
+  g.splits = splits;
+  g.band = (g.tiles_m * g.tiles_n > kNumCUs) ? 4 : 1;
+  const size_t shmem = (size_t)2 * (BM + BN) * 8 * sizeof(bf16x8_t);
+  hipError_t e = hipFuncSetAttribute((const void*)k_gemm_mfma_k64<BM, BN, WM, WN, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+  if (e != hipSuccess) return fail(FASTAV_EHIP, "gemm: hipFuncSetAttribute: %s", hipGetErrorString(e));
+  hipLaunchKernelGGL((k_gemm_mfma_k64<BM, BN, WM, WN, EPI>), dim3((unsigned)(g.tiles_m * g.tiles_n), (unsigned)splits),
+                     dim3(WM * WN * 64), shmem, s, g);
+  return check_launch("gemm_mfma_k64");
 }
 
 bool mfma_linear_supported(int64_t m, int n, int k, int epilogue, int dtype) {
@@ -324,9 +512,9 @@ constexpr int kCUs = kNumCUs;
 template <int EPI>
 static fastav_status_t launch_big(const GemmArgs& g, int col0, int ncols, int64_t tiles, hipStream_t s) {
   if constexpr (EPI == FASTAV_EPI_RESADD) {
-    if (tiles >= 2 * kCUs) return launch_cfg<256, 256, 2, 4, kEpiResAtomic>(g, col0, ncols, 1, s);
+    if (tiles >= 2 * kCUs) return launch_cfg_k64<256, 256, 2, 4, kEpiResAtomic>(g, col0, ncols, 1, s);
   }
-  return launch_cfg<256, 256, 2, 4, EPI>(g, col0, ncols, 1, s);
+  return launch_cfg_k64<256, 256, 2, 4, EPI>(g, col0, ncols, 1, s);
 }
 
 constexpr size_t kSplitKScratchBytes = (size_t)2 * kCUs * 256 * 256 * sizeof(float);   // <= 512 partial tiles
