@@ -290,7 +290,7 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 4 && NST == 3) ? 2 : 1) v
 // the 16 lanes of a fragment read then hit 16 different bank groups.
 __device__ __forceinline__ int swz8(int row, int chunk) { return row * 8 + (chunk ^ ((row >> 1) & 7)); }   // 16-byte units
 
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int WM, int WN, int EPI, int LATE = 0>
 __global__ __launch_bounds__(WM * WN * 64, 1) void k_gemm_mfma_k64(GemmArgs g) {
   constexpr int NW = WM * WN;                          // waves
   constexpr int WTM = BM / WM, WTN = BN / WN;          // wave tile
@@ -389,23 +389,26 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void k_gemm_mfma_k64(GemmArgs g) {
     b_fu[kk] = 2 * BM * 8 + swz8(wn * WTN + frow, kk * 2 + fch);
   }
   // One k-slice: NMF MFMAs; after each of the first TM + TN of them one fragment of the next slice (slot nslot,
-  // k-slice nkk; nkk < 0: none) is read into the other register buffer; copies c0 .. c0 + D/2 - 1 of stage t_copy
-  // (t_copy < 0: none) are issued one per group of MFMAs.
-  auto slice = [&](int buf, int t_copy, int c0, uint32_t nslot, int nkk) __attribute__((always_inline)) {
+  // k-slice nkk; nkk < 0: none) is read into the other register buffer; `ncopy` copies of stage t_copy, numbers
+  // c0 .. c0 + ncopy - 1, are issued evenly between the MFMAs.
+  auto slice = [&](int buf, int t_copy, int c0, int ncopy, uint32_t nslot, int nkk) __attribute__((always_inline)) {
+    const int groups = ncopy > 0 ? ncopy : 1;
 #pragma unroll
-    for (int grp = 0; grp < D / 2; ++grp) {
+    for (int grp = 0; grp < groups; ++grp) {
 #pragma unroll
-      for (int q = grp * NMF / (D / 2); q < (grp + 1) * NMF / (D / 2); ++q) {
+      for (int q = grp * NMF / groups; q < (grp + 1) * NMF / groups; ++q) {
         const int i = q / TN, j = q % TN;
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
         if (nkk >= 0) {
-          if (q < TM) af[buf ^ 1][q] = lds[a_fu[nkk < 0 ? 0 : nkk] + (int)nslot * BM * 8 + q * 256];
-          else if (q < TM + TN) bfr[buf ^ 1][q - TM] = lds[b_fu[nkk < 0 ? 0 : nkk] + (int)nslot * BN * 8 + (q - TM) * 256];
+          // fragments in the order the next slice's MFMAs first need them: A block 0, all B blocks, the other A blocks
+          if (q == 0) af[buf ^ 1][0] = lds[a_fu[nkk < 0 ? 0 : nkk] + (int)nslot * BM * 8];
+          else if (q <= TN) bfr[buf ^ 1][q - 1] = lds[b_fu[nkk < 0 ? 0 : nkk] + (int)nslot * BN * 8 + (q - 1) * 256];
+          else if (q < TM + TN) af[buf ^ 1][q - TN] = lds[a_fu[nkk < 0 ? 0 : nkk] + (int)nslot * BM * 8 + (q - TN) * 256];
         }
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // one MFMA ...
         if (nkk >= 0 && q < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // ... then one LDS read
       }
-      if (t_copy >= 0) {
+      if (ncopy > 0) {
         __builtin_amdgcn_sched_barrier(0);
         dma_one(t_copy, c0 + grp);
         __builtin_amdgcn_sched_barrier(0);
@@ -414,23 +417,24 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void k_gemm_mfma_k64(GemmArgs g) {
   };
   // stage t in slot `slot`: three slices read the rest of the stage, then - all of this stage's fragments are in
   // registers, stage t+1 has landed - the barrier, and the last slice reads the first fragments of stage t+1
-  // while the copies of stage t+2 start into the slot just freed.
+  // while all copies of stage t+2 go out into the slot just freed: they have a whole stage of matrix work to land.
   auto stage = [&](int t, uint32_t slot) __attribute__((always_inline)) {
-    slice(0, t + 1, D / 2, slot, 1);                     // second half of stage t+1's copies
-    slice(1, -1, 0, slot, 2);
-    slice(0, -1, 0, slot, 3);
+    slice(0, t + 1, D - LATE, LATE, slot, 1);            // the last LATE copies of stage t+1
+    slice(1, 0, 0, 0, slot, 2);
+    slice(0, 0, 0, 0, slot, 3);
     dma_wait_keep<0>();                                  // stage t+1 has landed (this wave's share)
     asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory"); // this wave's reads of the slot are complete
     __syncthreads();
-    slice(1, t + 2, 0, slot ^ 1u, 0);                    // first half of stage t+2's copies, into `slot`
+    slice(1, t + 2, 0, D - LATE, slot ^ 1u, 0);
   };
+  static_assert(NMF >= D, "a slice has fewer MFMAs than a stage has copies");
 
-  // ---- prologue: stage 0 and the first half of stage 1 in flight, stage 0 landed and published
+  // ---- prologue: stages 0 and 1 in flight, stage 0 landed and published
 #pragma unroll
   for (int c = 0; c < D; ++c) dma_one(0, c);
 #pragma unroll
-  for (int c = 0; c < D / 2; ++c) dma_one(1, c);
-  dma_wait_keep<D / 2>();
+  for (int c = 0; c < D - LATE; ++c) dma_one(1, c);
+  dma_wait_keep<D - LATE>();
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < TM; ++i) af[0][i] = lds[a_fu[0] + i * 256];
@@ -448,7 +452,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void k_gemm_mfma_k64(GemmArgs g) {
 }
 
 // Launches tile columns [col0, col0 + ncols) of the GEMM with the 64-k kernel.
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int WM, int WN, int EPI, int LATE = 0>
 static fastav_status_t launch_cfg_k64(GemmArgs g, int col0, int ncols, int splits, hipStream_t s) {
   constexpr int OUT_BN = (EPI == FASTAV_EPI_SWIGLU) ? BN / 2 : BN;
   g.tiles_m = (g.M + BM - 1) / BM;
@@ -457,9 +461,9 @@ static fastav_status_t launch_cfg_k64(GemmArgs g, int col0, int ncols, int split
   g.splits = splits;
   g.band = (g.tiles_m * g.tiles_n > kNumCUs) ? 4 : 1;
   const size_t shmem = (size_t)2 * (BM + BN) * 8 * sizeof(bf16x8_t);
-  hipError_t e = hipFuncSetAttribute((const void*)k_gemm_mfma_k64<BM, BN, WM, WN, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+  hipError_t e = hipFuncSetAttribute((const void*)k_gemm_mfma_k64<BM, BN, WM, WN, EPI, LATE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
   if (e != hipSuccess) return fail(FASTAV_EHIP, "gemm: hipFuncSetAttribute: %s", hipGetErrorString(e));
-  hipLaunchKernelGGL((k_gemm_mfma_k64<BM, BN, WM, WN, EPI>), dim3((unsigned)(g.tiles_m * g.tiles_n), (unsigned)splits),
+  hipLaunchKernelGGL((k_gemm_mfma_k64<BM, BN, WM, WN, EPI, LATE>), dim3((unsigned)(g.tiles_m * g.tiles_n), (unsigned)splits),
                      dim3(WM * WN * 64), shmem, s, g);
   return check_launch("gemm_mfma_k64");
 }
@@ -545,7 +549,7 @@ static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, void* scratch, size_
     if (best > 1) {
       GemmArgs gp = g;
       gp.partial = (float*)scratch;
-      fastav_status_t st = launch_cfg<256, 256, 2, 4, kEpiPartial>(gp, 0, tn, best, s);
+      fastav_status_t st = launch_cfg_k64<256, 256, 2, 4, kEpiPartial>(gp, 0, tn, best, s);
       if (st != FASTAV_OK) return st;
       const int64_t total = (int64_t)g.M * (g.N / 4);
       const unsigned blocks = (unsigned)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
