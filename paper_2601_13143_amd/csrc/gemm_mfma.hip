@@ -549,7 +549,10 @@ static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, void* scratch, size_
     if (best > 1) {
       GemmArgs gp = g;
       gp.partial = (float*)scratch;
-      fastav_status_t st = launch_cfg_k64<256, 256, 2, 4, kEpiPartial>(gp, 0, tn, best, s);
+      // long K ranges: the 64-k kernel; short ones (an O projection cut in three) start and drain faster with
+      // the 32-k ring, whose prologue is half as large
+      fastav_status_t st = (g.K / best >= 2048) ? launch_cfg_k64<256, 256, 2, 4, kEpiPartial>(gp, 0, tn, best, s)
+                                                : launch_cfg<256, 256, 2, 4, kEpiPartial>(gp, 0, tn, best, s);
       if (st != FASTAV_OK) return st;
       const int64_t total = (int64_t)g.M * (g.N / 4);
       const unsigned blocks = (unsigned)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
