@@ -60,6 +60,21 @@ __device__ __forceinline__ void dma16_sbase(const void* base, uint32_t voff, uin
   const void* sbase = (const void*)(uintptr_t)(((uint64_t)hi << 32) | lo);
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(sbase), "s"(lds_byte_addr) : "memory");
 }
+// The same copy as a buffer load: a 128-bit resource (base, no stride, no bounds of interest) in SGPRs, a 32-bit
+// lane offset and a scalar byte offset that advances along K.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4_t make_rsrc(const void* base) {
+  const uint64_t u = (uint64_t)(uintptr_t)base;
+  u32x4_t r;
+  r[0] = __builtin_amdgcn_readfirstlane((uint32_t)u);
+  r[1] = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32) & 0xFFFFu);
+  r[2] = 0xFFFFFFFFu;                                  // num_records: the whole address range after base
+  r[3] = 0x00020000u;                                  // raw buffer, 32-bit data format
+  return r;
+}
+__device__ __forceinline__ void dma16_buf(u32x4_t rsrc, uint32_t voff, uint32_t soff, uint32_t lds_byte_addr) {
+  asm volatile("s_mov_b32 m0, %3\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds" : : "v"(voff), "s"(rsrc), "s"(soff), "s"(lds_byte_addr) : "memory");
+}
 template <int N> __device__ __forceinline__ void dma_wait_keep() {   // until at most N copies are in flight
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
@@ -365,11 +380,15 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void k_gemm_mfma_k64(GemmArgs g) {
   }
   // copy number c (0 .. D-1: A's first) of stage t into slot t & 1; past the last stage the copy is re-aimed at
   // the last stage (it lands in a slot nobody reads any more)
+  const u32x4_t a_rs = make_rsrc(a_sb);
+  u32x4_t b_rs[B_D];
+#pragma unroll
+  for (int i = 0; i < B_D; ++i) b_rs[i] = make_rsrc(b_sb[i]);
   auto dma_one = [&](int t, int c) __attribute__((always_inline)) {
-    const int koff = (t < KT ? t : KT - 1) * 64;
+    const uint32_t koff = (uint32_t)((t < KT ? t : KT - 1) * 128);            // bytes along K
     const uint32_t slot = (uint32_t)t & 1u;
-    if (c < A_D) dma16_sbase(a_sb + koff, a_vo[c < A_D ? c : 0], a_dst[c < A_D ? c : 0] + slot * (BM * 128u));
-    else dma16_sbase(b_sb[c >= A_D ? c - A_D : 0] + koff, b_vo[c >= A_D ? c - A_D : 0], b_dst[c >= A_D ? c - A_D : 0] + slot * (BN * 128u));
+    if (c < A_D) dma16_buf(a_rs, a_vo[c < A_D ? c : 0], koff, a_dst[c < A_D ? c : 0] + slot * (BM * 128u));
+    else dma16_buf(b_rs[c >= A_D ? c - A_D : 0], b_vo[c >= A_D ? c - A_D : 0], koff, b_dst[c >= A_D ? c - A_D : 0] + slot * (BN * 128u));
   };
 
   f32x16_t acc[TM][TN];
