@@ -306,7 +306,7 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 4 && NST == 3) ? 2 : 1) v
 __device__ __forceinline__ int swz8(int row, int chunk) { return row * 8 + (chunk ^ ((row >> 1) & 7)); }   // 16-byte units
 
 template <int BM, int BN, int WM, int WN, int EPI, int LATE = 0>
-__global__ __launch_bounds__(WM * WN * 64, 1) void k_gemm_mfma_k64(GemmArgs g) {
+__global__ __launch_bounds__(WM * WN * 64, (BM + BN) * 256 <= 80 * 1024 ? 2 : 1) void k_gemm_mfma_k64(GemmArgs g) {
   constexpr int NW = WM * WN;                          // waves
   constexpr int WTM = BM / WM, WTN = BN / WN;          // wave tile
   constexpr int TM = WTM / 32, TN = WTN / 32;          // 32x32 blocks per wave
@@ -446,7 +446,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void k_gemm_mfma_k64(GemmArgs g) {
     __syncthreads();
     slice(1, t + 2, 0, D - LATE, slot ^ 1u, 0);
   };
-  static_assert(NMF >= D, "a slice has fewer MFMAs than a stage has copies");
+  static_assert(NMF >= D - LATE && NMF >= LATE, "a slice has fewer MFMAs than it has copies to issue");
 
   // ---- prologue: stages 0 and 1 in flight, stage 0 landed and published
 #pragma unroll
@@ -550,7 +550,7 @@ static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, void* scratch, size_
   const int tm = (g.M + 255) / 256;
   const int tn = g.N / OUT_BIG;                         // tile columns of the 256 x 256 tiling (valid if big_ok)
   const int64_t tiles_big = (int64_t)tm * tn;
-  if (!big_ok) return launch_cfg<128, 128, 2, 2, EPI>(g, 0, g.N / OUT_SMALL, 1, s);
+  if (!big_ok) return launch_cfg_k64<128, 128, 2, 2, EPI, 4>(g, 0, g.N / OUT_SMALL, 1, s);
 
   // Less than one round of 256 x 256 tiles and a linear epilogue: split K so that about one tile per CU
   // is in flight; partial tiles go to scratch and are added to the residual in split order.
@@ -579,7 +579,9 @@ static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, void* scratch, size_
       return check_launch("splitk_reduce");
     }
   }
-  if (tiles_big < 192) return launch_cfg<128, 128, 2, 2, EPI>(g, 0, g.N / OUT_SMALL, 1, s);
+  // small launches: 128 x 128 tiles, two workgroups per CU, through the 64-k loop (copies split over two slices:
+  // a 64 x 64 wave tile has four MFMAs per slice); +10-20 % over the 32-k ring on the pruned layers' QKV
+  if (tiles_big < 192) return launch_cfg_k64<128, 128, 2, 2, EPI, 4>(g, 0, g.N / OUT_SMALL, 1, s);
 
   // Whole rounds of big tiles, then the leftover tile columns with 128 x 128 tiles (two workgroups per CU)
   // when the last round would leave three quarters of the CUs idle.
