@@ -487,6 +487,197 @@ static fastav_status_t launch_cfg_k64(GemmArgs g, int col0, int ncols, int split
   return check_launch("gemm_mfma_k64");
 }
 
+// The 64-k loop with three slots for A and two for B (160 KB for a 256 x 256 tile: all of a CU's LDS).  With two
+// slots each, every copy of stage t+2 has to go out inside stage t's last k-slice, and that burst asks the CU's
+// vector-memory path for twice what it moves per clock: in-kernel timestamps show that slice taking about three
+// times as long as a slice without copies.  The third A slot is free one stage earlier, so A's copies of stage
+// t+2 are spread over stage t's first three slices and only B's are left for the last one - the request rate
+// stays at or under what the path sustains, and every copy still has at least three slices to land.
+template <int BM, int BN, int WM, int WN, int EPI>
+__global__ __launch_bounds__(WM * WN * 64, 1) void k_gemm_mfma_k64a3(GemmArgs g) {
+  constexpr int NW = WM * WN;                          // waves
+  constexpr int WTM = BM / WM, WTN = BN / WN;          // wave tile
+  constexpr int TM = WTM / 32, TN = WTN / 32;          // 32x32 blocks per wave
+  constexpr int A_D = BM / (8 * NW), B_D = BN / (8 * NW);     // copy instructions per wave and stage (8 rows each)
+  constexpr int D = A_D + B_D;
+  constexpr int NMF = TM * TN;                         // MFMAs per k-slice
+  constexpr int KS = 4;                                // k-slices of 16 per stage
+  constexpr int OUT_BN = (EPI == FASTAV_EPI_SWIGLU) ? BN / 2 : BN;
+  static_assert(A_D >= 1 && B_D >= 1 && D % 2 == 0 && NMF >= D / 2 && NMF >= TM + TN && TN % 2 == 0, "tile shape");
+  extern __shared__ bf16x8_t lds[];                    // [3][BM*8] A, then [2][BN*8] B
+
+  // ---- tile assignment (as in k_gemm_mfma)
+  const int nblk = g.tiles_m * g.tiles_n;
+  int pid = blockIdx.x;
+  {
+    const int per = nblk / 8, rem = nblk % 8, xcd = pid % 8, idx = pid / 8;
+    pid = xcd * per + (xcd < rem ? xcd : rem) + idx;
+  }
+  const int kb = g.band;
+  const int band = pid / (kb * g.tiles_m);
+  const int bw = (g.tiles_n - band * kb < kb) ? g.tiles_n - band * kb : kb;   // columns in this band
+  const int inb = pid - band * kb * g.tiles_m;
+  const int tile_m = inb / bw, tile_n = band * kb + inb % bw;
+  const int m0 = tile_m * BM;
+  const int n0 = g.n_off + tile_n * OUT_BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int wm = wave / WN, wn = wave % WN;
+  const int K = g.K;
+  // stages of 64 k owned by this workgroup (all of them unless split-K)
+  const int kt_all = K / 64;
+  const int kt0 = (int)((int64_t)kt_all * blockIdx.y / g.splits);
+  const int KT = (int)((int64_t)kt_all * (blockIdx.y + 1) / g.splits) - kt0;
+
+  const bf16_t* wbase = g.W[0];
+  int seg_start = 0;
+  if (EPI != FASTAV_EPI_SWIGLU) {
+    if (n0 >= g.seg_end[0]) { wbase = g.W[1]; seg_start = g.seg_end[0]; }
+    if (n0 >= g.seg_end[1]) { wbase = g.W[2]; seg_start = g.seg_end[1]; }
+  }
+
+  // ---- this wave's copies: instruction i covers tile rows [(i*NW + wave)*8, +8), lane = (row, 16-byte chunk)
+  const int drow = lane >> 3, dpos = lane & 7;
+  const bf16_t* a_sb = g.A + (int64_t)m0 * K + kt0 * 64;
+  const bf16_t* b_sb[B_D];
+  uint32_t a_vo[A_D], b_vo[B_D];                        // lane offsets in bytes
+  uint32_t a_dst[A_D], b_dst[B_D];                      // LDS byte address of the 8-row group in slot 0
+  const uint32_t a_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
+  const uint32_t b_base = a_base + 3u * BM * 128u;
+#pragma unroll
+  for (int i = 0; i < A_D; ++i) {
+    const int r0 = (i * NW + wave_u) * 8, row = r0 + drow;
+    int grow = m0 + row;
+    grow = grow < g.M ? grow : g.M - 1;                 // clamp: stay inside A, the epilogue masks the row
+    a_vo[i] = (uint32_t)(((int64_t)(grow - m0) * K + (dpos ^ ((row >> 1) & 7)) * 8) * 2);
+    a_dst[i] = a_base + (uint32_t)r0 * 128u;
+  }
+#pragma unroll
+  for (int i = 0; i < B_D; ++i) {
+    const int r0 = (i * NW + wave_u) * 8, row = r0 + drow;
+    if (EPI == FASTAV_EPI_SWIGLU) {
+      const int blk = r0 >> 5;                          // the 8 rows of a copy lie inside one 32-row block
+      b_sb[i] = ((blk & 1) ? g.W2 : g.W[0]) + (int64_t)(n0 + (blk >> 1) * 32) * K + kt0 * 64;
+      b_vo[i] = (uint32_t)(((int64_t)(row & 31) * K + (dpos ^ ((row >> 1) & 7)) * 8) * 2);
+    } else {
+      b_sb[i] = wbase + (int64_t)(n0 - seg_start) * K + kt0 * 64;
+      b_vo[i] = (uint32_t)(((int64_t)row * K + (dpos ^ ((row >> 1) & 7)) * 8) * 2);
+    }
+    b_dst[i] = b_base + (uint32_t)r0 * 128u;
+  }
+  // copy number c (0 .. D-1: A's first) of stage t into slot t & 1; past the last stage the copy is re-aimed at
+  // the last stage (it lands in a slot nobody reads any more)
+  const u32x4_t a_rs = make_rsrc(a_sb);
+  u32x4_t b_rs[B_D];
+#pragma unroll
+  for (int i = 0; i < B_D; ++i) b_rs[i] = make_rsrc(b_sb[i]);
+  auto dma_one = [&](int t, int c, uint32_t aslot, uint32_t bslot) __attribute__((always_inline)) {
+    const uint32_t koff = (uint32_t)((t < KT ? t : KT - 1) * 128);            // bytes along K
+    if (c < A_D) dma16_buf(a_rs, a_vo[c < A_D ? c : 0], koff, a_dst[c < A_D ? c : 0] + aslot * (BM * 128u));
+    else dma16_buf(b_rs[c >= A_D ? c - A_D : 0], b_vo[c >= A_D ? c - A_D : 0], koff, b_dst[c >= A_D ? c - A_D : 0] + bslot * (BN * 128u));
+  };
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int frow = lane & 31, fch = lane >> 5;          // operand fragment: row in block, which 8-wide k chunk
+  bf16x8_t af[2][TM], bfr[2][TN];                       // operand fragments of two k-slices
+  int a_fu[KS], b_fu[KS];                               // fragment positions inside a slot (16-byte units) per k-slice
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) {
+    a_fu[kk] = swz8(wm * WTM + frow, kk * 2 + fch);
+    b_fu[kk] = 3 * BM * 8 + swz8(wn * WTN + frow, kk * 2 + fch);
+  }
+  // One k-slice: NMF MFMAs; after each of the first TM + TN of them one fragment of the next slice (slot nslot,
+  // k-slice nkk; nkk < 0: none) is read into the other register buffer; `ncopy` copies of stage t_copy, numbers
+  // c0 .. c0 + ncopy - 1, are issued evenly between the MFMAs.
+  auto slice = [&](int buf, int t_copy, int c0, int ncopy, uint32_t cas, uint32_t cbs, uint32_t ras, uint32_t rbs, int nkk) __attribute__((always_inline)) {
+    const int groups = ncopy > 0 ? ncopy : 1;
+#pragma unroll
+    for (int grp = 0; grp < groups; ++grp) {
+#pragma unroll
+      for (int q = grp * NMF / groups; q < (grp + 1) * NMF / groups; ++q) {
+        const int i = q / TN, j = q % TN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
+        if (nkk >= 0) {
+          if (q == 0) af[buf ^ 1][0] = lds[a_fu[nkk < 0 ? 0 : nkk] + (int)ras * BM * 8];
+          else if (q <= TN) bfr[buf ^ 1][q - 1] = lds[b_fu[nkk < 0 ? 0 : nkk] + (int)rbs * BN * 8 + (q - 1) * 256];
+          else if (q < TM + TN) af[buf ^ 1][q - TN] = lds[a_fu[nkk < 0 ? 0 : nkk] + (int)ras * BM * 8 + (q - TN) * 256];
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (nkk >= 0 && q < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      if (ncopy > 0) {
+        __builtin_amdgcn_sched_barrier(0);
+        dma_one(t_copy, c0 + grp, cas, cbs);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  };
+  // stage t reads A slot `as` (t mod 3) and B slot `bs` (t mod 2).  A's copies of stage t+2 go out during the
+  // first three slices into the A slot freed by the previous stage's barrier; B's copies of stage t+2 go out in
+  // the last slice, after this stage's barrier, into the B slot this stage has just finished reading.
+  constexpr int A0 = A_D / 3, A1 = (2 * A_D) / 3 - A0, A2 = A_D - A0 - A1;
+  auto stage = [&](int t, uint32_t as, uint32_t bs) __attribute__((always_inline)) {
+    const uint32_t as2 = as >= 1u ? as - 1u : 2u;        // (t + 2) mod 3
+    const uint32_t as1 = as == 2u ? 0u : as + 1u;        // (t + 1) mod 3
+    slice(0, t + 2, 0, A0, as2, 0u, as, bs, 1);
+    slice(1, t + 2, A0, A1, as2, 0u, as, bs, 2);
+    slice(0, t + 2, A0 + A1, A2, as2, 0u, as, bs, 3);
+    dma_wait_keep<A_D>();                                // stage t+1 has landed; only A of stage t+2 may be in flight
+    asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");
+    __syncthreads();
+    slice(1, t + 2, A_D, B_D, 0u, bs, as1, bs ^ 1u, 0);
+  };
+  static_assert(NMF >= B_D && NMF >= A2, "a slice has fewer MFMAs than it has copies to issue");
+
+  // ---- prologue: stages 0 and 1 in flight, stage 0 landed and published
+#pragma unroll
+  for (int c = 0; c < D; ++c) dma_one(0, c, 0u, 0u);
+#pragma unroll
+  for (int c = 0; c < D; ++c) dma_one(1, c, 1u, 1u);
+  dma_wait_keep<D>();
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < TM; ++i) af[0][i] = lds[a_fu[0] + i * 256];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) bfr[0][j] = lds[b_fu[0] + j * 256];
+
+  int t = 0;
+  for (; t + 6 <= KT; t += 6) {                          // t is a multiple of 6 here: slots are literals
+#pragma unroll
+    for (int u = 0; u < 6; ++u) stage(t + u, (uint32_t)(u % 3), (uint32_t)(u % 2));
+  }
+#pragma unroll 1
+  for (; t < KT; ++t) stage(t, (uint32_t)t % 3u, (uint32_t)t & 1u);
+  dma_wait_keep<0>();
+  gemm_epilogue<EPI, TM, TN, WTM, WTN>(g, acc, m0, n0, wm, wn, lane);
+}
+
+
+// Launches tile columns [col0, col0 + ncols) of the GEMM with the 64-k kernel with three A slots.
+template <int BM, int BN, int WM, int WN, int EPI>
+static fastav_status_t launch_cfg_k64a3(GemmArgs g, int col0, int ncols, int splits, hipStream_t s) {
+  constexpr int OUT_BN = (EPI == FASTAV_EPI_SWIGLU) ? BN / 2 : BN;
+  g.tiles_m = (g.M + BM - 1) / BM;
+  g.tiles_n = ncols;
+  g.n_off = col0 * OUT_BN;
+  g.splits = splits;
+  g.band = (g.tiles_m * g.tiles_n > kNumCUs) ? 4 : 1;
+  const size_t shmem = (size_t)(3 * BM + 2 * BN) * 8 * sizeof(bf16x8_t);
+  hipError_t e = hipFuncSetAttribute((const void*)k_gemm_mfma_k64a3<BM, BN, WM, WN, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+  if (e != hipSuccess) return fail(FASTAV_EHIP, "gemm: hipFuncSetAttribute: %s", hipGetErrorString(e));
+  hipLaunchKernelGGL((k_gemm_mfma_k64a3<BM, BN, WM, WN, EPI>), dim3((unsigned)(g.tiles_m * g.tiles_n), (unsigned)splits),
+                     dim3(WM * WN * 64), shmem, s, g);
+  return check_launch("gemm_mfma_k64a3");
+}
+
 bool mfma_linear_supported(int64_t m, int n, int k, int epilogue, int dtype) {
   if (dtype != FASTAV_BF16 || m < 1 || m > 0x7FFFFFFF) return false;
   if (k % 64 != 0 || k < 128) return false;            // >= 4 stages of 32
@@ -535,9 +726,12 @@ constexpr int kCUs = kNumCUs;
 template <int EPI>
 static fastav_status_t launch_big(const GemmArgs& g, int col0, int ncols, int64_t tiles, hipStream_t s) {
   if constexpr (EPI == FASTAV_EPI_RESADD) {
-    if (tiles >= 2 * kCUs) return launch_cfg_k64<256, 256, 2, 4, kEpiResAtomic>(g, col0, ncols, 1, s);
+    if (tiles >= 2 * kCUs) return launch_cfg_k64a3<256, 256, 2, 4, kEpiResAtomic>(g, col0, ncols, 1, s);
   }
-  return launch_cfg_k64<256, 256, 2, 4, EPI>(g, col0, ncols, 1, s);
+  // the gate/up epilogue pairs columns inside a wave, so four waves of 128 x 128 work as well as eight of
+  // 128 x 64 and read half as many fragments from LDS
+  if constexpr (EPI == FASTAV_EPI_SWIGLU) return launch_cfg_k64a3<256, 256, 2, 2, EPI>(g, col0, ncols, 1, s);
+  else return launch_cfg_k64a3<256, 256, 2, 4, EPI>(g, col0, ncols, 1, s);
 }
 
 constexpr size_t kSplitKScratchBytes = (size_t)2 * kCUs * 256 * 256 * sizeof(float);   // <= 512 partial tiles
@@ -570,7 +764,7 @@ static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, void* scratch, size_
       gp.partial = (float*)scratch;
       // long K ranges: the 64-k kernel; short ones (an O projection cut in three) start and drain faster with
       // the 32-k ring, whose prologue is half as large
-      fastav_status_t st = (g.K / best >= 2048) ? launch_cfg_k64<256, 256, 2, 4, kEpiPartial>(gp, 0, tn, best, s)
+      fastav_status_t st = (g.K / best >= 2048) ? launch_cfg_k64a3<256, 256, 2, 4, kEpiPartial>(gp, 0, tn, best, s)
                                                 : launch_cfg<256, 256, 2, 4, kEpiPartial>(gp, 0, tn, best, s);
       if (st != FASTAV_OK) return st;
       const int64_t total = (int64_t)g.M * (g.N / 4);
