@@ -40,6 +40,7 @@ struct GemmArgs {
   int n_off;               // first output column of this launch (a launch may cover a range of tile columns)
   int splits;              // split-K: blockIdx.y picks a K range and writes an fp32 partial tile to `partial`
   float* partial;          // [splits][M][N] fp32 (split-K only)
+  int vec_ok;              // the output (C, or `partial`) takes 16-byte accesses: base and row pitch are multiples of 16 bytes
 };
 
 constexpr int kNumCUs = 256;
@@ -81,28 +82,23 @@ template <int N> __device__ __forceinline__ void dma_wait_keep() {   // until at
 
 __device__ __forceinline__ int swz4(int row, int chunk) { return row * 4 + (chunk ^ ((row >> 2) & 3)); }   // 16-byte units
 
-// Epilogue shared by the GEMM kernels.  Accumulator register r of a 32x32 block: column = lane % 32,
-// row = (r / 4) * 8 + (lane / 32) * 4 + r % 4.
+// Epilogue shared by the GEMM kernels.  The main loops compute the transposed product (weight fragment as the
+// first MFMA operand), so accumulator register r of a 32x32 block holds row = lane % 32 and
+// column = (r / 4) * 8 + (lane / 32) * 4 + r % 4: four consecutive columns of one row per register quad.  fp32
+// outputs go out as 16-byte accesses; bf16 outputs first trade quads between lanes l and l + 32 so that every lane
+// owns eight consecutive columns (16 bytes).  Only the hardware-add epilogue keeps the untransposed product (row
+// quads per lane, one column): its adds are issued element by element and want the 32 lanes on one line.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  bf16x2_t t = {(bf16_t)a, (bf16_t)b};
+  return __builtin_bit_cast(uint32_t, t);
+}
+constexpr bool gemm_transposed(int epi) { return epi != kEpiResAtomic; }
+
 template <int EPI, int TM, int TN, int WTM, int WTN>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, f32x16_t (&acc)[TM][TN], int m0, int n0, int wm, int wn, int lane) {
-  const int ecol = lane & 31, erow0 = (lane >> 5) * 4;
-  if (EPI == FASTAV_EPI_SWIGLU) {
-    bf16_t* C = (bf16_t*)g.C;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; j += 2) {
-        const int col = n0 + (wn * TN / 2 + j / 2) * 32 + ecol;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = m0 + wm * WTM + i * 32 + (r >> 2) * 8 + erow0 + (r & 3);
-          if (row < g.M) {
-            const float gt = acc[i][j][r], up = acc[i][j + 1][r];
-            C[(int64_t)row * g.ldc + col] = (bf16_t)(gt / (1.0f + __expf(-gt)) * up);
-          }
-        }
-      }
-  } else {
+  if constexpr (EPI == kEpiResAtomic) {
+    const int ecol = lane & 31, erow0 = (lane >> 5) * 4;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -111,19 +107,75 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, f32x16_t (&acc)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int row = m0 + wm * WTM + i * 32 + (r >> 2) * 8 + erow0 + (r & 3);
-          if (row < g.M) {
-            if (EPI == FASTAV_EPI_STORE) ((bf16_t*)g.C)[(int64_t)row * g.ldc + col] = (bf16_t)acc[i][j][r];
-            else if (EPI == kEpiPartial) g.partial[((int64_t)blockIdx.y * g.M + row) * g.N + col] = acc[i][j][r];
-            else if (EPI == kEpiResAtomic) {
-              // Residual update as a fire-and-forget hardware add at the L2: no read round trip holds the
-              // wave, so the next tile's main loop on this CU overlaps the drain.  Each element receives
-              // exactly one addend per launch, so the result is that of a read-modify-write.
-              unsafeAtomicAdd(&((float*)g.C)[(int64_t)row * g.ldc + col], acc[i][j][r]);
+          // Residual update as a fire-and-forget hardware add at the L2: no read round trip holds the
+          // wave, so the next tile's main loop on this CU overlaps the drain.  Each element receives
+          // exactly one addend per launch, so the result is that of a read-modify-write.
+          if (row < g.M) unsafeAtomicAdd(&((float*)g.C)[(int64_t)row * g.ldc + col], acc[i][j][r]);
+        }
+      }
+  } else {
+    constexpr int JS = (EPI == FASTAV_EPI_SWIGLU) ? 2 : 1;
+    const int erow = lane & 31, hf = lane >> 5;
+    const bool vec = g.vec_ok != 0;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int row = m0 + wm * WTM + i * 32 + erow;
+      const bool ok = row < g.M;
+#pragma unroll
+      for (int j = 0; j < TN; j += JS) {
+        float v[16];                                     // v[4q + e]: column 8q + 4 hf + e of the block
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          if constexpr (EPI == FASTAV_EPI_SWIGLU) {
+            const float gt = acc[i][j][r], up = acc[i][j + 1][r];
+            v[r] = gt / (1.0f + __expf(-gt)) * up;
+          } else {
+            v[r] = acc[i][j][r];
+          }
+        }
+        const int colb = (EPI == FASTAV_EPI_SWIGLU) ? n0 + (wn * TN / 2 + j / 2) * 32 : n0 + wn * WTN + j * 32;
+        if constexpr (EPI == FASTAV_EPI_STORE || EPI == FASTAV_EPI_SWIGLU) {
+          bf16_t* C = (bf16_t*)g.C + (int64_t)row * g.ldc + colb;
+          if (vec) {
+#pragma unroll
+            for (int pr = 0; pr < 2; ++pr) {             // quads (2 pr, 2 pr + 1): columns 16 pr .. 16 pr + 15
+              const uint32_t x0 = pack_bf16(v[8 * pr + 0], v[8 * pr + 1]), x1 = pack_bf16(v[8 * pr + 2], v[8 * pr + 3]);
+              const uint32_t y0 = pack_bf16(v[8 * pr + 4], v[8 * pr + 5]), y1 = pack_bf16(v[8 * pr + 6], v[8 * pr + 7]);
+              // upper half of x <-> lower half of y: lanes 0-31 end up with columns 0-7, lanes 32-63 with 8-15
+              const auto s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
+              const auto s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
+              const u32x4_t out = {s0[0], s1[0], s0[1], s1[1]};
+              if (ok) *(u32x4_t*)(C + pr * 16 + hf * 8) = out;
             }
-            else ((float*)g.C)[(int64_t)row * g.ldc + col] += acc[i][j][r];
+          } else if (ok) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) C[(r >> 2) * 8 + hf * 4 + (r & 3)] = (bf16_t)v[r];
+          }
+        } else {
+          float* C = (EPI == kEpiPartial) ? g.partial + ((int64_t)blockIdx.y * g.M + row) * g.N + colb + hf * 4
+                                          : (float*)g.C + (int64_t)row * g.ldc + colb + hf * 4;
+          if (ok) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              if (vec) {
+                f32x4_t t = {v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
+                if constexpr (EPI == FASTAV_EPI_RESADD) {
+                  const f32x4_t o = *(const f32x4_t*)(C + 8 * q);
+                  t[0] += o[0]; t[1] += o[1]; t[2] += o[2]; t[3] += o[3];
+                }
+                *(f32x4_t*)(C + 8 * q) = t;
+              } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  if constexpr (EPI == FASTAV_EPI_RESADD) C[8 * q + e] += v[4 * q + e];
+                  else C[8 * q + e] = v[4 * q + e];
+                }
+              }
+            }
           }
         }
       }
+    }
   }
 }
 
@@ -251,7 +303,8 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 4 && NST == 3) ? 2 : 1) v
 #pragma unroll
       for (int q = grp * NMF / (D / 2); q < (grp + 1) * NMF / (D / 2); ++q) {     // MFMAs between two copies
         const int i = q / TN, j = q % TN;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
+        acc[i][j] = gemm_transposed(EPI) ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[buf][j], af[buf][i], acc[i][j], 0, 0, 0)
+                                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
         if (q < TM) af[buf ^ 1][q] = lds[a_fu[nkk] + (int)nslot * BM * 4 + q * 128];
         else if (q < TM + TN) bfr[buf ^ 1][q - TM] = lds[b_fu[nkk] + (int)nslot * BN * 4 + (q - TM) * 128];
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // one MFMA ...
@@ -417,7 +470,8 @@ __global__ __launch_bounds__(WM * WN * 64, (BM + BN) * 256 <= 80 * 1024 ? 2 : 1)
 #pragma unroll
       for (int q = grp * NMF / groups; q < (grp + 1) * NMF / groups; ++q) {
         const int i = q / TN, j = q % TN;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
+        acc[i][j] = gemm_transposed(EPI) ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[buf][j], af[buf][i], acc[i][j], 0, 0, 0)
+                                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
         if (nkk >= 0) {
           // fragments in the order the next slice's MFMAs first need them: A block 0, all B blocks, the other A blocks
           if (q == 0) af[buf ^ 1][0] = lds[a_fu[nkk < 0 ? 0 : nkk] + (int)nslot * BM * 8];
@@ -604,7 +658,8 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void k_gemm_mfma_k64a3(GemmArgs g)
 #pragma unroll
       for (int q = grp * NMF / groups; q < (grp + 1) * NMF / groups; ++q) {
         const int i = q / TN, j = q % TN;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
+        acc[i][j] = gemm_transposed(EPI) ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[buf][j], af[buf][i], acc[i][j], 0, 0, 0)
+                                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bfr[buf][j], acc[i][j], 0, 0, 0);
         if (nkk >= 0) {
           if (q == 0) af[buf ^ 1][0] = lds[a_fu[nkk < 0 ? 0 : nkk] + (int)ras * BM * 8];
           else if (q <= TN) bfr[buf ^ 1][q - 1] = lds[b_fu[nkk < 0 ? 0 : nkk] + (int)rbs * BN * 8 + (q - 1) * 256];
@@ -762,6 +817,7 @@ static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, void* scratch, size_
     if (best > 1) {
       GemmArgs gp = g;
       gp.partial = (float*)scratch;
+      gp.vec_ok = ((uintptr_t)scratch % 16 == 0) ? 1 : 0;   // partial rows are N floats, N a multiple of 128
       // long K ranges: the 64-k kernel; short ones (an O projection cut in three) start and drain faster with
       // the 32-k ring, whose prologue is half as large
       fastav_status_t st = (g.K / best >= 2048) ? launch_cfg_k64a3<256, 256, 2, 4, kEpiPartial>(gp, 0, tn, best, s)
@@ -810,6 +866,7 @@ fastav_status_t launch_linear_mfma(const void* a, const void* const* w_seg, cons
   }
   g.W2 = (const bf16_t*)w2;
   g.C = c; g.ldc = ldc; g.M = (int)m; g.N = n; g.K = k; g.n_off = 0; g.splits = 1; g.partial = nullptr;
+  g.vec_ok = ((uintptr_t)c % 16 == 0 && ldc % (epilogue == FASTAV_EPI_RESADD ? 4 : 8) == 0) ? 1 : 0;
   if (((uintptr_t)a | (uintptr_t)w_seg[0]) % 16) return fail(FASTAV_EINVAL, "gemm: A and W must be 16-byte aligned");
   if (epilogue == FASTAV_EPI_STORE) return launch_epi<FASTAV_EPI_STORE>(g, big_ok, scratch, scratch_bytes, s);
   if (epilogue == FASTAV_EPI_RESADD) return launch_epi<FASTAV_EPI_RESADD>(g, big_ok, scratch, scratch_bytes, s);

@@ -195,6 +195,32 @@ def test_linear(dtype, M, N, K, epi):
     assert_close(got, want, dtype, what=f"linear epi={epi}")
 
 
+@pytest.mark.parametrize("epi", [fa.EPI_STORE, fa.EPI_RESADD, fa.EPI_SWIGLU])
+def test_linear_output_not_16_byte_aligned(epi):
+    """An output that starts one element past a 16-byte boundary takes the element-wise store path."""
+    M, N, K = 300, 1024, 512
+    rng = np.random.default_rng(7 + epi)
+    a = rng.standard_normal((M, K)).astype(np.float32)
+    w = (rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32)
+    w2 = (rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32)
+    fi.round_bf16(a); fi.round_bf16(w); fi.round_bf16(w2)
+    a64, w64, w264 = a.astype(np.float64), w.astype(np.float64), w2.astype(np.float64)
+    if epi == fa.EPI_RESADD:
+        r = rng.standard_normal((M, N)).astype(np.float32)
+        buf = torch.zeros(M * N + 8, dtype=torch.float32, device="cuda")
+        c = buf[1:1 + M * N].view(M, N)
+        c.copy_(torch.from_numpy(r))
+        want = r.astype(np.float64) + a64 @ w64.T
+    else:
+        buf = torch.zeros(M * N + 8, dtype=torch.bfloat16, device="cuda")
+        c = buf[1:1 + M * N].view(M, N)
+        want = a64 @ w64.T if epi == fa.EPI_STORE else orc.silu(a64 @ w64.T) * (a64 @ w264.T)
+    assert c.data_ptr() % 16 != 0
+    fa.fastav_linear(dev(a, "bf16"), dev(w, "bf16"), epi, w2=dev(w2, "bf16") if epi == fa.EPI_SWIGLU else None, c=c)
+    assert_close(host(c), want, "bf16", what=f"linear (unaligned output) epi={epi}")
+    assert float(buf[0]) == 0.0 and float(buf[1 + M * N:].abs().max()) == 0.0
+
+
 # ------------------------------------------------------------------------------------ attention (+ side output)
 @pytest.mark.parametrize("dtype,Hq,Hkv,dh,lens", [("f32", 4, 2, 64, [130, 1, 77]), ("bf16", 8, 2, 128, [300, 129, 64]),
                                                  ("bf16", 4, 4, 64, [200, 65]), ("bf16", 32, 8, 128, [700]),
