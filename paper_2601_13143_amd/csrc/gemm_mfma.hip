@@ -95,88 +95,184 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 }
 constexpr bool gemm_transposed(int epi) { return epi != kEpiResAtomic; }
 
-template <int EPI, int TM, int TN, int WTM, int WTN>
-__device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, f32x16_t (&acc)[TM][TN], int m0, int n0, int wm, int wn, int lane) {
+// One 32x32 block (SwiGLU: the gate block `b0` and the up block `b1` of one output block) of a wave's tile.
+// row0 / col0: the block's first output row / column.
+template <int EPI>
+__device__ __forceinline__ void gemm_epilogue_block(const GemmArgs& g, const f32x16_t& b0, const f32x16_t& b1, int row0, int col0, int lane) {
   if constexpr (EPI == kEpiResAtomic) {
-    const int ecol = lane & 31, erow0 = (lane >> 5) * 4;
+    const int col = col0 + (lane & 31), erow0 = row0 + (lane >> 5) * 4;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wn * WTN + j * 32 + ecol;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = m0 + wm * WTM + i * 32 + (r >> 2) * 8 + erow0 + (r & 3);
-          // Residual update as a fire-and-forget hardware add at the L2: no read round trip holds the
-          // wave, so the next tile's main loop on this CU overlaps the drain.  Each element receives
-          // exactly one addend per launch, so the result is that of a read-modify-write.
-          if (row < g.M) unsafeAtomicAdd(&((float*)g.C)[(int64_t)row * g.ldc + col], acc[i][j][r]);
-        }
-      }
+    for (int r = 0; r < 16; ++r) {
+      const int row = erow0 + (r >> 2) * 8 + (r & 3);
+      // Residual update as a fire-and-forget hardware add at the L2: no read round trip holds the
+      // wave, so the main loop that follows on this CU overlaps the drain.  Each element receives
+      // exactly one addend per launch, so the result is that of a read-modify-write.
+      if (row < g.M) unsafeAtomicAdd(&((float*)g.C)[(int64_t)row * g.ldc + col], b0[r]);
+    }
   } else {
-    constexpr int JS = (EPI == FASTAV_EPI_SWIGLU) ? 2 : 1;
-    const int erow = lane & 31, hf = lane >> 5;
+    const int row = row0 + (lane & 31), hf = lane >> 5;
+    const bool ok = row < g.M;
     const bool vec = g.vec_ok != 0;
+    float v[16];                                         // v[4q + e]: column 8q + 4 hf + e of the block
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int row = m0 + wm * WTM + i * 32 + erow;
-      const bool ok = row < g.M;
+    for (int r = 0; r < 16; ++r) {
+      if constexpr (EPI == FASTAV_EPI_SWIGLU) v[r] = b0[r] / (1.0f + __expf(-b0[r])) * b1[r];
+      else v[r] = b0[r];
+    }
+    if constexpr (EPI == FASTAV_EPI_STORE || EPI == FASTAV_EPI_SWIGLU) {
+      bf16_t* C = (bf16_t*)g.C + (int64_t)row * g.ldc + col0;
+      if (vec) {
 #pragma unroll
-      for (int j = 0; j < TN; j += JS) {
-        float v[16];                                     // v[4q + e]: column 8q + 4 hf + e of the block
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          if constexpr (EPI == FASTAV_EPI_SWIGLU) {
-            const float gt = acc[i][j][r], up = acc[i][j + 1][r];
-            v[r] = gt / (1.0f + __expf(-gt)) * up;
-          } else {
-            v[r] = acc[i][j][r];
-          }
+        for (int pr = 0; pr < 2; ++pr) {                 // quads (2 pr, 2 pr + 1): columns 16 pr .. 16 pr + 15
+          const uint32_t x0 = pack_bf16(v[8 * pr + 0], v[8 * pr + 1]), x1 = pack_bf16(v[8 * pr + 2], v[8 * pr + 3]);
+          const uint32_t y0 = pack_bf16(v[8 * pr + 4], v[8 * pr + 5]), y1 = pack_bf16(v[8 * pr + 6], v[8 * pr + 7]);
+          // upper half of x <-> lower half of y: lanes 0-31 end up with columns 0-7, lanes 32-63 with 8-15
+          const auto s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
+          const auto s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
+          const u32x4_t out = {s0[0], s1[0], s0[1], s1[1]};
+          if (ok) *(u32x4_t*)(C + pr * 16 + hf * 8) = out;
         }
-        const int colb = (EPI == FASTAV_EPI_SWIGLU) ? n0 + (wn * TN / 2 + j / 2) * 32 : n0 + wn * WTN + j * 32;
-        if constexpr (EPI == FASTAV_EPI_STORE || EPI == FASTAV_EPI_SWIGLU) {
-          bf16_t* C = (bf16_t*)g.C + (int64_t)row * g.ldc + colb;
+      } else if (ok) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) C[(r >> 2) * 8 + hf * 4 + (r & 3)] = (bf16_t)v[r];
+      }
+    } else {
+      float* C = (EPI == kEpiPartial) ? g.partial + ((int64_t)blockIdx.y * g.M + row) * g.N + col0 + hf * 4
+                                      : (float*)g.C + (int64_t)row * g.ldc + col0 + hf * 4;
+      if (ok) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
           if (vec) {
-#pragma unroll
-            for (int pr = 0; pr < 2; ++pr) {             // quads (2 pr, 2 pr + 1): columns 16 pr .. 16 pr + 15
-              const uint32_t x0 = pack_bf16(v[8 * pr + 0], v[8 * pr + 1]), x1 = pack_bf16(v[8 * pr + 2], v[8 * pr + 3]);
-              const uint32_t y0 = pack_bf16(v[8 * pr + 4], v[8 * pr + 5]), y1 = pack_bf16(v[8 * pr + 6], v[8 * pr + 7]);
-              // upper half of x <-> lower half of y: lanes 0-31 end up with columns 0-7, lanes 32-63 with 8-15
-              const auto s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
-              const auto s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
-              const u32x4_t out = {s0[0], s1[0], s0[1], s1[1]};
-              if (ok) *(u32x4_t*)(C + pr * 16 + hf * 8) = out;
+            f32x4_t t = {v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
+            if constexpr (EPI == FASTAV_EPI_RESADD) {
+              const f32x4_t o = *(const f32x4_t*)(C + 8 * q);
+              t[0] += o[0]; t[1] += o[1]; t[2] += o[2]; t[3] += o[3];
             }
-          } else if (ok) {
+            *(f32x4_t*)(C + 8 * q) = t;
+          } else {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) C[(r >> 2) * 8 + hf * 4 + (r & 3)] = (bf16_t)v[r];
-          }
-        } else {
-          float* C = (EPI == kEpiPartial) ? g.partial + ((int64_t)blockIdx.y * g.M + row) * g.N + colb + hf * 4
-                                          : (float*)g.C + (int64_t)row * g.ldc + colb + hf * 4;
-          if (ok) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              if (vec) {
-                f32x4_t t = {v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
-                if constexpr (EPI == FASTAV_EPI_RESADD) {
-                  const f32x4_t o = *(const f32x4_t*)(C + 8 * q);
-                  t[0] += o[0]; t[1] += o[1]; t[2] += o[2]; t[3] += o[3];
-                }
-                *(f32x4_t*)(C + 8 * q) = t;
-              } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                  if constexpr (EPI == FASTAV_EPI_RESADD) C[8 * q + e] += v[4 * q + e];
-                  else C[8 * q + e] = v[4 * q + e];
-                }
-              }
+            for (int e = 0; e < 4; ++e) {
+              if constexpr (EPI == FASTAV_EPI_RESADD) C[8 * q + e] += v[4 * q + e];
+              else C[8 * q + e] = v[4 * q + e];
             }
           }
         }
       }
     }
   }
+}
+
+// Epilogue of a wave's tile.  `stage` is LDS the wave may use as it likes (the caller has made sure that no copy
+// is still in flight and no other wave reads it): 2 x 32 rows of the wave's output width in bf16.  An aligned bf16
+// output goes through it - the lanes' 16-byte pieces are laid down row by row and read back so that a store
+// instruction covers whole rows of the wave's tile (full 128-byte lines, a quarter of the L2 write requests of
+// storing the pieces as the accumulators hold them).
+template <int EPI, int TM, int TN, int WTM, int WTN, bool USE_F32_STAGE = true>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, f32x16_t (&acc)[TM][TN], int m0, int n0, int wm, int wn, int lane,
+                                              bf16x8_t* stage) {
+  constexpr int JS = (EPI == FASTAV_EPI_SWIGLU) ? 2 : 1;
+  constexpr int NB = TN / JS;                            // output blocks per block row
+  constexpr int NCHK = NB * 4;                           // 16-byte chunks per output row of the wave
+  constexpr int RPI = 64 / NCHK;                         // rows a 64-lane access covers
+  if constexpr (EPI == FASTAV_EPI_STORE || EPI == FASTAV_EPI_SWIGLU) {
+    // (measured: worth 1.5-3 % for the plain store; the gate/up output is half as wide and comes out 1 % slower
+    // this way than with the pieces stored directly, so it keeps the direct path)
+    if (EPI == FASTAV_EPI_STORE && g.vec_ok) {
+      static_assert(NCHK == 4 || NCHK == 8 || NCHK == 16, "wave tile width");
+      constexpr int SWM = NCHK >= 8 ? 7 : NCHK - 1;          // chunk swizzle: spreads a column of pieces over the banks
+      const int m = lane & 31, hf = lane >> 5;
+      const int rr = lane / NCHK, cc = lane % NCHK;
+      const int colw = (EPI == FASTAV_EPI_SWIGLU) ? n0 + wn * (WTN / 2) : n0 + wn * WTN;
+      bf16_t* C = (bf16_t*)g.C + colw + cc * 8;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        bf16x8_t* st = stage + (i & 1) * 32 * NCHK;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) {
+          float v[16];                                   // v[4q + e]: column 8q + 4 hf + e of the block
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            if constexpr (EPI == FASTAV_EPI_SWIGLU) {
+              const float gt = acc[i][2 * jb][r], up = acc[i][2 * jb + 1][r];
+              v[r] = gt / (1.0f + __expf(-gt)) * up;
+            } else {
+              v[r] = acc[i][jb][r];
+            }
+          }
+#pragma unroll
+          for (int pr = 0; pr < 2; ++pr) {               // quads (2 pr, 2 pr + 1): columns 16 pr .. 16 pr + 15
+            const uint32_t x0 = pack_bf16(v[8 * pr + 0], v[8 * pr + 1]), x1 = pack_bf16(v[8 * pr + 2], v[8 * pr + 3]);
+            const uint32_t y0 = pack_bf16(v[8 * pr + 4], v[8 * pr + 5]), y1 = pack_bf16(v[8 * pr + 6], v[8 * pr + 7]);
+            // upper half of x <-> lower half of y: lanes 0-31 end up with columns 0-7, lanes 32-63 with 8-15
+            const auto s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
+            const auto s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
+            const u32x4_t out = {s0[0], s1[0], s0[1], s1[1]};
+            const int c = jb * 4 + pr * 2 + hf;
+            *(u32x4_t*)&st[m * NCHK + (c ^ (m & SWM))] = out;
+          }
+        }
+        // the wave's own LDS accesses execute in order: no wait between the writes above and the reads below
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it) {
+          const int r = it * RPI + rr;
+          const u32x4_t val = *(const u32x4_t*)&st[r * NCHK + (cc ^ (r & SWM))];
+          const int row = m0 + wm * WTM + i * 32 + r;
+          if (row < g.M) *(u32x4_t*)(C + (int64_t)row * g.ldc) = val;
+        }
+      }
+      return;
+    }
+  }
+  if constexpr (EPI == FASTAV_EPI_RESADD || EPI == kEpiPartial) {
+    // fp32 outputs the same way: 16-byte pieces of four columns, 8 TN of them per output row of the wave
+    if (g.vec_ok && USE_F32_STAGE) {
+      constexpr int NC = TN * 8, RP = 64 / NC;           // chunks per row, rows per 64-lane access
+      static_assert(NC == 16 || NC == 32, "wave tile width");
+      const int m = lane & 31, hf = lane >> 5;
+      const int rr = lane / NC, cc = lane % NC;
+      float* C = (EPI == kEpiPartial) ? g.partial + (int64_t)blockIdx.y * g.M * g.N + n0 + wn * WTN + cc * 4
+                                      : (float*)g.C + n0 + wn * WTN + cc * 4;
+      const int64_t pitch = (EPI == kEpiPartial) ? g.N : g.ldc;
+      f32x4_t* stf = (f32x4_t*)stage;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        f32x4_t* st = stf + (i & 1) * 32 * NC;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const f32x4_t t = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+            const int c = j * 8 + q * 2 + hf;
+            st[m * NC + (c ^ (m & 7))] = t;
+          }
+        f32x4_t old[32 / RP];
+        if constexpr (EPI == FASTAV_EPI_RESADD) {
+#pragma unroll
+          for (int it = 0; it < 32 / RP; ++it) {
+            const int row = m0 + wm * WTM + i * 32 + it * RP + rr;
+            old[it] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            if (row < g.M) old[it] = *(const f32x4_t*)(C + (int64_t)row * pitch);
+          }
+        }
+#pragma unroll
+        for (int it = 0; it < 32 / RP; ++it) {
+          const int r = it * RP + rr;
+          f32x4_t val = st[r * NC + (cc ^ (r & 7))];
+          if constexpr (EPI == FASTAV_EPI_RESADD) { val[0] += old[it][0]; val[1] += old[it][1]; val[2] += old[it][2]; val[3] += old[it][3]; }
+          const int row = m0 + wm * WTM + i * 32 + r;
+          if (row < g.M) *(f32x4_t*)(C + (int64_t)row * pitch) = val;
+        }
+      }
+      return;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; j += JS) {
+      const int col0 = (EPI == FASTAV_EPI_SWIGLU) ? n0 + (wn * TN / 2 + j / 2) * 32 : n0 + wn * WTN + j * 32;
+      gemm_epilogue_block<EPI>(g, acc[i][j], acc[i][JS == 2 ? j + 1 : j], m0 + wm * WTM + i * 32, col0, lane);
+    }
 }
 
 // NST = LDS ring depth in stages of 32 k (copies run NST-1 stages ahead).  A 256 x 128 tile with 4 waves and
@@ -346,7 +442,9 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 4 && NST == 3) ? 2 : 1) v
   for (; t < KT; ++t) stage(t, (uint32_t)t % (uint32_t)NST);
   dma_wait_keep<0>();
 
-  gemm_epilogue<EPI, TM, TN, WTM, WTN>(g, acc, m0, n0, wm, wn, lane);
+  __syncthreads();                                     // every wave's copies have landed: LDS is free for the epilogue
+  gemm_epilogue<EPI, TM, TN, WTM, WTN>(g, acc, m0, n0, wm, wn, lane,
+                                       lds + wave * (2 * 32 * 8 * TN));
 }
 
 // The same GEMM with stages of 64 k in a double buffer.  What changes is the shape of a copy: a wave instruction
@@ -521,7 +619,9 @@ __global__ __launch_bounds__(WM * WN * 64, (BM + BN) * 256 <= 80 * 1024 ? 2 : 1)
   }
   if (t < KT) stage(t, (uint32_t)t & 1u);
   dma_wait_keep<0>();
-  gemm_epilogue<EPI, TM, TN, WTM, WTN>(g, acc, m0, n0, wm, wn, lane);
+  __syncthreads();                                     // every wave's copies have landed: LDS is free for the epilogue
+  gemm_epilogue<EPI, TM, TN, WTM, WTN>(g, acc, m0, n0, wm, wn, lane,
+                                       lds + wave * (2 * 32 * 8 * TN));
 }
 
 // Launches tile columns [col0, col0 + ncols) of the GEMM with the 64-k kernel.
@@ -712,7 +812,9 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void k_gemm_mfma_k64a3(GemmArgs g)
 #pragma unroll 1
   for (; t < KT; ++t) stage(t, (uint32_t)t % 3u, (uint32_t)t & 1u);
   dma_wait_keep<0>();
-  gemm_epilogue<EPI, TM, TN, WTM, WTN>(g, acc, m0, n0, wm, wn, lane);
+  __syncthreads();                                     // every wave's copies have landed: LDS is free for the epilogue
+  gemm_epilogue<EPI, TM, TN, WTM, WTN>(g, acc, m0, n0, wm, wn, lane,
+                                       lds + wave * (2 * 32 * 8 * TN));
 }
 
 
