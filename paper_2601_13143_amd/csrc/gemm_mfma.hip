@@ -835,6 +835,348 @@ static fastav_status_t launch_cfg_k64a3(GemmArgs g, int col0, int ncols, int spl
   return check_launch("gemm_mfma_k64a3");
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// The 256 x 256 kernel on v_mfma_f32_16x16x32_bf16.  Under these GEMMs the chip is power-limited, and this shape
+// reads and writes half as many accumulator registers per flop as 32x32x16: a loop of nothing but matrix
+// instructions sustains 2.05 GHz with it against 1.76 GHz (both at full issue rate).  Same LDS plan as
+// k_gemm_mfma_k64a3 (64-k stages, three A slots, two B slots, 8-row x 128-byte copies, chunk swizzle).
+//
+// A stage is two k-steps of 32; a k-step is TM x TN matrix instructions, A block outer, B block inner.  Fragment
+// registers: one 16-row A fragment per A block (reloaded for the next k-step as soon as the block's instructions
+// are done), B fragments double-buffered by k-step.  So every read of a stage's own data has been issued when
+// its second k-step starts; the stage's barrier sits after that k-step's second A block, and everything read
+// after it belongs to the next stage.  B's copies of stage t+2 follow the barrier, A's go out during the first
+// k-step into the slot the previous stage freed.
+//
+// Accumulators hold the transposed product (weight fragment first): register quad = 4 consecutive output columns
+// of row lane % 16, columns (lane / 16) * 4.. of the 16 x 16 block.  The hardware-add epilogue keeps the
+// untransposed product (column lane % 16, rows (lane / 16) * 4..).
+// scheduling hint "then n LDS reads" for an n known after unrolling (the builtin wants literals)
+__device__ __forceinline__ void sched_ds_reads(int n) {
+  if (n == 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+  else if (n == 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+  else if (n == 3) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+  else if (n == 4) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+  else if (n == 5) __builtin_amdgcn_sched_group_barrier(0x100, 5, 0);
+}
+
+template <int EPI, int TM, int TN, int WTM, int WTN>
+__device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, f32x4_t (&acc)[TM][TN], int m0, int n0, int wm, int wn, int lane,
+                                                bf16x8_t* stage) {
+  const int mr = lane & 15, gq = lane >> 4;
+  if constexpr (EPI == kEpiResAtomic) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int col = n0 + wn * WTN + j * 16 + mr;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = m0 + wm * WTM + i * 16 + gq * 4 + r;
+          // fire-and-forget hardware add at the L2; each element receives exactly one addend per launch
+          if (row < g.M) unsafeAtomicAdd(&((float*)g.C)[(int64_t)row * g.ldc + col], acc[i][j][r]);
+        }
+      }
+  } else if constexpr (EPI == FASTAV_EPI_STORE || EPI == FASTAV_EPI_SWIGLU) {
+    // bf16 output.  SwiGLU: B rows come in groups of 64 = 32 gate rows, then 32 up rows -> of four 16-blocks
+    // j = 4u .. 4u + 3 the output blocks are (gate 4u, up 4u + 2) and (gate 4u + 1, up 4u + 3).
+    constexpr int NB = (EPI == FASTAV_EPI_SWIGLU) ? TN / 2 : TN;     // output blocks (16 columns) per row of the wave
+    constexpr int NCH = NB * 2;                                      // 16-byte chunks per output row
+    constexpr int RPI = 64 / NCH;                                    // rows per 64-lane access
+    constexpr int SWM = NCH >= 8 ? 7 : NCH - 1;
+    static_assert(NCH == 4 || NCH == 8 || NCH == 16, "wave tile width");
+    const int colw = (EPI == FASTAV_EPI_SWIGLU) ? n0 + wn * (WTN / 2) : n0 + wn * WTN;
+    const bool vec = g.vec_ok != 0;
+    typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int jb = 0; jb < NB; ++jb) {
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          if constexpr (EPI == FASTAV_EPI_SWIGLU) {
+            const int jg = (jb / 2) * 4 + (jb & 1);
+            const float gt = acc[i][jg][r], up = acc[i][jg + 2][r];
+            v[r] = gt / (1.0f + __expf(-gt)) * up;
+          } else {
+            v[r] = acc[i][jb][r];
+          }
+        }
+        if (vec) {
+          // 8-byte piece: columns jb * 16 + gq * 4 .. + 3 of row mr -> chunk jb * 2 + gq / 2, half gq & 1
+          const u32x2_t pc = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+          const int c = jb * 2 + (gq >> 1);
+          *(u32x2_t*)((char*)&stage[mr * NCH + (c ^ ((mr >> 1) & SWM))] + (gq & 1) * 8) = pc;
+        } else {
+          const int row = m0 + wm * WTM + i * 16 + mr;
+          if (row < g.M) {
+            bf16_t* C = (bf16_t*)g.C + (int64_t)row * g.ldc + colw + jb * 16 + gq * 4;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) C[r] = (bf16_t)v[r];
+          }
+        }
+      }
+      if (vec) {
+        // the wave's own LDS accesses execute in order: rows are read back whole, 16 bytes per lane
+        const int rr = lane / NCH, cc = lane % NCH;
+#pragma unroll
+        for (int it = 0; it < 16 / RPI; ++it) {
+          const int r = it * RPI + rr;
+          const u32x4_t val = *(const u32x4_t*)&stage[r * NCH + (cc ^ ((r >> 1) & SWM))];
+          const int row = m0 + wm * WTM + i * 16 + r;
+          if (row < g.M) *(u32x4_t*)((bf16_t*)g.C + (int64_t)row * g.ldc + colw + cc * 8) = val;
+        }
+      }
+    }
+  } else {
+    // fp32 output (residual read-modify-write, split-K partial): 16-byte pieces, TN * 4 of them per row
+    constexpr int NC = TN * 4, RP = 64 / NC;
+    static_assert(NC == 16 || NC == 32, "wave tile width");
+    const bool vec = g.vec_ok != 0;
+    float* Cb = (EPI == kEpiPartial) ? g.partial + (int64_t)blockIdx.y * g.M * g.N + n0 + wn * WTN : (float*)g.C + n0 + wn * WTN;
+    const int64_t pitch = (EPI == kEpiPartial) ? g.N : g.ldc;
+    f32x4_t* st = (f32x4_t*)stage;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      if (vec) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) st[mr * NC + ((j * 4 + gq) ^ (mr & 7))] = acc[i][j];
+        const int rr = lane / NC, cc = lane % NC;
+        f32x4_t old[16 / RP];
+        if constexpr (EPI == FASTAV_EPI_RESADD) {
+#pragma unroll
+          for (int it = 0; it < 16 / RP; ++it) {
+            const int row = m0 + wm * WTM + i * 16 + it * RP + rr;
+            old[it] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            if (row < g.M) old[it] = *(const f32x4_t*)(Cb + (int64_t)row * pitch + cc * 4);
+          }
+        }
+#pragma unroll
+        for (int it = 0; it < 16 / RP; ++it) {
+          const int r = it * RP + rr;
+          f32x4_t val = st[r * NC + (cc ^ (r & 7))];
+          if constexpr (EPI == FASTAV_EPI_RESADD) { val[0] += old[it][0]; val[1] += old[it][1]; val[2] += old[it][2]; val[3] += old[it][3]; }
+          const int row = m0 + wm * WTM + i * 16 + r;
+          if (row < g.M) *(f32x4_t*)(Cb + (int64_t)row * pitch + cc * 4) = val;
+        }
+      } else {
+        const int row = m0 + wm * WTM + i * 16 + mr;
+        if (row < g.M) {
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              float* C = Cb + (int64_t)row * pitch + j * 16 + gq * 4 + r;
+              if constexpr (EPI == FASTAV_EPI_RESADD) *C += acc[i][j][r];
+              else *C = acc[i][j][r];
+            }
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WM, int WN, int EPI>
+__global__ __launch_bounds__(WM * WN * 64, 1) void k_gemm_mfma16(GemmArgs g) {
+  constexpr int NW = WM * WN;                          // waves
+  constexpr int WTM = BM / WM, WTN = BN / WN;          // wave tile
+  constexpr int TM = WTM / 16, TN = WTN / 16;          // 16x16 blocks per wave
+  constexpr int A_D = BM / (8 * NW), B_D = BN / (8 * NW);     // copy instructions per wave and stage (8 rows each)
+  constexpr int D = A_D + B_D;
+  constexpr int OUT_BN = (EPI == FASTAV_EPI_SWIGLU) ? BN / 2 : BN;
+  static_assert(A_D >= 1 && B_D >= 1 && TM >= 4 && TN >= 4 && TN % 4 == 0, "tile shape");
+  extern __shared__ bf16x8_t lds[];                    // [3][BM*8] A, then [2][BN*8] B
+
+  // ---- tile assignment (as in k_gemm_mfma)
+  const int nblk = g.tiles_m * g.tiles_n;
+  int pid = blockIdx.x;
+  {
+    const int per = nblk / 8, rem = nblk % 8, xcd = pid % 8, idx = pid / 8;
+    pid = xcd * per + (xcd < rem ? xcd : rem) + idx;
+  }
+  const int kb = g.band;
+  const int band = pid / (kb * g.tiles_m);
+  const int bw = (g.tiles_n - band * kb < kb) ? g.tiles_n - band * kb : kb;   // columns in this band
+  const int inb = pid - band * kb * g.tiles_m;
+  const int tile_m = inb / bw, tile_n = band * kb + inb % bw;
+  const int m0 = tile_m * BM;
+  const int n0 = g.n_off + tile_n * OUT_BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int wm = wave / WN, wn = wave % WN;
+  const int K = g.K;
+  const int kt_all = K / 64;
+  const int kt0 = (int)((int64_t)kt_all * blockIdx.y / g.splits);
+  const int KT = (int)((int64_t)kt_all * (blockIdx.y + 1) / g.splits) - kt0;
+
+  const bf16_t* wbase = g.W[0];
+  int seg_start = 0;
+  if (EPI != FASTAV_EPI_SWIGLU) {
+    if (n0 >= g.seg_end[0]) { wbase = g.W[1]; seg_start = g.seg_end[0]; }
+    if (n0 >= g.seg_end[1]) { wbase = g.W[2]; seg_start = g.seg_end[1]; }
+  }
+
+  // ---- this wave's copies: instruction i covers tile rows [(i*NW + wave)*8, +8), lane = (row, 16-byte chunk)
+  const int drow = lane >> 3, dpos = lane & 7;
+  uint32_t a_vo[A_D], b_vo[B_D];                        // lane offsets in bytes
+  uint32_t a_dst[A_D], b_dst[B_D];                      // LDS byte address of the 8-row group in slot 0
+  u32x4_t a_rs, b_rs[B_D];
+  const uint32_t a_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
+  const uint32_t b_base = a_base + 3u * BM * 128u;
+  a_rs = make_rsrc(g.A + (int64_t)m0 * K + kt0 * 64);
+#pragma unroll
+  for (int i = 0; i < A_D; ++i) {
+    const int r0 = (i * NW + wave_u) * 8, row = r0 + drow;
+    int grow = m0 + row;
+    grow = grow < g.M ? grow : g.M - 1;                 // clamp: stay inside A, the epilogue masks the row
+    a_vo[i] = ((uint32_t)(grow - m0) * (uint32_t)K + (uint32_t)(dpos ^ ((row >> 1) & 7)) * 8u) * 2u;
+    a_dst[i] = a_base + (uint32_t)r0 * 128u;
+  }
+#pragma unroll
+  for (int i = 0; i < B_D; ++i) {
+    const int r0 = (i * NW + wave_u) * 8, row = r0 + drow;
+    if (EPI == FASTAV_EPI_SWIGLU) {
+      const int blk = r0 >> 5;                          // the 8 rows of a copy lie inside one 32-row block
+      b_rs[i] = make_rsrc(((blk & 1) ? g.W2 : g.W[0]) + (int64_t)(n0 + (blk >> 1) * 32) * K + kt0 * 64);
+      b_vo[i] = ((uint32_t)(row & 31) * (uint32_t)K + (uint32_t)(dpos ^ ((row >> 1) & 7)) * 8u) * 2u;
+    } else {
+      b_rs[i] = make_rsrc(wbase + (int64_t)(n0 - seg_start) * K + kt0 * 64);
+      b_vo[i] = ((uint32_t)row * (uint32_t)K + (uint32_t)(dpos ^ ((row >> 1) & 7)) * 8u) * 2u;
+    }
+    b_dst[i] = b_base + (uint32_t)r0 * 128u;
+  }
+  // copy number c of A (B) for stage t; past the last stage it is re-aimed at the last stage (nobody reads it)
+  auto dma_a = [&](int t, int c, uint32_t slot) __attribute__((always_inline)) {
+    dma16_buf(a_rs, a_vo[c], (uint32_t)((t < KT ? t : KT - 1) * 128), a_dst[c] + slot * (BM * 128u));
+  };
+  auto dma_b = [&](int t, int c, uint32_t slot) __attribute__((always_inline)) {
+    dma16_buf(b_rs[c], b_vo[c], (uint32_t)((t < KT ? t : KT - 1) * 128), b_dst[c] + slot * (BN * 128u));
+  };
+
+  f32x4_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  // operand fragment of a 16-row block for k-step s: row lane % 16, 16-byte chunk s * 4 + lane / 16
+  const int frow = lane & 15, fch = lane >> 4;
+  bf16x8_t af[TM], bfr[2][TN];
+  int a_fu[2], b_fu[2];                                 // fragment positions inside a slot (16-byte units) per k-step
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    a_fu[ks] = swz8(wm * WTM + frow, ks * 4 + fch);
+    b_fu[ks] = 3 * BM * 8 + swz8(wn * WTN + frow, ks * 4 + fch);
+  }
+  auto mfma_block = [&](int i, int ks) __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      acc[i][j] = gemm_transposed(EPI) ? __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[ks][j], af[i], acc[i][j], 0, 0, 0)
+                                       : __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[ks][j], acc[i][j], 0, 0, 0);
+    }
+  };
+  // One stage.  `as`, `bs`: this stage's slots (t mod 3, t mod 2).
+  constexpr int PB = (TN + TM / 2 - 1) / (TM / 2);       // B fragments read behind one A block (first half of a k-step)
+  constexpr int PA = (A_D + TM - 2) / (TM - 1);          // A copies issued behind one A block of the first k-step
+  constexpr int PC = (B_D + TM - 3) / (TM - 2);          // B copies issued behind one A block after the barrier
+  auto stage = [&](int t, uint32_t as, uint32_t bs) __attribute__((always_inline)) {
+    const uint32_t as2 = as >= 1u ? as - 1u : 2u;        // (t + 2) mod 3
+    const uint32_t as1 = as == 2u ? 0u : as + 1u;        // (t + 1) mod 3
+    // k-step 0: after A block i is done its register takes the block's k-step-1 fragment; B's k-step-1 fragments
+    // are read behind the first blocks; A's copies of stage t+2 go out behind blocks 1, 2, ...
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      mfma_block(i, 0);
+      af[i] = lds[a_fu[1] + (int)as * BM * 8 + i * 128];
+      int nrd = 1;
+#pragma unroll
+      for (int j = i * PB; j < (i + 1) * PB && j < TN; ++j) { bfr[1][j] = lds[b_fu[1] + (int)bs * BN * 8 + j * 128]; ++nrd; }
+      __builtin_amdgcn_sched_group_barrier(0x008, TN, 0);
+      sched_ds_reads(nrd);
+      if (i >= 1 && (i - 1) * PA < A_D) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int c = (i - 1) * PA; c < i * PA && c < A_D; ++c) dma_a(t + 2, c, as2);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    // k-step 1: two blocks, then - every fragment of this stage is in registers, stage t+1 has landed - the
+    // barrier; from there on the freed registers take the next stage's k-step-0 fragments and B's copies of
+    // stage t+2 go out into the slot this stage has finished with
+    mfma_block(0, 1);
+    mfma_block(1, 1);
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * TN, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    dma_wait_keep<A_D>();                                // stage t+1 has landed; only A of stage t+2 may be in flight
+    asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");
+    __syncthreads();
+    af[0] = lds[a_fu[0] + (int)as1 * BM * 8];
+    af[1] = lds[a_fu[0] + (int)as1 * BM * 8 + 128];
+#pragma unroll
+    for (int i = 2; i < TM; ++i) {
+      mfma_block(i, 1);
+      af[i] = lds[a_fu[0] + (int)as1 * BM * 8 + i * 128];
+      int nrd = (i == 2) ? 3 : 1;
+#pragma unroll
+      for (int j = (i - 2) * PB; j < (i - 1) * PB && j < TN; ++j) { bfr[0][j] = lds[b_fu[0] + (int)(bs ^ 1u) * BN * 8 + j * 128]; ++nrd; }
+      __builtin_amdgcn_sched_group_barrier(0x008, TN, 0);
+      sched_ds_reads(nrd);
+      if ((i - 2) * PC < B_D) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int c = (i - 2) * PC; c < (i - 1) * PC && c < B_D; ++c) dma_b(t + 2, c, bs);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  };
+  static_assert(PB * (TM / 2) >= TN && PB * (TM - 2) >= TN && PA * (TM - 1) >= A_D && PC * (TM - 2) >= B_D, "schedule");
+
+  // ---- prologue: stages 0 and 1 in flight, stage 0 landed and published
+#pragma unroll
+  for (int c = 0; c < A_D; ++c) dma_a(0, c, 0u);
+#pragma unroll
+  for (int c = 0; c < B_D; ++c) dma_b(0, c, 0u);
+#pragma unroll
+  for (int c = 0; c < A_D; ++c) dma_a(1, c, 1u);
+#pragma unroll
+  for (int c = 0; c < B_D; ++c) dma_b(1, c, 1u);
+  dma_wait_keep<D>();
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < TM; ++i) af[i] = lds[a_fu[0] + i * 128];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) bfr[0][j] = lds[b_fu[0] + j * 128];
+
+  int t = 0;
+  for (; t + 6 <= KT; t += 6) {                          // t is a multiple of 6 here: slots are literals
+#pragma unroll
+    for (int u = 0; u < 6; ++u) stage(t + u, (uint32_t)(u % 3), (uint32_t)(u % 2));
+  }
+#pragma unroll 1
+  for (; t < KT; ++t) stage(t, (uint32_t)t % 3u, (uint32_t)t & 1u);
+  dma_wait_keep<0>();
+  __syncthreads();                                     // every wave's copies have landed: LDS is free for the epilogue
+  gemm16_epilogue<EPI, TM, TN, WTM, WTN>(g, acc, m0, n0, wm, wn, lane, lds + wave * (16 * 4 * TN));
+}
+
+template <int BM, int BN, int WM, int WN, int EPI>
+static fastav_status_t launch_cfg_16(GemmArgs g, int col0, int ncols, int splits, hipStream_t s) {
+  constexpr int OUT_BN = (EPI == FASTAV_EPI_SWIGLU) ? BN / 2 : BN;
+  g.tiles_m = (g.M + BM - 1) / BM;
+  g.tiles_n = ncols;
+  g.n_off = col0 * OUT_BN;
+  g.splits = splits;
+  g.band = (g.tiles_m * g.tiles_n > kNumCUs) ? 4 : 1;
+  const size_t shmem = (size_t)(3 * BM + 2 * BN) * 8 * sizeof(bf16x8_t);
+  hipError_t e = hipFuncSetAttribute((const void*)k_gemm_mfma16<BM, BN, WM, WN, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+  if (e != hipSuccess) return fail(FASTAV_EHIP, "gemm: hipFuncSetAttribute: %s", hipGetErrorString(e));
+  hipLaunchKernelGGL((k_gemm_mfma16<BM, BN, WM, WN, EPI>), dim3((unsigned)(g.tiles_m * g.tiles_n), (unsigned)splits),
+                     dim3(WM * WN * 64), shmem, s, g);
+  return check_launch("gemm_mfma16");
+}
+
 bool mfma_linear_supported(int64_t m, int n, int k, int epilogue, int dtype) {
   if (dtype != FASTAV_BF16 || m < 1 || m > 0x7FFFFFFF) return false;
   if (k % 64 != 0 || k < 128) return false;            // >= 4 stages of 32
@@ -883,12 +1225,9 @@ constexpr int kCUs = kNumCUs;
 template <int EPI>
 static fastav_status_t launch_big(const GemmArgs& g, int col0, int ncols, int64_t tiles, hipStream_t s) {
   if constexpr (EPI == FASTAV_EPI_RESADD) {
-    if (tiles >= 2 * kCUs) return launch_cfg_k64a3<256, 256, 2, 4, kEpiResAtomic>(g, col0, ncols, 1, s);
+    if (tiles >= 2 * kCUs) return launch_cfg_16<256, 256, 2, 4, kEpiResAtomic>(g, col0, ncols, 1, s);
   }
-  // the gate/up epilogue pairs columns inside a wave, so four waves of 128 x 128 work as well as eight of
-  // 128 x 64 and read half as many fragments from LDS
-  if constexpr (EPI == FASTAV_EPI_SWIGLU) return launch_cfg_k64a3<256, 256, 2, 2, EPI>(g, col0, ncols, 1, s);
-  else return launch_cfg_k64a3<256, 256, 2, 4, EPI>(g, col0, ncols, 1, s);
+  return launch_cfg_16<256, 256, 2, 4, EPI>(g, col0, ncols, 1, s);
 }
 
 constexpr size_t kSplitKScratchBytes = (size_t)2 * kCUs * 256 * 256 * sizeof(float);   // <= 512 partial tiles
@@ -922,7 +1261,7 @@ static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, void* scratch, size_
       gp.vec_ok = ((uintptr_t)scratch % 16 == 0) ? 1 : 0;   // partial rows are N floats, N a multiple of 128
       // long K ranges: the 64-k kernel; short ones (an O projection cut in three) start and drain faster with
       // the 32-k ring, whose prologue is half as large
-      fastav_status_t st = (g.K / best >= 2048) ? launch_cfg_k64a3<256, 256, 2, 4, kEpiPartial>(gp, 0, tn, best, s)
+      fastav_status_t st = (g.K / best >= 2048) ? launch_cfg_16<256, 256, 2, 4, kEpiPartial>(gp, 0, tn, best, s)
                                                 : launch_cfg<256, 256, 2, 4, kEpiPartial>(gp, 0, tn, best, s);
       if (st != FASTAV_OK) return st;
       const int64_t total = (int64_t)g.M * (g.N / 4);
