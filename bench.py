@@ -321,7 +321,7 @@ def main():
         "unpruned_ms_per_step_median": float(np.median(per_plain)), "unpruned_ms_per_step_min": float(np.min(per_plain)),
         "pruned_over_unpruned": s_plain / s_pruned,
         "prune_steps_us_per_prefill": prune_us,
-        "roofline": {"kernel": "k_gemm_mfma_k64a3<SwiGLU> (gate/up projection)", "bound": "mfma", "achieved": achieved,
+        "roofline": {"kernel": "k_gemm_mfma16<SwiGLU> (gate/up projection)", "bound": "mfma", "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": _recorded_traffic(args.workload),
                      "launches": n, "avg_launch_us": 1e3 * ms / max(n, 1)},
         "kernels": kernels,
