@@ -98,13 +98,25 @@ constexpr bool gemm_transposed(int epi) { return epi != kEpiResAtomic; }
 // and no other wave reads it): 16 rows of the wave's output width.  Aligned outputs pass through it - the lanes'
 // pieces are laid down row by row and read back so that a global access covers whole rows of the wave's tile
 // (full 128-byte lines: a quarter of the L2 requests of storing the pieces as the accumulators hold them).
-// scheduling hint "then n LDS reads" for an n known after unrolling (the builtin wants literals)
-__device__ __forceinline__ void sched_ds_reads(int n) {
-  if (n == 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-  else if (n == 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-  else if (n == 3) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
-  else if (n == 4) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-  else if (n == 5) __builtin_amdgcn_sched_group_barrier(0x100, 5, 0);
+// Scheduling hint for one A block: its `nmfma` matrix instructions with `nrd` LDS reads behind the first ones,
+// one read per matrix instruction (+1-2 % over all reads after the block).  Counts are known after unrolling;
+// the builtin wants literals.
+__device__ __forceinline__ void sched_block(int nmfma, int nrd) {
+#pragma unroll
+  for (int r = 0; r < 8; ++r)
+    if (r < nrd && r < nmfma) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+  const int rest = nmfma - nrd;
+  if (rest == 1) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+  else if (rest == 2) __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+  else if (rest == 3) __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
+  else if (rest == 4) __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+  else if (rest == 5) __builtin_amdgcn_sched_group_barrier(0x008, 5, 0);
+  else if (rest == 6) __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
+  else if (rest >= 7) __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
+  if (nrd > nmfma) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
 }
 
 template <int EPI, int TM, int TN, int WTM, int WTN>
@@ -340,8 +352,7 @@ __global__ __launch_bounds__(WM * WN * 64, (3 * BM + 2 * BN) * 128 <= 80 * 1024 
       int nrd = 1;
 #pragma unroll
       for (int j = i * PB; j < (i + 1) * PB && j < TN; ++j) { bfr[1][j] = lds[b_fu[1] + (int)bs * BN * 8 + j * 128]; ++nrd; }
-      __builtin_amdgcn_sched_group_barrier(0x008, TN, 0);
-      sched_ds_reads(nrd);
+      sched_block(TN, nrd);
       if (i >= 1 && (i - 1) * PA < A_D) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -368,8 +379,7 @@ __global__ __launch_bounds__(WM * WN * 64, (3 * BM + 2 * BN) * 128 <= 80 * 1024 
       int nrd = (i == 2) ? 3 : 1;
 #pragma unroll
       for (int j = (i - 2) * PB; j < (i - 1) * PB && j < TN; ++j) { bfr[0][j] = lds[b_fu[0] + (int)(bs ^ 1u) * BN * 8 + j * 128]; ++nrd; }
-      __builtin_amdgcn_sched_group_barrier(0x008, TN, 0);
-      sched_ds_reads(nrd);
+      sched_block(TN, nrd);
       if ((i - 2) * PC < B_D) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
