@@ -168,7 +168,11 @@ LINEAR_SHAPES = [("f32", 100, 688, 256), ("f32", 37, 256, 688), ("bf16", 100, 20
                  ("bf16", 3000, 8192, 256),       # 384 big tiles = 1.5 rounds
                  ("bf16", 2458, 4608, 192),       # SwiGLU: 360 big tiles = 1.4 rounds
                  ("bf16", 1721, 2816, 320),       # 77 tiles; SwiGLU has 154
-                 ("bf16", 8200, 4096, 256)]       # 33 x 16 = 528 big tiles: several rounds (hardware-add residual epilogue)
+                 ("bf16", 8200, 4096, 256),       # 33 x 16 = 528 big tiles: several rounds (hardware-add residual epilogue)
+                 ("bf16", 300, 512, 128),         # two 64-k stages: the shortest pipeline
+                 ("bf16", 1, 1024, 320),          # one row; five stages (the unrolled loop's remainder path only)
+                 ("bf16", 257, 256, 448),         # one row past a tile; seven stages (unrolled loop + remainder)
+                 ("bf16", 5000, 14336, 128)]      # 20 x 56 = 1120 big tiles of two stages each: rounds + tail columns
 
 
 @pytest.mark.parametrize("dtype,M,N,K", LINEAR_SHAPES)
