@@ -236,8 +236,12 @@ __device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, f32x4_t (&acc
   }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI>
-__global__ __launch_bounds__(WM * WN * 64, (3 * BM + 2 * BN) * 128 <= 80 * 1024 ? 2 : 1) void k_gemm_mfma16(GemmArgs g) {
+template <int BM, int BN, int WM, int WN, int EPI, bool W3 = true>
+__global__ __launch_bounds__(WM * WN * 64, ((W3 ? 2 : 3) * BM + (W3 ? 3 : 2) * BN) * 128 <= 80 * 1024 ? 2 : 1) void k_gemm_mfma16(GemmArgs g) {
+  // W3: the weights (B) get the three slots and the early copies, the activations (A) the two slots and the copies
+  // behind the barrier.  In a model's forward pass the weights always come from HBM (they are far larger than the
+  // memory-side cache) and need the longer lead; the activations were written by the previous kernel.
+  constexpr int NSA = W3 ? 2 : 3, NSB = W3 ? 3 : 2;    // LDS slots per operand
   constexpr int NW = WM * WN;                          // waves
   constexpr int WTM = BM / WM, WTN = BN / WN;          // wave tile
   constexpr int TM = WTM / 16, TN = WTN / 16;          // 16x16 blocks per wave
@@ -245,7 +249,7 @@ __global__ __launch_bounds__(WM * WN * 64, (3 * BM + 2 * BN) * 128 <= 80 * 1024 
   constexpr int D = A_D + B_D;
   constexpr int OUT_BN = (EPI == FASTAV_EPI_SWIGLU) ? BN / 2 : BN;
   static_assert(A_D >= 1 && B_D >= 1 && TM >= 4 && TN >= 4 && TN % 4 == 0, "tile shape");
-  extern __shared__ bf16x8_t lds[];                    // [3][BM*8] A, then [2][BN*8] B
+  extern __shared__ bf16x8_t lds[];                    // [NSA][BM*8] A, then [NSB][BN*8] B
 
   // ---- tile assignment: XCD-contiguous, banded
   const int nblk = g.tiles_m * g.tiles_n;
@@ -283,7 +287,7 @@ __global__ __launch_bounds__(WM * WN * 64, (3 * BM + 2 * BN) * 128 <= 80 * 1024 
   uint32_t a_dst[A_D], b_dst[B_D];                      // LDS byte address of the 8-row group in slot 0
   u32x4_t a_rs, b_rs[B_D];
   const uint32_t a_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
-  const uint32_t b_base = a_base + 3u * BM * 128u;
+  const uint32_t b_base = a_base + (uint32_t)NSA * BM * 128u;
   a_rs = make_rsrc(g.A + (int64_t)m0 * K + kt0 * 64);
 #pragma unroll
   for (int i = 0; i < A_D; ++i) {
@@ -327,7 +331,7 @@ __global__ __launch_bounds__(WM * WN * 64, (3 * BM + 2 * BN) * 128 <= 80 * 1024 
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) {
     a_fu[ks] = swz8(wm * WTM + frow, ks * 4 + fch);
-    b_fu[ks] = 3 * BM * 8 + swz8(wn * WTN + frow, ks * 4 + fch);
+    b_fu[ks] = NSA * BM * 8 + swz8(wn * WTN + frow, ks * 4 + fch);
   }
   auto mfma_block = [&](int i, int ks) __attribute__((always_inline)) {
 #pragma unroll
@@ -336,15 +340,18 @@ __global__ __launch_bounds__(WM * WN * 64, (3 * BM + 2 * BN) * 128 <= 80 * 1024 
                                        : __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[ks][j], acc[i][j], 0, 0, 0);
     }
   };
-  // One stage.  `as`, `bs`: this stage's slots (t mod 3, t mod 2).
+  // One stage.  `as`, `bs`: this stage's slots (t mod NSA, t mod NSB).  The operand with three slots ("early") has
+  // its copies of stage t+2 issued during the first k-step, into the slot the previous stage freed; the operand
+  // with two slots ("late") behind the barrier, into the slot this stage has just finished with.
   constexpr int PB = (TN + TM / 2 - 1) / (TM / 2);       // B fragments read behind one A block (first half of a k-step)
-  constexpr int PA = (A_D + TM - 2) / (TM - 1);          // A copies issued behind one A block of the first k-step
-  constexpr int PC = (B_D + TM - 3) / (TM - 2);          // B copies issued behind one A block after the barrier
+  constexpr int E_D = W3 ? B_D : A_D, L_D = W3 ? A_D : B_D;
+  constexpr int PE = (E_D + TM - 2) / (TM - 1);          // early copies issued behind one A block of the first k-step
+  constexpr int PL = (L_D + TM - 3) / (TM - 2);          // late copies issued behind one A block after the barrier
   auto stage = [&](int t, uint32_t as, uint32_t bs) __attribute__((always_inline)) {
-    const uint32_t as2 = as >= 1u ? as - 1u : 2u;        // (t + 2) mod 3
-    const uint32_t as1 = as == 2u ? 0u : as + 1u;        // (t + 1) mod 3
+    const uint32_t as1 = (as + 1u) % (uint32_t)NSA, bs1 = (bs + 1u) % (uint32_t)NSB;   // next stage's slots
+    const uint32_t es2 = ((W3 ? bs : as) + 2u) % 3u;     // early operand's slot of stage t+2
     // k-step 0: after A block i is done its register takes the block's k-step-1 fragment; B's k-step-1 fragments
-    // are read behind the first blocks; A's copies of stage t+2 go out behind blocks 1, 2, ...
+    // are read behind the first blocks; the early copies go out behind blocks 1, 2, ...
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       mfma_block(i, 0);
@@ -353,21 +360,24 @@ __global__ __launch_bounds__(WM * WN * 64, (3 * BM + 2 * BN) * 128 <= 80 * 1024 
 #pragma unroll
       for (int j = i * PB; j < (i + 1) * PB && j < TN; ++j) { bfr[1][j] = lds[b_fu[1] + (int)bs * BN * 8 + j * 128]; ++nrd; }
       sched_block(TN, nrd);
-      if (i >= 1 && (i - 1) * PA < A_D) {
+      if (i >= 1 && (i - 1) * PE < E_D) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int c = (i - 1) * PA; c < i * PA && c < A_D; ++c) dma_a(t + 2, c, as2);
+        for (int c = (i - 1) * PE; c < i * PE && c < E_D; ++c) {
+          if (W3) dma_b(t + 2, c < B_D ? c : 0, es2);
+          else dma_a(t + 2, c < A_D ? c : 0, es2);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
     // k-step 1: two blocks, then - every fragment of this stage is in registers, stage t+1 has landed - the
-    // barrier; from there on the freed registers take the next stage's k-step-0 fragments and B's copies of
-    // stage t+2 go out into the slot this stage has finished with
+    // barrier; from there on the freed registers take the next stage's k-step-0 fragments and the late copies of
+    // stage t+2 go out
     mfma_block(0, 1);
     mfma_block(1, 1);
     __builtin_amdgcn_sched_group_barrier(0x008, 2 * TN, 0);
     __builtin_amdgcn_sched_barrier(0);
-    dma_wait_keep<A_D>();                                // stage t+1 has landed; only A of stage t+2 may be in flight
+    dma_wait_keep<E_D>();                                // stage t+1 has landed; only the early copies of stage t+2 may be in flight
     asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");
     __syncthreads();
     af[0] = lds[a_fu[0] + (int)as1 * BM * 8];
@@ -378,17 +388,20 @@ __global__ __launch_bounds__(WM * WN * 64, (3 * BM + 2 * BN) * 128 <= 80 * 1024 
       af[i] = lds[a_fu[0] + (int)as1 * BM * 8 + i * 128];
       int nrd = (i == 2) ? 3 : 1;
 #pragma unroll
-      for (int j = (i - 2) * PB; j < (i - 1) * PB && j < TN; ++j) { bfr[0][j] = lds[b_fu[0] + (int)(bs ^ 1u) * BN * 8 + j * 128]; ++nrd; }
+      for (int j = (i - 2) * PB; j < (i - 1) * PB && j < TN; ++j) { bfr[0][j] = lds[b_fu[0] + (int)bs1 * BN * 8 + j * 128]; ++nrd; }
       sched_block(TN, nrd);
-      if ((i - 2) * PC < B_D) {
+      if ((i - 2) * PL < L_D) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int c = (i - 2) * PC; c < (i - 1) * PC && c < B_D; ++c) dma_b(t + 2, c, bs);
+        for (int c = (i - 2) * PL; c < (i - 1) * PL && c < L_D; ++c) {
+          if (W3) dma_a(t + 2, c < A_D ? c : 0, as);
+          else dma_b(t + 2, c < B_D ? c : 0, bs);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
   };
-  static_assert(PB * (TM / 2) >= TN && PB * (TM - 2) >= TN && PA * (TM - 1) >= A_D && PC * (TM - 2) >= B_D, "schedule");
+  static_assert(PB * (TM / 2) >= TN && PB * (TM - 2) >= TN && PE * (TM - 1) >= E_D && PL * (TM - 2) >= L_D, "schedule");
 
   // ---- prologue: stages 0 and 1 in flight, stage 0 landed and published
 #pragma unroll
@@ -409,16 +422,16 @@ __global__ __launch_bounds__(WM * WN * 64, (3 * BM + 2 * BN) * 128 <= 80 * 1024 
   int t = 0;
   for (; t + 6 <= KT; t += 6) {                          // t is a multiple of 6 here: slots are literals
 #pragma unroll
-    for (int u = 0; u < 6; ++u) stage(t + u, (uint32_t)(u % 3), (uint32_t)(u % 2));
+    for (int u = 0; u < 6; ++u) stage(t + u, (uint32_t)(u % NSA), (uint32_t)(u % NSB));
   }
 #pragma unroll 1
-  for (; t < KT; ++t) stage(t, (uint32_t)t % 3u, (uint32_t)t & 1u);
+  for (; t < KT; ++t) stage(t, (uint32_t)t % (uint32_t)NSA, (uint32_t)t % (uint32_t)NSB);
   dma_wait_keep<0>();
   __syncthreads();                                     // every wave's copies have landed: LDS is free for the epilogue
   gemm16_epilogue<EPI, TM, TN, WTM, WTN>(g, acc, m0, n0, wm, wn, lane, lds + wave * (16 * 4 * TN));
 }
 
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int WM, int WN, int EPI, bool W3 = true>
 static fastav_status_t launch_cfg_16(GemmArgs g, int col0, int ncols, int splits, hipStream_t s) {
   constexpr int OUT_BN = (EPI == FASTAV_EPI_SWIGLU) ? BN / 2 : BN;
   g.tiles_m = (g.M + BM - 1) / BM;
@@ -426,10 +439,10 @@ static fastav_status_t launch_cfg_16(GemmArgs g, int col0, int ncols, int splits
   g.n_off = col0 * OUT_BN;
   g.splits = splits;
   g.band = (g.tiles_m * g.tiles_n > kNumCUs) ? 4 : 1;
-  const size_t shmem = (size_t)(3 * BM + 2 * BN) * 8 * sizeof(bf16x8_t);
-  hipError_t e = hipFuncSetAttribute((const void*)k_gemm_mfma16<BM, BN, WM, WN, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+  const size_t shmem = (size_t)((W3 ? 2 : 3) * BM + (W3 ? 3 : 2) * BN) * 8 * sizeof(bf16x8_t);
+  hipError_t e = hipFuncSetAttribute((const void*)k_gemm_mfma16<BM, BN, WM, WN, EPI, W3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
   if (e != hipSuccess) return fail(FASTAV_EHIP, "gemm: hipFuncSetAttribute: %s", hipGetErrorString(e));
-  hipLaunchKernelGGL((k_gemm_mfma16<BM, BN, WM, WN, EPI>), dim3((unsigned)(g.tiles_m * g.tiles_n), (unsigned)splits),
+  hipLaunchKernelGGL((k_gemm_mfma16<BM, BN, WM, WN, EPI, W3>), dim3((unsigned)(g.tiles_m * g.tiles_n), (unsigned)splits),
                      dim3(WM * WN * 64), shmem, s, g);
   return check_launch("gemm_mfma16");
 }
