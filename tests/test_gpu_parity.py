@@ -169,6 +169,7 @@ LINEAR_SHAPES = [("f32", 100, 688, 256), ("f32", 37, 256, 688), ("bf16", 100, 20
                  ("bf16", 2458, 4608, 192),       # SwiGLU: 360 big tiles = 1.4 rounds
                  ("bf16", 1721, 2816, 320),       # 77 tiles; SwiGLU has 154
                  ("bf16", 8200, 4096, 256),       # 33 x 16 = 528 big tiles: several rounds (hardware-add residual epilogue)
+                 ("bf16", 2458, 4096, 512),       # residual epilogue: 208 tiles of 192 rows instead of 160 of 256
                  ("bf16", 300, 512, 128),         # two 64-k stages: the shortest pipeline
                  ("bf16", 1, 1024, 320),          # one row; five stages (the unrolled loop's remainder path only)
                  ("bf16", 257, 256, 448),         # one row past a tile; seven stages (unrolled loop + remainder)
