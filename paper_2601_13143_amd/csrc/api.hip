@@ -33,8 +33,8 @@ fastav_status_t launch_linear_generic(const void* a, const void* w, const void* 
                                       int n, int k, int epilogue, int dtype, hipStream_t s);
 bool mfma_linear_supported(int64_t m, int n, int k, int epilogue, int dtype);
 fastav_status_t launch_linear_mfma(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
-                                   const void* w2, void* c, int64_t ldc, int64_t m, int n, int k, int epilogue,
-                                   void* scratch, size_t scratch_bytes, hipStream_t s);
+                                   const void* w2, void* c, int64_t ldc, void* const* c_seg, const int64_t* ldc_seg,
+                                   int64_t m, int n, int k, int epilogue, void* scratch, size_t scratch_bytes, hipStream_t s);
 size_t mfma_linear_scratch_bytes();
 fastav_status_t launch_attention_generic(const void* q, int64_t q_stride, const void* k, const void* v,
                                          int64_t kv_stride, void* o, int64_t o_stride, const int32_t* cu, int batch,
@@ -72,15 +72,19 @@ fastav_status_t launch_rollout_cutoff(const float* rt, int n, const uint8_t* pro
 fastav_status_t launch_rollout_step(float* rt, void* rt16, const void* a16, float* c, int n, float alpha,
                                     void* linear_ws, size_t linear_ws_bytes, hipStream_t s);
 
-// One linear layer whose weight rows may come from up to three matrices stacked along N (Q|K|V).
+// One linear layer whose weight rows may come from up to three matrices stacked along N (Q|K|V).  With c_seg the
+// output columns of segment i go to their own matrix c_seg[i] (row pitch ldc_seg[i] elements) instead of columns
+// of c (plain-store epilogue only).
 static fastav_status_t linear_segments(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
                                        const void* w2, void* c, int64_t ldc, int64_t m, int k, int epilogue, int dtype,
-                                       void* scratch, size_t scratch_bytes, hipStream_t s) {
+                                       void* scratch, size_t scratch_bytes, hipStream_t s,
+                                       void* const* c_seg = nullptr, const int64_t* ldc_seg = nullptr) {
   int n = 0;
   for (int i = 0; i < n_seg; ++i) n += seg_rows[i];
   if (m == 0 || n == 0) return FASTAV_OK;
   // a handful of rows (a decode step): stream the weights through the skinny kernel, which times itself
-  if (m <= FASTAV_MAX_DECODE_BATCH && skinny_linear_supported(m, n, k, dtype, ldc)) {
+  if (c_seg != nullptr && epilogue != FASTAV_EPI_STORE) return fail(FASTAV_EINVAL, "per-segment outputs need the plain-store epilogue");
+  if (c_seg == nullptr && m <= FASTAV_MAX_DECODE_BATCH && skinny_linear_supported(m, n, k, dtype, ldc)) {
     bool sk = (((uintptr_t)a | (uintptr_t)c) % 16) == 0;
     for (int i = 0; i < n_seg && sk; ++i) sk = seg_rows[i] % 16 == 0;
     if (sk) return launch_skinny_linear(a, w_seg, seg_rows, n_seg, w2, c, ldc, (int)m, n, k, epilogue, s);
@@ -90,12 +94,12 @@ static fastav_status_t linear_segments(const void* a, const void* const* w_seg, 
   ProfScope prof(kind, 2.0 * (double)m * n * k * (epilogue == FASTAV_EPI_SWIGLU ? 2.0 : 1.0), s);
   bool ok = mfma_linear_supported(m, n, k, epilogue, dtype);
   for (int i = 0; i < n_seg && ok; ++i) ok = mfma_linear_supported(m, seg_rows[i], k, epilogue, dtype);
-  if (ok) return launch_linear_mfma(a, w_seg, seg_rows, n_seg, w2, c, ldc, m, n, k, epilogue, scratch, scratch_bytes, s);
+  if (ok) return launch_linear_mfma(a, w_seg, seg_rows, n_seg, w2, c, ldc, c_seg, ldc_seg, m, n, k, epilogue, scratch, scratch_bytes, s);
   const size_t es = dtype == FASTAV_BF16 ? 2 : 4;
   int col = 0;
   for (int i = 0; i < n_seg; ++i) {
-    void* ci = epilogue == FASTAV_EPI_RESADD ? (void*)((float*)c + col) : (void*)((char*)c + (size_t)col * es);
-    fastav_status_t st = launch_linear_generic(a, w_seg[i], w2, ci, ldc, m, seg_rows[i], k, epilogue, dtype, s);
+    void* ci = c_seg ? c_seg[i] : epilogue == FASTAV_EPI_RESADD ? (void*)((float*)c + col) : (void*)((char*)c + (size_t)col * es);
+    fastav_status_t st = launch_linear_generic(a, w_seg[i], w2, ci, c_seg ? ldc_seg[i] : ldc, m, seg_rows[i], k, epilogue, dtype, s);
     if (st != FASTAV_OK) return st;
     col += seg_rows[i];
   }
@@ -454,20 +458,33 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
     const bool side = fine_scored && n_last == 1;
 
     FASTAV_TRY(launch_rmsnorm(resid[cur], W.g_attn, hn, Tl, m.hidden, m.rms_eps, m.dtype, s));
+    void* const k_out = out->kv_out ? out->kv_out[2 * l] : nullptr;
+    void* const v_out = out->kv_out ? out->kv_out[2 * l + 1] : nullptr;
+    // A layer that keeps all its tokens writes K and V straight into the caller's cache (the projection stores
+    // them there, RoPE and attention work on them there); a fine-prune layer keeps them in the workspace, from
+    // which only the surviving rows go to the cache.
+    const bool kv_direct = !fine && k_out != nullptr && v_out != nullptr && Tl > FASTAV_MAX_DECODE_BATCH;
+    const char* kptr = kv_direct ? (const char*)k_out : qkv + (size_t)qd * es;
+    const char* vptr = kv_direct ? (const char*)v_out : qkv + (size_t)(qd + kd) * es;
+    const int64_t kv_stride = kv_direct ? (int64_t)kd : qkv_stride;
     {
       const void* seg[3] = {W.wq, W.wk, W.wv};
       int rows[3] = {qd, kd, kd};
-      FASTAV_TRY(linear_segments(hn, seg, rows, 3, nullptr, qkv, qkv_stride, Tl, m.hidden, FASTAV_EPI_STORE, m.dtype, nullptr, 0, s));
+      void* cs[3] = {qkv, k_out, v_out};
+      const int64_t lds_[3] = {qkv_stride, (int64_t)kd, (int64_t)kd};
+      FASTAV_TRY(linear_segments(hn, seg, rows, 3, nullptr, qkv, qkv_stride, Tl, m.hidden, FASTAV_EPI_STORE, m.dtype, nullptr, 0, s,
+                                 kv_direct ? cs : nullptr, kv_direct ? lds_ : nullptr));
     }
-    FASTAV_TRY(launch_rope(qkv, qkv_stride, pos[cur], Tl, m.n_q_heads + m.n_kv_heads, m.head_dim, m.rope_base, m.dtype, s));
-    const char* kptr = qkv + (size_t)qd * es;
-    const char* vptr = qkv + (size_t)(qd + kd) * es;
-    FASTAV_TRY(launch_attention(qkv, qkv_stride, kptr, vptr, qkv_stride, attn[0], qd, cu_l, B, Tl, maxlen_stage[stage],
+    if (kv_direct) {
+      FASTAV_TRY(launch_rope(qkv, qkv_stride, pos[cur], Tl, m.n_q_heads, m.head_dim, m.rope_base, m.dtype, s));
+      FASTAV_TRY(launch_rope(k_out, kd, pos[cur], Tl, m.n_kv_heads, m.head_dim, m.rope_base, m.dtype, s));
+    } else {
+      FASTAV_TRY(launch_rope(qkv, qkv_stride, pos[cur], Tl, m.n_q_heads + m.n_kv_heads, m.head_dim, m.rope_base, m.dtype, s));
+    }
+    FASTAV_TRY(launch_attention(qkv, qkv_stride, kptr, vptr, kv_stride, attn[0], qd, cu_l, B, Tl, maxlen_stage[stage],
                                 m.n_q_heads, m.n_kv_heads, m.head_dim, side ? logits : nullptr, side ? ml : nullptr,
                                 m.dtype, attn_flops[stage], s));
     void* attn_cur = attn[0];
-    void* const k_out = out->kv_out ? out->kv_out[2 * l] : nullptr;
-    void* const v_out = out->kv_out ? out->kv_out[2 * l + 1] : nullptr;
     if (fine) {
       // ---- FINE prune: Eq. 4 scores of the last query row(s), top-k, compaction of everything later work reads
       float* sc = (out->prune_scores_out && out->prune_scores_out[pi]) ? out->prune_scores_out[pi] : scores_ws;
@@ -498,10 +515,10 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
       cur ^= 1; ++stage; ++pi;
       attn_cur = attn[1];
     } else {
-      // this layer's K and V rows go to the caller's cache in one launch
+      // this layer's K and V rows go to the caller's cache in one launch, unless they were produced there
       GatherTensor kvc[2] = {{kptr, k_out, k_out ? (int64_t)kd * (int64_t)es : 0, qkv_stride * (int64_t)es},
                              {vptr, v_out, v_out ? (int64_t)kd * (int64_t)es : 0, qkv_stride * (int64_t)es}};
-      if (k_out || v_out) FASTAV_TRY(launch_gather(kvc, 2, nullptr, Tl, s));
+      if (!kv_direct && (k_out || v_out)) FASTAV_TRY(launch_gather(kvc, 2, nullptr, Tl, s));
     }
     const int64_t To = T_stage[stage];
     FASTAV_TRY(launch_linear(attn_cur, W.wo, nullptr, resid[cur], To, m.hidden, qd, FASTAV_EPI_RESADD, m.dtype, gscr, ws.gemm_scratch_bytes, s));

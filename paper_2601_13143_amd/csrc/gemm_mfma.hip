@@ -44,6 +44,9 @@ struct GemmArgs {
   int n_off;               // first output column of this launch (a launch may cover a range of tile columns)
   int splits;              // split-K: blockIdx.y picks a K range and writes an fp32 partial tile to `partial`
   float* partial;          // [splits][M][N] fp32 (split-K only)
+  void* Cs[3];             // plain-store epilogue with seg_out: segment i of the output columns goes to its own matrix
+  int64_t ldcs[3];         //   Cs[i] (row pitch ldcs[i] elements) instead of columns of C
+  int seg_out;
   int vec_ok;              // the output (C, or `partial`) takes 16-byte accesses: base and row pitch are multiples of 16 bytes
 };
 
@@ -120,8 +123,8 @@ __device__ __forceinline__ void sched_block(int nmfma, int nrd) {
 }
 
 template <int EPI, int TM, int TN, int WTM, int WTN>
-__device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, f32x4_t (&acc)[TM][TN], int m0, int n0, int wm, int wn, int lane,
-                                                bf16x8_t* stage) {
+__device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, void* c_out, int64_t c_ld, f32x4_t (&acc)[TM][TN], int m0, int n0,
+                                                int wm, int wn, int lane, bf16x8_t* stage) {
   const int mr = lane & 15, gq = lane >> 4;
   if constexpr (EPI == kEpiResAtomic) {
 #pragma unroll
@@ -133,7 +136,7 @@ __device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, f32x4_t (&acc
         for (int r = 0; r < 4; ++r) {
           const int row = m0 + wm * WTM + i * 16 + gq * 4 + r;
           // fire-and-forget hardware add at the L2; each element receives exactly one addend per launch
-          if (row < g.M) unsafeAtomicAdd(&((float*)g.C)[(int64_t)row * g.ldc + col], acc[i][j][r]);
+          if (row < g.M) unsafeAtomicAdd(&((float*)c_out)[(int64_t)row * c_ld + col], acc[i][j][r]);
         }
       }
   } else if constexpr (EPI == FASTAV_EPI_STORE || EPI == FASTAV_EPI_SWIGLU) {
@@ -170,7 +173,7 @@ __device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, f32x4_t (&acc
         } else {
           const int row = m0 + wm * WTM + i * 16 + mr;
           if (row < g.M) {
-            bf16_t* C = (bf16_t*)g.C + (int64_t)row * g.ldc + colw + jb * 16 + gq * 4;
+            bf16_t* C = (bf16_t*)c_out + (int64_t)row * c_ld + colw + jb * 16 + gq * 4;
 #pragma unroll
             for (int r = 0; r < 4; ++r) C[r] = (bf16_t)v[r];
           }
@@ -184,7 +187,7 @@ __device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, f32x4_t (&acc
           const int r = it * RPI + rr;
           const u32x4_t val = *(const u32x4_t*)&stage[r * NCH + (cc ^ ((r >> 1) & SWM))];
           const int row = m0 + wm * WTM + i * 16 + r;
-          if (row < g.M) *(u32x4_t*)((bf16_t*)g.C + (int64_t)row * g.ldc + colw + cc * 8) = val;
+          if (row < g.M) *(u32x4_t*)((bf16_t*)c_out + (int64_t)row * c_ld + colw + cc * 8) = val;
         }
       }
     }
@@ -193,8 +196,8 @@ __device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, f32x4_t (&acc
     constexpr int NC = TN * 4, RP = 64 / NC;
     static_assert(NC == 16 || NC == 32, "wave tile width");
     const bool vec = g.vec_ok != 0;
-    float* Cb = (EPI == kEpiPartial) ? g.partial + (int64_t)blockIdx.y * g.M * g.N + n0 + wn * WTN : (float*)g.C + n0 + wn * WTN;
-    const int64_t pitch = (EPI == kEpiPartial) ? g.N : g.ldc;
+    float* Cb = (EPI == kEpiPartial) ? g.partial + (int64_t)blockIdx.y * g.M * g.N + n0 + wn * WTN : (float*)c_out + n0 + wn * WTN;
+    const int64_t pitch = (EPI == kEpiPartial) ? g.N : c_ld;
     f32x4_t* st = (f32x4_t*)stage;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -275,10 +278,10 @@ __global__ __launch_bounds__(WM * WN * 64, ((W3 ? 2 : 3) * BM + (W3 ? 3 : 2) * B
   const int KT = (int)((int64_t)kt_all * (blockIdx.y + 1) / g.splits) - kt0;
 
   const bf16_t* wbase = g.W[0];
-  int seg_start = 0;
+  int seg_start = 0, seg = 0;
   if (EPI != FASTAV_EPI_SWIGLU) {
-    if (n0 >= g.seg_end[0]) { wbase = g.W[1]; seg_start = g.seg_end[0]; }
-    if (n0 >= g.seg_end[1]) { wbase = g.W[2]; seg_start = g.seg_end[1]; }
+    if (n0 >= g.seg_end[0]) { wbase = g.W[1]; seg_start = g.seg_end[0]; seg = 1; }
+    if (n0 >= g.seg_end[1]) { wbase = g.W[2]; seg_start = g.seg_end[1]; seg = 2; }
   }
 
   // ---- this wave's copies: instruction i covers tile rows [(i*NW + wave)*8, +8), lane = (row, 16-byte chunk)
@@ -428,7 +431,11 @@ __global__ __launch_bounds__(WM * WN * 64, ((W3 ? 2 : 3) * BM + (W3 ? 3 : 2) * B
   for (; t < KT; ++t) stage(t, (uint32_t)t % (uint32_t)NSA, (uint32_t)t % (uint32_t)NSB);
   dma_wait_keep<0>();
   __syncthreads();                                     // every wave's copies have landed: LDS is free for the epilogue
-  gemm16_epilogue<EPI, TM, TN, WTM, WTN>(g, acc, m0, n0, wm, wn, lane, lds + wave * (16 * 4 * TN));
+  void* c_out = g.C;
+  int64_t c_ld = g.ldc;
+  int n0e = n0;
+  if (EPI == FASTAV_EPI_STORE && g.seg_out) { c_out = g.Cs[seg]; c_ld = g.ldcs[seg]; n0e = n0 - seg_start; }
+  gemm16_epilogue<EPI, TM, TN, WTM, WTN>(g, c_out, c_ld, acc, m0, n0e, wm, wn, lane, lds + wave * (16 * 4 * TN));
 }
 
 template <int BM, int BN, int WM, int WN, int EPI, bool W3 = true>
@@ -542,8 +549,8 @@ static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, void* scratch, size_
 }
 
 fastav_status_t launch_linear_mfma(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
-                                   const void* w2, void* c, int64_t ldc, int64_t m, int n, int k, int epilogue,
-                                   void* scratch, size_t scratch_bytes, hipStream_t s) {
+                                   const void* w2, void* c, int64_t ldc, void* const* c_seg, const int64_t* ldc_seg,
+                                   int64_t m, int n, int k, int epilogue, void* scratch, size_t scratch_bytes, hipStream_t s) {
   GemmArgs g;
   g.A = (const bf16_t*)a;
   int end = 0;
@@ -561,6 +568,17 @@ fastav_status_t launch_linear_mfma(const void* a, const void* const* w_seg, cons
   g.W2 = (const bf16_t*)w2;
   g.C = c; g.ldc = ldc; g.M = (int)m; g.N = n; g.K = k; g.n_off = 0; g.splits = 1; g.partial = nullptr;
   g.vec_ok = ((uintptr_t)c % 16 == 0 && ldc % (epilogue == FASTAV_EPI_RESADD ? 4 : 8) == 0) ? 1 : 0;
+  g.seg_out = 0;
+  for (int i = 0; i < 3; ++i) { g.Cs[i] = c; g.ldcs[i] = ldc; }
+  if (c_seg != nullptr) {
+    if (epilogue != FASTAV_EPI_STORE) return fail(FASTAV_EINVAL, "gemm: per-segment outputs need the plain-store epilogue");
+    g.seg_out = 1;
+    g.vec_ok = 1;
+    for (int i = 0; i < n_seg; ++i) {
+      g.Cs[i] = c_seg[i]; g.ldcs[i] = ldc_seg[i];
+      if ((uintptr_t)c_seg[i] % 16 != 0 || ldc_seg[i] % 8 != 0) g.vec_ok = 0;
+    }
+  }
   if (((uintptr_t)a | (uintptr_t)w_seg[0]) % 16) return fail(FASTAV_EINVAL, "gemm: A and W must be 16-byte aligned");
   if (epilogue == FASTAV_EPI_STORE) return launch_epi<FASTAV_EPI_STORE>(g, big_ok, scratch, scratch_bytes, s);
   if (epilogue == FASTAV_EPI_RESADD) return launch_epi<FASTAV_EPI_RESADD>(g, big_ok, scratch, scratch_bytes, s);
