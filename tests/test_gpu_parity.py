@@ -200,6 +200,32 @@ def test_linear(dtype, M, N, K, epi):
     assert_close(got, want, dtype, what=f"linear epi={epi}")
 
 
+def test_linear_seeded_random_shapes():
+    """Thirty seeded shapes around the tile, stage and row-block boundaries, every epilogue in turn."""
+    rng = np.random.default_rng(20260113)
+    for case in range(30):
+        M = int(rng.choice([1, 15, 16, 17, 127, 128, 129, 191, 192, 193, 255, 256, 257, 300, 511, 600]))
+        N = 128 * int(rng.choice([1, 2, 3, 5, 8]))
+        K = 64 * int(rng.choice([2, 3, 5, 6, 7, 8]))
+        epi = [fa.EPI_STORE, fa.EPI_RESADD, fa.EPI_SWIGLU][case % 3]
+        a = rng.standard_normal((M, K)).astype(np.float32)
+        w = (rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32)
+        w2 = (rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32)
+        fi.round_bf16(a); fi.round_bf16(w); fi.round_bf16(w2)
+        a64, w64, w264 = a.astype(np.float64), w.astype(np.float64), w2.astype(np.float64)
+        if epi == fa.EPI_STORE:
+            got, want = host(fa.fastav_linear(dev(a, "bf16"), dev(w, "bf16"))), a64 @ w64.T
+        elif epi == fa.EPI_RESADD:
+            r = rng.standard_normal((M, N)).astype(np.float32)
+            c = torch.from_numpy(r.copy()).cuda()
+            fa.fastav_linear(dev(a, "bf16"), dev(w, "bf16"), fa.EPI_RESADD, c=c)
+            got, want = host(c), r.astype(np.float64) + a64 @ w64.T
+        else:
+            got = host(fa.fastav_linear(dev(a, "bf16"), dev(w, "bf16"), fa.EPI_SWIGLU, w2=dev(w2, "bf16")))
+            want = orc.silu(a64 @ w64.T) * (a64 @ w264.T)
+        assert_close(got, want, "bf16", what=f"linear case {case}: M={M} N={N} K={K} epi={epi}")
+
+
 @pytest.mark.parametrize("epi", [fa.EPI_STORE, fa.EPI_RESADD, fa.EPI_SWIGLU])
 def test_linear_output_not_16_byte_aligned(epi):
     """An output that starts one element past a 16-byte boundary takes the element-wise store path."""
