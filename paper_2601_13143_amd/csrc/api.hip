@@ -476,8 +476,7 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
                                  kv_direct ? cs : nullptr, kv_direct ? lds_ : nullptr));
     }
     if (kv_direct) {
-      FASTAV_TRY(launch_rope(qkv, qkv_stride, pos[cur], Tl, m.n_q_heads, m.head_dim, m.rope_base, m.dtype, s));
-      FASTAV_TRY(launch_rope(k_out, kd, pos[cur], Tl, m.n_kv_heads, m.head_dim, m.rope_base, m.dtype, s));
+      FASTAV_TRY(launch_rope2(qkv, qkv_stride, m.n_q_heads, k_out, kd, m.n_kv_heads, pos[cur], Tl, m.head_dim, m.rope_base, m.dtype, s));
     } else {
       FASTAV_TRY(launch_rope(qkv, qkv_stride, pos[cur], Tl, m.n_q_heads + m.n_kv_heads, m.head_dim, m.rope_base, m.dtype, s));
     }

@@ -72,6 +72,9 @@ fastav_status_t launch_rmsnorm(const float* x, const void* g, void* y, int64_t r
                                hipStream_t s);
 fastav_status_t launch_rope(void* x, int64_t row_stride, const int32_t* pos, int64_t rows, int n_heads, int head_dim,
                             float base, int dtype, hipStream_t s);
+// the same over n_heads heads of x followed by n_heads2 heads of a second tensor (one launch)
+fastav_status_t launch_rope2(void* x, int64_t row_stride, int n_heads, void* x2, int64_t row_stride2, int n_heads2,
+                             const int32_t* pos, int64_t rows, int head_dim, float base, int dtype, hipStream_t s);
 // scratch (optional): device memory for split-K partial tiles; without it small-M residual GEMMs are not split
 fastav_status_t launch_linear(const void* a, const void* w, const void* w2, void* c, int64_t m, int n, int k,
                               int epilogue, int dtype, void* scratch, size_t scratch_bytes, hipStream_t s);

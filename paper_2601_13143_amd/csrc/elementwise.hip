@@ -140,10 +140,12 @@ fastav_status_t launch_rmsnorm(const float* x, const void* g, void* y, int64_t r
 // ---------------------------------------------------------------------------------------- rope
 // One workgroup per row.  Thread t < head_dim/2 owns frequency index i = t: it evaluates the angle
 // pos * base^(-2i/dh) once in fp64 (positions reach 16k+, where an fp32 angle loses ~1e-3 rad) and applies
-// the rotation to pair (i, i + dh/2) of every head.
+// the rotation to pair (i, i + dh/2) of every head: n_heads heads of x, then n_heads2 heads of a second tensor x2
+// (K living in a cache of its own).
 template <typename T>
-__global__ void k_rope(T* __restrict__ x, int64_t row_stride, const int32_t* __restrict__ pos, int n_heads,
-                       int head_dim, double neg_log2_base_2_over_dh) {
+__global__ void k_rope(T* __restrict__ x, int64_t row_stride, T* __restrict__ x2, int64_t row_stride2,
+                       const int32_t* __restrict__ pos, int n_heads, int n_heads2, int head_dim,
+                       double neg_log2_base_2_over_dh) {
   const int half = head_dim >> 1;
   const int i = threadIdx.x % half;
   const int h0 = threadIdx.x / half;
@@ -155,26 +157,35 @@ __global__ void k_rope(T* __restrict__ x, int64_t row_stride, const int32_t* __r
   sincos(ang, &sd, &cd);
   const float c = (float)cd, sn = (float)sd;
   T* xr = x + r * row_stride;
-  for (int h = h0; h < n_heads; h += hstep) {
-    T* p = xr + h * head_dim;
+  T* xr2 = x2 + r * row_stride2;
+  for (int h = h0; h < n_heads + n_heads2; h += hstep) {
+    T* p = h < n_heads ? xr + h * head_dim : xr2 + (h - n_heads) * head_dim;
     const float a = to_f32(p[i]), b = to_f32(p[i + half]);
     p[i] = from_f32<T>(a * c - b * sn);
     p[i + half] = from_f32<T>(b * c + a * sn);
   }
 }
 
-fastav_status_t launch_rope(void* x, int64_t row_stride, const int32_t* pos, int64_t rows, int n_heads, int head_dim,
-                            float base, int dtype, hipStream_t s) {
-  if (rows == 0 || n_heads == 0) return FASTAV_OK;
-  ProfScope prof(FASTAV_PROF_ROPE, 2.0 * rows * n_heads * head_dim * (dtype == FASTAV_BF16 ? 2.0 : 4.0), s);
+fastav_status_t launch_rope2(void* x, int64_t row_stride, int n_heads, void* x2, int64_t row_stride2, int n_heads2,
+                             const int32_t* pos, int64_t rows, int head_dim, float base, int dtype, hipStream_t s) {
+  const int nh = n_heads + n_heads2;
+  if (rows == 0 || nh == 0) return FASTAV_OK;
+  ProfScope prof(FASTAV_PROF_ROPE, 2.0 * rows * nh * head_dim * (dtype == FASTAV_BF16 ? 2.0 : 4.0), s);
   const int half = head_dim / 2;
-  int hpb = 256 / half; if (hpb < 1) hpb = 1; if (hpb > n_heads) hpb = n_heads;
+  int hpb = 256 / half; if (hpb < 1) hpb = 1; if (hpb > nh) hpb = nh;
   const double e = -log2((double)base) * 2.0 / (double)head_dim;
   if (dtype == FASTAV_BF16)
-    hipLaunchKernelGGL(k_rope<bf16_t>, dim3((unsigned)rows), dim3(half * hpb), 0, s, (bf16_t*)x, row_stride, pos, n_heads, head_dim, e);
+    hipLaunchKernelGGL(k_rope<bf16_t>, dim3((unsigned)rows), dim3(half * hpb), 0, s, (bf16_t*)x, row_stride, (bf16_t*)x2, row_stride2,
+                       pos, n_heads, n_heads2, head_dim, e);
   else
-    hipLaunchKernelGGL(k_rope<float>, dim3((unsigned)rows), dim3(half * hpb), 0, s, (float*)x, row_stride, pos, n_heads, head_dim, e);
+    hipLaunchKernelGGL(k_rope<float>, dim3((unsigned)rows), dim3(half * hpb), 0, s, (float*)x, row_stride, (float*)x2, row_stride2,
+                       pos, n_heads, n_heads2, head_dim, e);
   return check_launch("rope");
+}
+
+fastav_status_t launch_rope(void* x, int64_t row_stride, const int32_t* pos, int64_t rows, int n_heads, int head_dim,
+                            float base, int dtype, hipStream_t s) {
+  return launch_rope2(x, row_stride, n_heads, x, row_stride, 0, pos, rows, head_dim, base, dtype, s);
 }
 
 }  // namespace fastav
