@@ -198,7 +198,7 @@ def main():
     ap.add_argument("--no-kernel-passes", action="store_true", help="skip the per-kernel timing passes")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (the path is single-GPU by design; see DESIGN.md); "
+        print("bench.py: this build runs on ONE GPU (the path is single-GPU by design: no collectives, no sharding); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
