@@ -410,6 +410,27 @@ def test_prefill_small_bf16_ragged_batch():
         assert st[f"x_rel_l2_{b}"] <= 1e-2 and st[f"x_max_abs_over_rms_{b}"] <= 5e-2, st
 
 
+def test_prefill_kv_cache_written_in_place_or_not_is_the_same_forward():
+    """Layers without a fine prune produce K and V directly in the caller's cache; without a cache they stay in
+    the workspace.  Both must give the same forward, and the cache of the unpruned first layer the oracle's K, V."""
+    w, weights, x = _small_bf16()
+    dec = make_decoder(w.model, weights)
+    spans, offs = fi.span_table(w)
+    xd = dev(x, "bf16")
+    with_kv = dec.fastav_prefill(xd, fi.cu_seqlens(w), spans, offs, prune_tuples(w), 1, want_kv=True)
+    x_with, pos_with = with_kv["x_out"].clone(), with_kv["kept_pos"].clone()
+    k0, v0 = with_kv["kv"][0]
+    k0, v0 = host(k0), host(v0)
+    without = dec.fastav_prefill(xd, fi.cu_seqlens(w), spans, offs, prune_tuples(w), 1, want_kv=False)
+    torch.cuda.synchronize()
+    assert torch.equal(x_with, without["x_out"]) and torch.equal(pos_with, without["kept_pos"])
+    ref = orc.prefill(w, weights, x)
+    rk = np.concatenate([ref[b]["kv"][0][0] for b in range(len(ref))])
+    rv = np.concatenate([ref[b]["kv"][0][1] for b in range(len(ref))])
+    assert_close(k0.reshape(rk.shape), rk, "bf16", what="K layer 0")
+    assert_close(v0.reshape(rv.shape), rv, "bf16", what="V layer 0")
+
+
 def test_prefill_keep_ratio_one_is_the_unpruned_forward():
     w, weights, x = _small_bf16()
     dec = make_decoder(w.model, weights)
