@@ -144,11 +144,12 @@ def unpruned(w: Workload) -> Workload:
 
 
 def paper_schedule(w: Workload, global_keep: float = 0.6, fine_drop: float = 0.2) -> Workload:
-    """Same workload under the schedule the paper runs (Sec. 4, implementation details): one global prune at
-    the middle layer, then a fine prune at every layer after it, each dropping ``fine_drop`` (the paper's
-    P = 20 %) of the tokens that are left."""
+    """Same workload under the schedule the paper runs (Section 3.1, implementation details; Section 2.2, "Fine
+    pruning": at each layer following global pruning): one global prune on the input of the middle layer, then a
+    fine prune at the middle layer itself and at every layer after it, each dropping ``fine_drop`` (the paper's
+    P = 20 %) of the tokens that are left.  This is the placement that reproduces Table 4's FLOPs column."""
     mid = w.model.n_layers // 2
-    prunes = [Prune(mid, GLOBAL, global_keep)] + [Prune(l, FINE, 1.0 - fine_drop) for l in range(mid + 1, w.model.n_layers)]
+    prunes = [Prune(mid, GLOBAL, global_keep)] + [Prune(l, FINE, 1.0 - fine_drop) for l in range(mid, w.model.n_layers)]
     return Workload(w.name + "_paper_schedule", w.model, w.samples, prunes, w.n_last, w.seed, w.weight_seed)
 
 

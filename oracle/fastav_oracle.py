@@ -272,6 +272,23 @@ def causal_gqa_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, row_block:
     return out
 
 
+def causal_gqa_attention_rows(q: np.ndarray, k: np.ndarray, v: np.ndarray, rows: Sequence[int]) -> np.ndarray:
+    """The rows ``rows`` of causal_gqa_attention(q, k, v), each written out from the definition on its own:
+    row r of head h is softmax_j(q[r,h] . k[j,g(h)] / sqrt(dh), j <= r) applied to v[0..r, g(h)].  O(n) work per
+    row and head, so single rows of a long sequence can be checked without forming anything n x n.
+    -> [len(rows), Hq, dh]"""
+    n, Hq, dh = q.shape
+    G = Hq // k.shape[1]
+    scale = 1.0 / math.sqrt(dh)
+    out = np.empty((len(rows), Hq, dh), dtype=np.float64)
+    for i, r in enumerate(rows):
+        for h in range(Hq):
+            z = (k[: r + 1, h // G, :].astype(np.float64) @ q[r, h, :].astype(np.float64)) * scale
+            e = np.exp(z - z.max())
+            out[i, h, :] = (e / e.sum()) @ v[: r + 1, h // G, :].astype(np.float64)
+    return out
+
+
 def last_query_scores(q: np.ndarray, k: np.ndarray, n_last: int = 1) -> np.ndarray:
     """Eq. 4: s = mean over heads of softmax(Q_last K^T)  (readings R1, R2, R3, R10).
 

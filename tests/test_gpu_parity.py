@@ -473,13 +473,14 @@ def test_prefill_n_last_greater_than_one():
 
 
 def test_prefill_paper_schedule_fine_prune_at_every_later_layer():
-    """The schedule the paper runs (global prune at the middle layer, a 20 % fine prune at every layer after
-    it) on a small 8-layer model and a ragged batch: 1 + 3 prune steps' worth of kept sets against the oracle."""
+    """The schedule the paper runs (global prune on the input of the middle layer, a 20 % fine prune at that layer
+    and at every later one) on a small 8-layer model and a ragged batch: 1 + 4 prune steps' worth of kept sets
+    against the oracle."""
     m = fi.Model(8, 512, 8, 2, 128, 1024, 1.0e4, 1e-6, "bf16")
     base = fi.Workload("small8", m, [[(fi.VIDEO, 288), (fi.AUDIO, 150), (fi.TEXT, 30)], [(fi.VIDEO, 144), (fi.AUDIO, 97), (fi.TEXT, 9)]],
                        [], seed=43)
     w = fi.paper_schedule(base, global_keep=0.6, fine_drop=0.2)
-    assert [p.layer for p in w.prunes] == [4, 5, 6, 7] and w.prunes[0].kind == fi.GLOBAL
+    assert [(p.layer, p.kind) for p in w.prunes] == [(4, fi.GLOBAL)] + [(l, fi.FINE) for l in (4, 5, 6, 7)]
     weights = [fi.layer_weights(m, l, 9) for l in range(m.n_layers)]
     out, ref = _oracle_and_gpu(w, weights, fi.embeddings(w), want_kv=False)
     st = _check_prefill(w, out, ref)

@@ -34,6 +34,36 @@ def test_attention_matches_bruteforce(n, Hq, Hkv, dh):
     np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
 
 
+def test_attention_rows_match_bruteforce_and_closed_forms():
+    """The row-sampled form used for long sequences: chosen rows against the pure-loop brute force, against SDPA
+    on a longer sequence, and two closed forms (one dominant key -> that key's value; zero query -> running mean)."""
+    n, Hq, Hkv, dh = 19, 6, 2, 4
+    q, k, v = _rand_qkv(n, Hq, Hkv, dh, 77)
+    rows = [0, 1, 7, 18]
+    got = orc.causal_gqa_attention_rows(q, k, v, rows)
+    want = np.asarray(brute.attention_output(q.tolist(), k.tolist(), v.tolist(), Hq // Hkv))[rows]
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
+    n, Hq, Hkv, dh = 96, 8, 2, 16
+    q, k, v = _rand_qkv(n, Hq, Hkv, dh, 78)
+    tq = torch.from_numpy(q).permute(1, 0, 2)[None]
+    tk = torch.from_numpy(k).permute(1, 0, 2).repeat_interleave(Hq // Hkv, dim=0)[None]
+    tv = torch.from_numpy(v).permute(1, 0, 2).repeat_interleave(Hq // Hkv, dim=0)[None]
+    sdpa = F.scaled_dot_product_attention(tq, tk, tv, is_causal=True)[0].permute(1, 0, 2).numpy()
+    rows = [0, 5, 50, 95]
+    np.testing.assert_allclose(orc.causal_gqa_attention_rows(q, k, v, rows), sdpa[rows], rtol=1e-10, atol=1e-12)
+    # key 30 dominates every later row (its logit exceeds all others by > 700 * ln 2): the output is v[30]
+    kk = k.copy()
+    qq = np.abs(q) + 0.1
+    kk[30] = 1000.0
+    out = orc.causal_gqa_attention_rows(qq, kk, v, [29, 30, 60])
+    for h in range(Hq):
+        np.testing.assert_allclose(out[1, h], v[30, h // (Hq // Hkv)], rtol=1e-12)
+        np.testing.assert_allclose(out[2, h], v[30, h // (Hq // Hkv)], rtol=1e-12)
+        assert np.abs(out[0, h] - v[30, h // (Hq // Hkv)]).max() > 1e-3          # row 29 cannot see key 30
+    out0 = orc.causal_gqa_attention_rows(np.zeros_like(q), k, v, [9])
+    np.testing.assert_allclose(out0[0, 3], v[:10, 0].mean(axis=0), rtol=1e-12)
+
+
 @pytest.mark.parametrize("n_last", [1, 2, 5])
 def test_scores_equal_last_rows_of_head_mean_map(n_last):
     """Eq. 4 == last row(s) of the head-averaged full attention map A of Section 2.2."""
@@ -232,6 +262,31 @@ def test_table4_flops_fix_prune_placement():
         assert abs(rel(14, P / 100.0) - want) <= 1.0, (P, rel(14, P / 100.0), want)
     assert abs(rel(13, 0.0) - printed[0]) > 1.0 and abs(rel(15, 0.0) - printed[0]) > 1.0
     assert abs(rel(14, 0.2, compound=False) - printed[20]) > 1.0
+
+
+def test_paper_schedule_helper_reproduces_table4():
+    """The schedule helper the benchmark and the GPU parity test use (global prune on the input of the middle layer,
+    fine prunes from that layer on) gives Table 4's FLOPs column within +-1 point for P = 10 / 20 / 30 % on the
+    VideoLLaMA2-shaped sequence; starting the fine prunes one layer later misses P = 30 %."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "table4_flops.txt")) if l.strip() and not l.startswith("#")]
+    printed = {int(p): float(v) for p, v in rows}
+    L, d, mlp = 28, 3584, 18944
+    M, U, E = 676, 1496, 64
+    n = M + U + E
+    g = (M + 10 + E) / n
+    m = fi.Model(L, d, 28, 4, 128, mlp, 1.0e6, 1e-6, "bf16")
+    base_w = fi.Workload("vl2", m, [[(fi.VIDEO, M), (fi.AUDIO, U), (fi.TEXT, E)]], [])
+    base = orc.decoder_flops([n] * L, d, mlp)
+    for P in (10, 20, 30):
+        w = fi.paper_schedule(base_w, global_keep=g, fine_drop=P / 100.0)
+        assert w.prunes[0].kind == fi.GLOBAL and w.prunes[0].layer == 14
+        assert [(p.layer, p.kind) for p in w.prunes[1:]] == [(l, fi.FINE) for l in range(14, L)]
+        counts = orc.token_schedule(n, E, w.prunes, L)
+        got = 100.0 * orc.decoder_flops(counts, d, mlp) / base
+        assert abs(got - printed[P]) <= 1.0, (P, got, printed[P])
+    late = [fi.Prune(14, fi.GLOBAL, g)] + [fi.Prune(l, fi.FINE, 0.7) for l in range(15, L)]
+    got_late = 100.0 * orc.decoder_flops(orc.token_schedule(n, E, late, L), d, mlp) / base
+    assert abs(got_late - printed[30]) > 1.0, got_late
 
 
 # ---------------------------------------------------------------- the pruned prefill as a whole
