@@ -125,7 +125,7 @@ typedef struct {
 /* ---- host helpers (no GPU work) ------------------------------------------------------------------ */
 
 /* The keep-count rule: k = min(n, max(n_protected, ceil(keep_ratio*n - 1e-9))) in double precision
- * ("tokens with the lowest P% scores are removed", Section 2.2; keep_ratio = 1 - P).  Returns -1 on a
+ * (Section 2.2, "Fine pruning": the share P of lowest-scoring tokens goes; keep_ratio = 1 - P).  Returns -1 on a
  * bad argument (n < 0, ratio outside (0,1], n_protected outside [0,n]). */
 int64_t fastav_keep_count(int64_t n, double keep_ratio, int64_t n_protected);
 
@@ -175,8 +175,8 @@ fastav_status_t fastav_score(const fastav_model_t* model, const void* q, int64_t
                              int64_t total_tokens, int32_t max_seqlen, int32_t n_last, float* scores_out,
                              void* workspace, size_t workspace_bytes, void* stream);
 
-/* Top-k selection per sample plus stable compaction (Section 2.2: "tokens with the lowest P% scores are
- * removed").  For sample b, keeps every row whose protected_mask byte is non-zero and the
+/* Top-k selection per sample plus stable compaction (Section 2.2, "Fine pruning" / Eq. 4, and "Global
+ * pruning" for the positional form).  For sample b, keeps every row whose protected_mask byte is non-zero and the
  * keep_counts[b] - (#protected) highest-scoring other rows (tie rule above); writes the kept packed row
  * indices, ascending, to keep_idx_out[cu_seqlens_out[b] ..], writes cu_seqlens_out (prefix sums of
  * keep_counts), and copies rows: dst[i][r] = src[i][keep_idx_out[r]] for each of the n_tensors tensors of
@@ -229,12 +229,6 @@ fastav_status_t fastav_attention(const fastav_model_t* model, const void* q, int
                                  int64_t total_tokens, int32_t max_seqlen, float* last_logits, float* last_ml,
                                  void* stream);
 
-/* ---- measurement aid (benchmarks only) -------------------------------------------------------------- */
-
-/* Kernel kinds whose launches can be timed with HIP events on the launch stream.  "work" is the
- * algorithmic work of a launch: flops for LINEAR_* (2 M N K; SwiGLU counts both matrices) and ATTENTION
- * (2 Hq dh n(n+1) per sample, the causal half only), bytes for the others (what the step must read and
- * write once). */
 /* ---- one decode step on the pruned caches ------------------------------------------------------------
  * Section 3.1 measures latency as the time to generate a single token, and the memory FastAV saves is the
  * per-layer K/V cache of the surviving tokens.  This is that forward for ONE new token per sample (bf16
@@ -305,6 +299,12 @@ fastav_status_t fastav_rollout(fastav_handle_t h, const void* x, int32_t n, floa
 fastav_status_t fastav_rollout_cutoff(const float* rt, int32_t n, const uint8_t* protected_mask, float threshold,
                                       float* influence_out, int32_t* cutoff_out, void* stream);
 
+/* ---- measurement aid (benchmarks only) -------------------------------------------------------------- */
+
+/* Kernel kinds whose launches can be timed with HIP events on the launch stream.  "work" is the
+ * algorithmic work of a launch: flops for LINEAR_* (2 M N K; SwiGLU counts both matrices) and ATTENTION
+ * (2 Hq dh n(n+1) per sample, the causal half only), bytes for the others (what the step must read and
+ * write once). */
 typedef enum {
   FASTAV_PROF_LINEAR_STORE = 0, FASTAV_PROF_LINEAR_RESADD = 1, FASTAV_PROF_LINEAR_SWIGLU = 2,
   FASTAV_PROF_ATTENTION = 3, FASTAV_PROF_SCORE = 4, FASTAV_PROF_SELECT = 5, FASTAV_PROF_GATHER = 6,

@@ -375,6 +375,10 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
   if (((uintptr_t)in->x % 16) || ((uintptr_t)out->x_out % 16)) return fail(FASTAV_EINVAL, "x and x_out must be 16-byte aligned");
   for (int l = 0; l < m.n_layers; ++l)
     if (!h->has_w[l]) return fail(FASTAV_EINVAL, "weights of layer %d were never set", l);
+  // a layer without a fine prune computes on K and V in the caller's cache: the kernels read them 16 bytes at a time
+  if (out->kv_out)
+    for (int i = 0; i < 2 * m.n_layers; ++i)
+      if ((uintptr_t)out->kv_out[i] % 16) return fail(FASTAV_EINVAL, "kv_out[%d] must be 16-byte aligned", i);
   const int B = in->batch;
   const Workspace ws = carve(m, T0, B);
   if (workspace_bytes < ws.total)

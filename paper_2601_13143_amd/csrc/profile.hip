@@ -35,14 +35,13 @@ ProfScope::ProfScope(int kind, double work, hipStream_t s) : rec_(nullptr), stre
   hipEvent_t a = get_event(g_prof), b = get_event(g_prof);
   if (!a || !b) return;
   g_prof.pending.push_back(Rec{a, b, kind, work});
-  rec_ = (void*)(uintptr_t)g_prof.pending.size();          // index + 1
+  rec_ = (void*)b;                                         // the end event itself: a collect in between may reorder `pending`
   (void)hipEventRecord(a, s);
 }
 
 ProfScope::~ProfScope() {
   if (!rec_) return;
-  std::lock_guard<std::mutex> lk(g_prof.mu);
-  (void)hipEventRecord(g_prof.pending[(size_t)(uintptr_t)rec_ - 1].b, stream_);
+  (void)hipEventRecord((hipEvent_t)rec_, stream_);
 }
 
 }  // namespace fastav

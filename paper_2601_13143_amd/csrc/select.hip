@@ -1,5 +1,5 @@
-// Top-k selection and compaction for the prune step ("tokens with the lowest P% scores are removed",
-// Section 2.2 of the paper; global pruning keeps the earliest positions instead; the other strategies of
+// Top-k selection and compaction for the prune step (Section 2.2, "Fine pruning" / Eq. 4: the lowest-scoring
+// share P of the tokens goes; global pruning keeps the earliest positions instead; the other strategies of
 // Tables 2-3 - top attentive, top informative, random - are further orders of the same kernel).
 //
 //   k_select  one 1024-thread workgroup per sample.  The sample's order-preserving 32-bit keys live in LDS;

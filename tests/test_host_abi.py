@@ -160,6 +160,8 @@ def test_prefill_rejects_bad_arguments_before_any_launch():
     assert call(n_prunes=B.MAX_PRUNES + 1) == B.EINVAL
     hb2 = B._HostBatch(None, [0, 8], [(0, 4, fi.VIDEO), (4, 4, fi.TEXT)], [0, 2])
     assert call(batch=hb2.c) == B.EINVAL                                                    # x NULL
+    kv_bad = (C.c_void_p * 4)(4096, 4096, 4096 + 8, 4096)                                   # a cache pointer off a 16-byte boundary
+    assert call(o=B.PrefillOut(4096, 4096, 4096, kv_bad, None, None, None)) == B.EINVAL and b"kv_out[2]" in lib.fastav_last_error()
 
 
 def test_score_and_select_reject_bad_arguments():
