@@ -175,6 +175,20 @@ fastav_status_t fastav_score(const fastav_model_t* model, const void* q, int64_t
                              int64_t total_tokens, int32_t max_seqlen, int32_t n_last, float* scores_out,
                              void* workspace, size_t workspace_bytes, void* stream);
 
+/* fastav_score for callers that cannot allocate device memory or bring a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same result as
+ * fastav_score, but the scratch (last-row logits and per-chunk partial sums) is a fixed FASTAV_SCORE_STATIC_BYTES
+ * array that is part of the library image: every GPU the library runs on holds its own copy until the process
+ * ends.  The call allocates and frees nothing.  Problems that need more scratch than that
+ * (fastav_score_workspace_bytes(...) > FASTAV_SCORE_STATIC_BYTES; at 32 query heads and n_last = 1 that is beyond
+ * roughly 65 000 packed tokens) are rejected with FASTAV_EWORKSPACE before any launch.  All calls on one GPU share
+ * that GPU's array: calls that overlap there (different streams or threads) race; calls on one stream do not. */
+#define FASTAV_SCORE_STATIC_BYTES (8u << 20)
+fastav_status_t fastav_score_static(const fastav_model_t* model, const void* q, int64_t q_row_stride, const void* k,
+                                    int64_t k_row_stride, const int32_t* cu_seqlens_dev, int32_t batch,
+                                    int64_t total_tokens, int32_t max_seqlen, int32_t n_last, float* scores_out,
+                                    void* stream);
+
 /* Top-k selection per sample plus stable compaction (Section 2.2, "Fine pruning" / Eq. 4, and "Global
  * pruning" for the positional form).  For sample b, keeps every row whose protected_mask byte is non-zero and the
  * keep_counts[b] - (#protected) highest-scoring other rows (tie rule above); writes the kept packed row

@@ -95,6 +95,8 @@ _SIGS = {
     "fastav_score_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int64, C.c_int32, C.c_int32]),
     "fastav_score": (C.c_int, [C.POINTER(Model), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
                                C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "fastav_score_static": (C.c_int, [C.POINTER(Model), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
+                                      C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "fastav_select_workspace_bytes": (C.c_size_t, [C.c_int32]),
     "fastav_select_gather": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32,
                                        C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_int64),
@@ -390,6 +392,25 @@ def fastav_score(model: Model, q: torch.Tensor, k: torch.Tensor, cu_seqlens_dev:
     return out
 
 
+SCORE_STATIC_BYTES = 8 << 20
+
+
+def fastav_score_static(model: Model, q: torch.Tensor, k: torch.Tensor, cu_seqlens_dev: torch.Tensor, max_seqlen: int,
+                        n_last: int = 1, out: Optional[torch.Tensor] = None, q_row_stride: Optional[int] = None,
+                        k_row_stride: Optional[int] = None) -> torch.Tensor:
+    """fastav_score through the entry point that allocates nothing: the scratch is the library's built-in array.
+    Pass ``out`` (fp32 [T]) to keep this wrapper from allocating as well."""
+    T = q.shape[0]
+    B = cu_seqlens_dev.numel() - 1
+    qs = q_row_stride if q_row_stride is not None else q.stride(0)
+    ks = k_row_stride if k_row_stride is not None else k.stride(0)
+    if out is None:
+        out = torch.empty(T, dtype=torch.float32, device=q.device)
+    _check(lib().fastav_score_static(C.byref(model), q.data_ptr(), qs, k.data_ptr(), ks, cu_seqlens_dev.data_ptr(), B, T,
+                                     max_seqlen, n_last, out.data_ptr(), _stream()))
+    return out
+
+
 def fastav_select_gather(scores: Optional[torch.Tensor], protected_mask: torch.Tensor, cu_seqlens, keep_counts,
                          tensors: Sequence[torch.Tensor] = ()):
     """-> (keep_idx int32 [total_keep], cu_seqlens_out int32 [B+1] (device), [gathered tensors]).
@@ -480,3 +501,4 @@ def fastav_profile_collect(kind: str):
 
 def fastav_profile_reset() -> None:
     _check(lib().fastav_profile_reset())
+

@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -567,6 +568,55 @@ fastav_status_t fastav_score(const fastav_model_t* model, const void* q, int64_t
                                  model->dtype, s));
   return launch_score_finalize(logits, nullptr, partials, cu_seqlens_dev, batch, total_tokens, max_seqlen,
                                model->n_q_heads, n_last, scores_out, s);
+}
+
+// ---- Eq. 4 without a workspace argument: the scratch of the score kernels (last-row logits and the per-chunk
+// (max, sum) partials) lives in a fixed array inside the library's code object.  Every GPU holds its own copy at its
+// own address; the address is looked up once per device and only that pointer is ever handed to a kernel (the
+// array's name is a host-side stand-in, not a device address).
+static __device__ __align__(256) unsigned char g_score_scratch[FASTAV_SCORE_STATIC_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of g_score_scratch on the current device (looked up on the first call there).
+fastav_status_t score_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(FASTAV_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(FASTAV_EUNSUPPORTED, "device index %d is beyond the %d this library tracks", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_score_scratch));
+    if (e != hipSuccess || !p) return fail(FASTAV_EHIP, "hipGetSymbolAddress(score scratch): %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return FASTAV_OK;
+}
+}  // namespace
+
+fastav_status_t fastav_score_static(const fastav_model_t* model, const void* q, int64_t q_row_stride, const void* k,
+                                    int64_t k_row_stride, const int32_t* cu_seqlens_dev, int32_t batch,
+                                    int64_t total_tokens, int32_t max_seqlen, int32_t n_last, float* scores_out,
+                                    void* stream) {
+  FASTAV_TRY(check_model(model));
+  if (batch < 1 || total_tokens < 0 || n_last < 1 || n_last > FASTAV_MAX_N_LAST)
+    return fail(FASTAV_EINVAL, "bad batch/total_tokens/n_last");
+  const size_t need = fastav_score_workspace_bytes(model->n_q_heads, total_tokens, batch, n_last);
+  if (need > (size_t)FASTAV_SCORE_STATIC_BYTES)
+    return fail(FASTAV_EWORKSPACE, "fastav_score_static: this problem needs %zu bytes of scratch, the built-in buffer holds %zu "
+                "(n_last * n_q_heads * total_tokens * 4 bytes plus the chunk partials); use fastav_score with a workspace",
+                need, (size_t)FASTAV_SCORE_STATIC_BYTES);
+  void* scratch = nullptr;
+  FASTAV_TRY(score_scratch(&scratch));
+  // every position of the scratch that the finalize pass reads is written by the logits pass of the same call,
+  // so nothing has to be cleared between calls
+  return fastav_score(model, q, q_row_stride, k, k_row_stride, cu_seqlens_dev, batch, total_tokens, max_seqlen, n_last,
+                      scores_out, scratch, (size_t)FASTAV_SCORE_STATIC_BYTES, stream);
 }
 
 size_t fastav_select_workspace_bytes(int32_t batch) {

@@ -175,6 +175,12 @@ def test_score_and_select_reject_bad_arguments():
     assert f(q=None) == B.EINVAL and f(qs=100) == B.EINVAL and f(ks=4) == B.EINVAL
     assert f(n_last=9) == B.EINVAL and f(maxlen=101) == B.EINVAL and f(wsb=need - 1) == B.EWORKSPACE
     assert f(q=4098) == B.EINVAL                                                            # misaligned q
+    # the entry point without a workspace: what does not fit its built-in scratch is refused on the host
+    big = 80000
+    assert lib.fastav_score_workspace_bytes(4, big * 8, 1, 1) > B.SCORE_STATIC_BYTES
+    assert lib.fastav_score_static(C.byref(m), 4096, 256, 4096, 128, 4096, 1, big * 8, big * 8, 1, 4096, None) == B.EWORKSPACE
+    assert b"built-in buffer" in lib.fastav_last_error()
+    assert lib.fastav_score_static(C.byref(m), 4096, 256, 4096, 128, 4096, 1, 100, 100, 9, 4096, None) == B.EINVAL
     cu = np.array([0, 10, 30], dtype=np.int32)
     kc = np.array([5, 25], dtype=np.int32)
     ip = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
