@@ -111,6 +111,8 @@ _SIGS = {
     "fastav_profile_enable": (C.c_int, [C.c_uint32]),
     "fastav_profile_collect": (C.c_int, [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
     "fastav_profile_reset": (C.c_int, []),
+    "fastav_probe_mfma": (C.c_int, [C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]),
+    "fastav_probe_read": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
 }
 
 PROF_KINDS = {"linear_store": 0, "linear_resadd": 1, "linear_swiglu": 2, "attention": 3, "score": 4, "select": 5,
@@ -502,3 +504,16 @@ def fastav_profile_collect(kind: str):
 def fastav_profile_reset() -> None:
     _check(lib().fastav_profile_reset())
 
+
+def fastav_probe_mfma(iters: int, sink: torch.Tensor) -> float:
+    """Enqueues the matrix-instruction-only probe on the current stream; -> flops of the launch."""
+    fl = C.c_double()
+    _check(lib().fastav_probe_mfma(iters, sink.data_ptr(), C.byref(fl), _stream()))
+    return fl.value
+
+
+def fastav_probe_read(src: torch.Tensor, sink: torch.Tensor) -> int:
+    """Enqueues one streaming read of ``src`` on the current stream; -> bytes read."""
+    nbytes = src.numel() * src.element_size()
+    _check(lib().fastav_probe_read(src.data_ptr(), nbytes, sink.data_ptr(), _stream()))
+    return nbytes

@@ -44,6 +44,43 @@ ProfScope::~ProfScope() {
   (void)hipEventRecord((hipEvent_t)rec_, stream_);
 }
 
+// ---- "achievable peak" probes: what this chip sustains with nothing in the way, next to the datasheet figures.
+// A loop of independent bf16 matrix instructions only (no memory traffic), two waves per SIMD on every CU.
+__global__ __launch_bounds__(256, 2) void k_probe_mfma(int iters, float* __restrict__ sink) {
+  const int lane = threadIdx.x & 63;
+  bf16x8_t a, b;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { a[e] = (bf16_t)(float)((lane + e) & 3); b[e] = (bf16_t)(float)((lane * 3 + e) & 1); }
+  f32x4_t acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[i], 0, 0, 0);
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) t += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+  if (t == -1.0f) sink[blockIdx.x * 256 + threadIdx.x] = t;      // never true: keeps the loop alive
+}
+
+// A plain streaming read: every lane loads 16 bytes per step, workgroups walk memory in launch order.
+__global__ __launch_bounds__(256) void k_probe_read(const f32x4_t* __restrict__ src, int64_t n16, float* __restrict__ sink) {
+  f32x4_t s = {0.f, 0.f, 0.f, 0.f};
+  const int64_t stride = (int64_t)gridDim.x * 256 * 4;
+  int64_t i = ((int64_t)blockIdx.x * 4) * 256 + threadIdx.x;
+  for (; i + 3 * 256 < n16; i += stride) {
+    const f32x4_t v0 = src[i], v1 = src[i + 256], v2 = src[i + 512], v3 = src[i + 768];
+    s[0] += v0[0] + v1[1] + v2[2] + v3[3];
+    s[1] += v0[1] + v1[2] + v2[3] + v3[0];
+    s[2] += v0[2] + v1[3] + v2[0] + v3[1];
+    s[3] += v0[3] + v1[0] + v2[1] + v3[2];
+  }
+  if (s[0] + s[1] + s[2] + s[3] == -1.2345e30f) sink[blockIdx.x] = s[0];
+}
+
 }  // namespace fastav
 
 using namespace fastav;
@@ -79,6 +116,23 @@ fastav_status_t fastav_profile_collect(int32_t kind, double* total_ms, int64_t* 
   if (launches) *launches = g_prof.n[kind];
   if (total_work) *total_work = g_prof.work[kind];
   return FASTAV_OK;
+}
+
+fastav_status_t fastav_probe_mfma(int32_t iters, float* sink, double* flops_out, void* stream) {
+  if (iters < 1 || !sink) return fail(FASTAV_EINVAL, "probe: iters must be >= 1 and sink non-NULL");
+  const int blocks = 2048;                                      // 8 workgroups of 4 waves per CU
+  hipLaunchKernelGGL(k_probe_mfma, dim3(blocks), dim3(256), 0, (hipStream_t)stream, iters, sink);
+  if (flops_out) *flops_out = (double)blocks * 4.0 * iters * 32.0 * (2.0 * 16 * 16 * 32);
+  return check_launch("probe_mfma");
+}
+
+fastav_status_t fastav_probe_read(const void* src, size_t bytes, float* sink, void* stream) {
+  if (!src || !sink || bytes < 16384 || ((uintptr_t)src % 16)) return fail(FASTAV_EINVAL, "probe: src (16-byte aligned, >= 16 KB) and sink must be given");
+  const int64_t n16 = (int64_t)(bytes / 16);
+  int64_t blocks = n16 / 1024;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(k_probe_read, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (const f32x4_t*)src, n16, sink);
+  return check_launch("probe_read");
 }
 
 fastav_status_t fastav_profile_reset(void) {

@@ -473,9 +473,11 @@ def _check_prefill(w: fi.Workload, out, ref, x_scale_from_ref=True):
                     # a token the oracle no longer holds can only be the partner of an earlier flip
                     assert p in pos_to_local, (b, i, p, "differs, yet was never within a tie band")
                     assert abs(s_ref[pos_to_local[p]] - kth) <= TIE_BAND, (b, i, p, s_ref[pos_to_local[p]], kth)
-                # beyond the literal band: bf16 noise may only flip a small fraction of the kept set
-                assert len(diff) <= max(4, int(0.03 * pr["k"])), (b, i, len(diff), pr["k"])
-            stats["flips_per_prune"].append((b, i, len(diff) // 2))
+                # beyond the literal band (loose where scores are ~1/n): bf16 noise may only exchange a small part of
+                # the kept set.  Measured on the full-size configurations: 0.3-0.7 % of k exchanged per prune
+                # (profiles/parity_cfg*.txt); the cap is 1 % of k exchanged = 2 % of k in the symmetric difference
+                assert len(diff) <= max(4, int(0.02 * pr["k"])), (b, i, len(diff), pr["k"])
+            stats["flips_per_prune"].append((b, i, len(diff) // 2, pr["k"]))
             stats["flipped"] += (len(diff) + 1) // 2
             # diagnostics: overlap of the two kept sets, and how many differing tokens lie outside a STRICT band
             # (1 % of the k-th score) around the cut - the literal band is wide where scores are ~1/n
@@ -697,9 +699,11 @@ def _record_parity(cfg, w, st):
             f.write("sample  x_rel_l2  x_max_abs_over_rms\n")
             for b in range(len(w.samples)):
                 f.write(f"{b:6d}  {st[f'x_rel_l2_{b}']:.4e}  {st[f'x_max_abs_over_rms_{b}']:.4e}\n")
-            f.write("sample  prune  tokens_that_differ  jaccard  differing_tokens_outside_1pct_band_of_kth_score\n")
-            for (b, i, fl), (_, _, jac), (_, _, ns) in zip(st["flips_per_prune"], st["jaccard"], st["outside_strict_band"]):
-                f.write(f"{b:6d}  {i:5d}  {fl:18d}  {jac:.5f}  {ns}\n")
+            f.write("limits asserted: x_rel_l2 <= 3e-2, x_max_abs_over_rms <= 0.25, tokens exchanged per prune <= max(2, 1 % of k), "
+                    "every exchanged token within 1e-3 of the k-th score\n")
+            f.write("sample  prune  kept_k  tokens_exchanged  share_of_k  jaccard  differing_tokens_outside_1pct_band_of_kth_score\n")
+            for (b, i, fl, k), (_, _, jac), (_, _, ns) in zip(st["flips_per_prune"], st["jaccard"], st["outside_strict_band"]):
+                f.write(f"{b:6d}  {i:5d}  {k:6d}  {fl:16d}  {fl / max(1, k):.4f}  {jac:.5f}  {ns}\n")
     except OSError:
         pass
 
