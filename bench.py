@@ -29,17 +29,18 @@ WORKLOADS = {"cfg1": 1, "cfg2": 2, "cfg3": 3, "cfg4": 4, "cfg5": 5}
 
 
 def _recorded_traffic(workload):
-    """Bytes per launch of the gate/up GEMM from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE,
-    calibrated on a copy kernel); None when no summary exists for this workload.  A profiler cannot run inside
-    this process, so the figure is read back from profiles/."""
-    path = os.path.join(ROOT, "profiles", f"prefill_{workload}_pmc_traffic.txt")
+    """-> (bytes per launch of the gate/up GEMM, where the figure comes from).  A profiler cannot run inside this
+    process, so the figure is NOT measured by this run: it is read back from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, calibrated on a copy kernel) and labelled as such; (None, None) when there is no
+    summary for this workload."""
+    rel = os.path.join("profiles", f"prefill_{workload}_pmc_traffic.txt")
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             if line.startswith("traffic_bytes_per_launch_gemm_swiglu:"):
-                return float(line.split(":")[1])
+                return float(line.split(":")[1]), f"recorded, not measured in this run: {rel} (two rocprofv3 --pmc runs of this script)"
     except OSError:
         pass
-    return None
+    return None, None
 
 
 def _upload_weights(dec, m, seed, threads):
@@ -149,6 +150,98 @@ def _prune_stress(fa, torch, model_struct, hq, hkv, dh, d):
             "score": mk(b_score, t_score), "select": mk(b_sel, t_sel), "gather": mk(b_gather, t_gather)}
 
 
+def _achievable_peak(fa, torch):
+    """What the chip sustains with nothing in the way, next to the datasheet peaks the roofline fractions use: a loop
+    of bf16 matrix instructions only (no memory traffic, two waves per SIMD on every CU) and one streaming read of a
+    1 GiB buffer (four times the memory-side cache).  Timed with events on the launch stream."""
+    sink = torch.zeros(1 << 20, dtype=torch.float32, device="cuda")
+    src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")          # 1 GiB
+
+    def timed(fn, reps):
+        fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        torch.cuda.synchronize()
+        work = 0.0
+        for i in range(reps):
+            ev[i].record()
+            work = fn()
+        ev[reps].record()
+        torch.cuda.synchronize()
+        return work, min(ev[i].elapsed_time(ev[i + 1]) for i in range(reps)) * 1e-3
+
+    fl, t_m = timed(lambda: fa.fastav_probe_mfma(2000, sink), 3)
+    by, t_r = timed(lambda: fa.fastav_probe_read(src, sink), 5)
+    del src
+    return {"mfma_bf16": {"achieved": fl / t_m / 1e12, "unit": "TFLOP/s", "of_datasheet": fl / t_m / 1e12 / PEAK_BF16_TFLOPS,
+                          "what": "v_mfma_f32_16x16x32_bf16 only, 32 independent accumulator chains per SIMD"},
+            "hbm_read": {"achieved": by / t_r / 1e9, "unit": "GB/s", "of_datasheet": by / t_r / 1e9 / PEAK_HBM_GBS,
+                         "what": "streaming read of 1 GiB, 16 bytes per lane and load"}}
+
+
+def _by_shape(fa, torch, dec, m, cu, spans, offs, prunes, n_last, iters=6):
+    """Every kernel of a layer at every token count of the schedule, on its own: us per launch and the fraction of
+    its roofline (flops over the bf16 MFMA peak for the GEMMs and attention, algorithmic bytes over the HBM peak
+    for RMSNorm and RoPE).  The GEMMs rotate through the layers' weights, so the weights stream from HBM as they do
+    in the model.  Timed with the library's events on the launch stream."""
+    if m.dtype != "bf16":
+        return None
+    L = m.n_layers
+    qd, kd, d, mlp, dh = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim, m.hidden, m.mlp_dim, m.head_dim
+    tin, tout, _ = fa.fastav_schedule(cu, spans, offs, prunes, n_last, L)
+    stages = [fa.fastav_schedule(cu, spans, offs, prunes[:i], n_last, L)[2] for i in range(len(prunes) + 1)]
+    g = torch.Generator(device="cuda").manual_seed(3)
+    nw = min(L, 4)
+    wqkv = [torch.cat([dec._weights[l]["wq"], dec._weights[l]["wk"], dec._weights[l]["wv"]]) for l in range(nw)]
+    out = []
+    for lens in stages:
+        T = int(lens.sum())
+        n_attn = int((tin == T).sum())
+        n_mlp = int((tout == T).sum())
+        if n_attn == 0 and n_mlp == 0:
+            continue
+        cu_s = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).cuda()
+        hn = torch.randn(T, d, device="cuda", generator=g).bfloat16()
+        ao = torch.randn(T, qd, device="cuda", generator=g).bfloat16()
+        hm = torch.randn(T, mlp, device="cuda", generator=g).bfloat16() * 0.1
+        res = torch.randn(T, d, device="cuda", generator=g)
+        qkv = torch.randn(T, qd + 2 * kd, device="cuda", generator=g).bfloat16()
+        pos = torch.arange(T, device="cuda", dtype=torch.int32)
+        q = qkv.as_strided((T, m.n_q_heads, dh), (qkv.stride(0), dh, 1))
+        k = qkv.as_strided((T, m.n_kv_heads, dh), (qkv.stride(0), dh, 1), qd)
+        v = qkv.as_strided((T, m.n_kv_heads, dh), (qkv.stride(0), dh, 1), qd + kd)
+        gain = dec._weights[0]["g_attn"]
+        c_qkv = torch.empty(T, qd + 2 * kd, device="cuda", dtype=torch.bfloat16)
+        c_mlp = torch.empty(T, mlp, device="cuda", dtype=torch.bfloat16)
+        attn_flops = float(sum(2.0 * m.n_q_heads * dh * n * (n + 1.0) for n in lens.tolist()))
+        cases = [
+            ("qkv_store", "linear_store", lambda i: fa.fastav_linear(hn, wqkv[i % nw], fa.EPI_STORE, c=c_qkv), 2.0 * T * (qd + 2 * kd) * d, True),
+            ("attention", "attention", lambda i: fa.fastav_attention(dec.model, q, k, v, cu_s, int(lens.max())), attn_flops, True),
+            ("o_resadd", "linear_resadd", lambda i: fa.fastav_linear(ao, dec._weights[i % L]["wo"], fa.EPI_RESADD, c=res), 2.0 * T * d * qd, True),
+            ("gateup_swiglu", "linear_swiglu", lambda i: fa.fastav_linear(hn, dec._weights[i % L]["w_gate"], fa.EPI_SWIGLU, w2=dec._weights[i % L]["w_up"], c=c_mlp), 4.0 * T * mlp * d, True),
+            ("down_resadd", "linear_resadd", lambda i: fa.fastav_linear(hm, dec._weights[i % L]["w_down"], fa.EPI_RESADD, c=res), 2.0 * T * d * mlp, True),
+            ("rmsnorm", "rmsnorm", lambda i: fa.fastav_rmsnorm(res, gain, 1e-6), T * d * 6.0, False),
+            ("rope", "rope", lambda i: fa.fastav_rope(qkv, pos, m.n_q_heads + m.n_kv_heads, dh, m.rope_base), 2.0 * T * (qd + kd) * 2.0, False),
+        ]
+        row = {"tokens": T, "layers_with_attention_at_this_count": n_attn, "layers_with_mlp_at_this_count": n_mlp, "kernels": {}}
+        for name, kind, fn, work, is_flops in cases:
+            fn(0); fn(1)
+            torch.cuda.synchronize()
+            fa.fastav_profile_enable([kind])
+            ms0, n0, _ = fa.fastav_profile_collect(kind)
+            for i in range(iters):
+                fn(i + 2)
+            torch.cuda.synchronize()
+            ms1, n1, _ = fa.fastav_profile_collect(kind)
+            fa.fastav_profile_enable([])
+            t = (ms1 - ms0) * 1e-3 / max(1, n1 - n0)
+            rate = work / t / (1e12 if is_flops else 1e9)
+            row["kernels"][name] = {"us": t * 1e6, "achieved": rate, "unit": "TFLOP/s" if is_flops else "GB/s",
+                                    "frac": rate / (PEAK_BF16_TFLOPS if is_flops else PEAK_HBM_GBS)}
+        out.append(row)
+        del hn, ao, hm, res, qkv, c_qkv, c_mlp
+    return out
+
+
 def _decode_bench(fa, torch, dec, m, w, x, cu, spans, offs, prunes, iters=20):
     """One generated token's forward (the paper's latency metric, Section 3.1) on the caches the pruned prefill
     left, and on the unpruned caches: ms per step and bytes moved (all weights once + every layer's cache once)
@@ -196,6 +289,10 @@ def main():
                     help="prune as the paper does: global at the middle layer, then 20 %% fine at every later layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-passes", action="store_true", help="skip the per-kernel timing passes")
+    ap.add_argument("--shapes-only", action="store_true",
+                    help="run only the per-shape kernel table and the achievable-peak probes (short: for counter runs under rocprofv3)")
+    ap.add_argument("--stress-only", action="store_true",
+                    help="run only the prune kernels at the stress shape (short: for counter runs under rocprofv3)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the path is single-GPU by design: no collectives, no sharding); "
@@ -221,6 +318,16 @@ def main():
     cu, (spans, offs) = fi.cu_seqlens(w), fi.span_table(w)
     prunes = [(p.layer, p.kind, p.keep_ratio) for p in w.prunes]
     tokens = w.total_tokens
+
+    if args.shapes_only or args.stress_only:
+        line = {"workload": w.name}
+        if args.shapes_only:
+            line["achievable_peak"] = _achievable_peak(fa, torch)
+            line["by_shape"] = _by_shape(fa, torch, dec, m, cu, spans, offs, prunes, w.n_last, iters=3)
+        else:
+            line["prune_kernels_stress"] = _prune_stress(fa, torch, dec.model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.hidden)
+        print(json.dumps(line))
+        return
 
     dominant = "linear_swiglu"
 
@@ -249,6 +356,11 @@ def main():
     fa.fastav_profile_enable([dominant])              # events around the dominant kernel only, whole run
     s_pruned, per_pruned = timed(prunes, args.steps, args.warmup)
     s_plain, per_plain = timed([], args.steps, args.warmup)
+    dom_ms, dom_n, dom_wk = fa.fastav_profile_collect(dominant)
+    achieved = dom_wk / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
+    # the same steps once more with the event bracket off: what the bracket itself costs (not `value`)
+    fa.fastav_profile_enable([])
+    s_pruned_noev, _ = timed(prunes, args.steps, 1)
 
     # ---- per-kernel passes (not part of `value`): all kinds timed with events, pruned then unpruned
     kernels = {}
@@ -279,8 +391,11 @@ def main():
     else:
         prune_us = None
     fa.fastav_profile_enable([])
-    ms, n, wk = fa.fastav_profile_collect(dominant)
-    achieved = wk / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
+
+    peak = by_shape = None
+    if not args.no_kernel_passes:
+        peak = _achievable_peak(fa, torch)
+        by_shape = _by_shape(fa, torch, dec, m, cu, spans, offs, prunes, w.n_last)
 
     stress = None
     if not args.no_kernel_passes and m.dtype == "bf16":
@@ -307,6 +422,7 @@ def main():
     if not args.no_cpu_baseline:
         cpu = _cpu_baseline(w, host_threads)
 
+    traffic, traffic_src = _recorded_traffic(args.workload)
     line = {
         "metric": "pruned prefill tokens/sec at 7B shape (unpruned rate, prune-step us and % roofline alongside)",
         "value": tokens / s_pruned, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -322,9 +438,12 @@ def main():
         "pruned_over_unpruned": s_plain / s_pruned,
         "prune_steps_us_per_prefill": prune_us,
         "roofline": {"kernel": "k_gemm_mfma16<SwiGLU> (gate/up projection)", "bound": "mfma", "achieved": achieved,
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": _recorded_traffic(args.workload),
-                     "launches": n, "avg_launch_us": 1e3 * ms / max(n, 1)},
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_source": traffic_src,
+                     "launches": dom_n, "avg_launch_us": 1e3 * dom_ms / max(dom_n, 1)},
+        "ms_per_step_without_kernel_events": s_pruned_noev * 1e3,
+        "achievable_peak": peak,
         "kernels": kernels,
+        "by_shape": by_shape,
         "prune_kernels_stress": stress,
         "decode_step": decode,
         "rollout": rollout,

@@ -73,6 +73,7 @@ class DecodeIn(C.Structure):
 
 _SIGS = {
     "fastav_last_error": (C.c_char_p, []),
+    "fastav_set_option": (C.c_int, [C.c_int32, C.c_int32]),
     "fastav_keep_count": (C.c_int64, [C.c_int64, C.c_double, C.c_int64]),
     "fastav_schedule": (C.c_int, [C.POINTER(Batch), C.POINTER(Prune), C.c_int32, C.c_int32, C.c_int32,
                                   C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]),
@@ -517,3 +518,10 @@ def fastav_probe_read(src: torch.Tensor, sink: torch.Tensor) -> int:
     nbytes = src.numel() * src.element_size()
     _check(lib().fastav_probe_read(src.data_ptr(), nbytes, sink.data_ptr(), _stream()))
     return nbytes
+
+
+OPT_FUSED_SCORE_SELECT = 0
+
+
+def fastav_set_option(option: int, value: int) -> None:
+    _check(lib().fastav_set_option(option, value))

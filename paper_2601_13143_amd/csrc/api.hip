@@ -15,6 +15,7 @@
 namespace fastav {
 
 static thread_local char g_err[512] = "";
+int g_options[FASTAV_OPT_COUNT] = {1};
 
 fastav_status_t fail(fastav_status_t st, const char* fmt, ...) {
   va_list ap;
@@ -228,7 +229,7 @@ static void build_schedule(const fastav_batch_t* in, const fastav_prune_t* prune
 // ------------------------------------------------------------------------------------------ workspace
 struct Workspace {
   size_t resid[2], hn, qkv, attn[2], hmlp, logits, ml, partials, scores, pos[2], prot[2], keep_idx, cu, span_off,
-      spans, gemm_scratch, gemm_scratch_bytes, total;
+      spans, gemm_scratch, gemm_scratch_bytes, rope_table, total;
 };
 
 static Workspace carve(const fastav_model_t& m, int64_t T, int B) {
@@ -258,6 +259,7 @@ static Workspace carve(const fastav_model_t& m, int64_t T, int B) {
   w.spans = take((size_t)T * sizeof(fastav_span_t));       // a span holds >= 1 token
   w.gemm_scratch_bytes = m.dtype == FASTAV_BF16 ? mfma_linear_scratch_bytes() : 0;   // split-K partial tiles
   w.gemm_scratch = take(w.gemm_scratch_bytes);
+  w.rope_table = take(rope_table_bytes((int)(T < 0x7FFFFFFF ? T : 0x7FFFFFFF), m.head_dim));   // a sample is at most T tokens long
   w.total = at;
   return w;
 }
@@ -275,6 +277,12 @@ struct fastav_ctx {
 extern "C" {
 
 const char* fastav_last_error(void) { return g_err; }
+
+fastav_status_t fastav_set_option(int32_t option, int32_t value) {
+  if (option < 0 || option >= FASTAV_OPT_COUNT) return fail(FASTAV_EINVAL, "unknown option %d", option);
+  g_options[option] = value;
+  return FASTAV_OK;
+}
 
 int64_t fastav_keep_count(int64_t n, double keep_ratio, int64_t n_protected) {
   if (n < 0 || !(keep_ratio > 0.0 && keep_ratio <= 1.0) || n_protected < 0 || n_protected > n) return -1;
@@ -432,6 +440,9 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
   FASTAV_TRY(upload_small(spans_dev, in->spans, (size_t)in->span_offsets[B] * sizeof(fastav_span_t), s));
   FASTAV_TRY(launch_init_tokens(cu_dev, span_off_dev, spans_dev, B, T0, max_len0, n_last, pos[0], prot[0], s));
   FASTAV_TRY(launch_to_f32(in->x, resid[0], T0 * m.hidden, m.dtype, s));
+  // rotary (cos, sin) of every original position, once: tokens keep their positions through every prune
+  void* rope_tab = m.dtype == FASTAV_BF16 ? (void*)(base + ws.rope_table) : nullptr;
+  if (rope_tab) FASTAV_TRY(launch_rope_table(rope_tab, max_len0, m.head_dim, m.rope_base, s));
 
   const size_t es = m.dtype == FASTAV_BF16 ? 2 : 4;
   const int qd = m.n_q_heads * m.head_dim, kd = m.n_kv_heads * m.head_dim;
@@ -481,9 +492,9 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
                                  kv_direct ? cs : nullptr, kv_direct ? lds_ : nullptr));
     }
     if (kv_direct) {
-      FASTAV_TRY(launch_rope2(qkv, qkv_stride, m.n_q_heads, k_out, kd, m.n_kv_heads, pos[cur], Tl, m.head_dim, m.rope_base, m.dtype, s));
+      FASTAV_TRY(launch_rope2(qkv, qkv_stride, m.n_q_heads, k_out, kd, m.n_kv_heads, pos[cur], Tl, m.head_dim, m.rope_base, m.dtype, s, rope_tab));
     } else {
-      FASTAV_TRY(launch_rope(qkv, qkv_stride, pos[cur], Tl, m.n_q_heads + m.n_kv_heads, m.head_dim, m.rope_base, m.dtype, s));
+      FASTAV_TRY(launch_rope(qkv, qkv_stride, pos[cur], Tl, m.n_q_heads + m.n_kv_heads, m.head_dim, m.rope_base, m.dtype, s, rope_tab));
     }
     FASTAV_TRY(launch_attention(qkv, qkv_stride, kptr, vptr, kv_stride, attn[0], qd, cu_l, B, Tl, maxlen_stage[stage],
                                 m.n_q_heads, m.n_kv_heads, m.head_dim, side ? logits : nullptr, side ? ml : nullptr,
@@ -493,11 +504,14 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
       // ---- FINE prune: Eq. 4 scores of the last query row(s), top-k, compaction of everything later work reads
       float* sc = (out->prune_scores_out && out->prune_scores_out[pi]) ? out->prune_scores_out[pi] : scores_ws;
       const fastav_prune_t& pr = prunes[pi];
-      const SelectRule rule = pr.selector == FASTAV_SEL_RANDOM ? SelectRule{kSelRandom, select_random_key(pr.seed, l), pos[cur]}
-                            : pr.selector == FASTAV_SEL_TOP_ATTENTIVE ? SelectRule{kSelLowScore, 0, nullptr}
-                                                                      : SelectRule{kSelHighScore, 0, nullptr};
+      SelectRule rule = pr.selector == FASTAV_SEL_RANDOM ? SelectRule{kSelRandom, select_random_key(pr.seed, l), pos[cur]}
+                      : pr.selector == FASTAV_SEL_TOP_ATTENTIVE ? SelectRule{kSelLowScore, 0, nullptr}
+                                                                : SelectRule{kSelHighScore, 0, nullptr};
       if (!fine_scored) {
         // random strategy: no scores
+      } else if (side && g_options[FASTAV_OPT_FUSED_SCORE_SELECT] && select_fuses_score(maxlen_stage[stage], m.n_q_heads)) {
+        // Eq. 4 is finished inside the select kernel, straight from the attention side output
+        rule.logits = logits; rule.ml = ml; rule.n_heads = m.n_q_heads; rule.T = Tl; rule.scores_out = sc;
       } else if (side) {
         FASTAV_TRY(launch_score_finalize(logits, ml, nullptr, cu_l, B, Tl, maxlen_stage[stage], m.n_q_heads, 1, sc, s));
       } else {

@@ -70,11 +70,16 @@ fastav_status_t launch_copy_rows(const void* src, int64_t src_row_bytes_stride, 
                                  int64_t rows, const int32_t* idx, hipStream_t s, int64_t dst_row_bytes_stride = 0);
 fastav_status_t launch_rmsnorm(const float* x, const void* g, void* y, int64_t rows, int d, float eps, int dtype,
                                hipStream_t s);
+// table (optional): (cos, sin) per (position, frequency index) as launch_rope_table writes it; positions in `pos`
+// must be below the n_pos it was built for.  Without it every launch evaluates the angles itself.
+size_t rope_table_bytes(int n_pos, int head_dim);
+fastav_status_t launch_rope_table(void* table, int n_pos, int head_dim, float base, hipStream_t s);
 fastav_status_t launch_rope(void* x, int64_t row_stride, const int32_t* pos, int64_t rows, int n_heads, int head_dim,
-                            float base, int dtype, hipStream_t s);
+                            float base, int dtype, hipStream_t s, const void* table = nullptr);
 // the same over n_heads heads of x followed by n_heads2 heads of a second tensor (one launch)
 fastav_status_t launch_rope2(void* x, int64_t row_stride, int n_heads, void* x2, int64_t row_stride2, int n_heads2,
-                             const int32_t* pos, int64_t rows, int head_dim, float base, int dtype, hipStream_t s);
+                             const int32_t* pos, int64_t rows, int head_dim, float base, int dtype, hipStream_t s,
+                             const void* table = nullptr);
 // scratch (optional): device memory for split-K partial tiles; without it small-M residual GEMMs are not split
 fastav_status_t launch_linear(const void* a, const void* w, const void* w2, void* c, int64_t m, int n, int k,
                               int epilogue, int dtype, void* scratch, size_t scratch_bytes, hipStream_t s);
@@ -107,7 +112,15 @@ struct SelectRule {
   int order;
   uint32_t key;        // kSelRandom: mix32(seed + G * (layer + 1)), prepared on the host
   const int32_t* pos;  // kSelRandom: position id of every packed row (nullptr -> index inside the sample)
+  // score orders, optional: finish Eq. 4 inside the select kernel from the attention side output instead of reading
+  // `scores` - logits [n_heads][T] fp32, ml [batch][n_heads][2] = (max, sum of exp); scores_out (optional) [T]
+  const float* logits = nullptr;
+  const float* ml = nullptr;
+  int n_heads = 0;
+  int64_t T = 0;
+  float* scores_out = nullptr;
 };
+bool select_fuses_score(int max_seqlen, int n_heads);   // limits of the fused path
 uint32_t select_random_key(uint32_t seed, int layer);
 
 // Selection + compaction.  keep_idx/cu_out as in fastav_select_gather; scores are read by the two score orders only.

@@ -126,14 +126,69 @@ __global__ __launch_bounds__(256) void k_rmsnorm(const float* __restrict__ x, co
   }
 }
 
+// The same for rows of up to 1024 * NV floats with d a multiple of 4: the row is read ONCE, 16 bytes per lane and
+// load, kept in registers across the reduction, and written back 4 elements per store.
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void k_rmsnorm_reg(const float* __restrict__ x, const T* __restrict__ g,
+                                                     T* __restrict__ y, int d, float eps) {
+  __shared__ float red[4];
+  const f32x4_t* xv = (const f32x4_t*)(x + (int64_t)blockIdx.x * d);
+  T* yr = y + (int64_t)blockIdx.x * d;
+  const int n4 = d >> 2;
+  f32x4_t v[NV];
+  float ss = 0.f;
+#pragma unroll
+  for (int u = 0; u < NV; ++u) {
+    const int i = threadIdx.x + u * 256;
+    v[u] = (i < n4) ? xv[i] : f32x4_t{0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll
+  for (int u = 0; u < NV; ++u) ss += v[u][0] * v[u][0] + v[u][1] * v[u][1] + v[u][2] * v[u][2] + v[u][3] * v[u][3];
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float tot = red[0] + red[1] + red[2] + red[3];
+  const float r = 1.0f / sqrtf(tot / (float)d + eps);
+#pragma unroll
+  for (int u = 0; u < NV; ++u) {
+    const int i = threadIdx.x + u * 256;
+    if (i < n4) {
+      if constexpr (sizeof(T) == 2) {
+        const bf16x4_t gv = *(const bf16x4_t*)(g + 4 * i);
+        bf16x4_t o;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) o[c] = (bf16_t)(v[u][c] * r * (float)gv[c]);
+        *(bf16x4_t*)(yr + 4 * i) = o;
+      } else {
+        const f32x4_t gv = *(const f32x4_t*)(g + 4 * i);
+        f32x4_t o;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) o[c] = v[u][c] * r * gv[c];
+        *(f32x4_t*)(yr + 4 * i) = o;
+      }
+    }
+  }
+}
+
 fastav_status_t launch_rmsnorm(const float* x, const void* g, void* y, int64_t rows, int d, float eps, int dtype,
                                hipStream_t s) {
   if (rows == 0) return FASTAV_OK;
   ProfScope prof(FASTAV_PROF_RMSNORM, (double)rows * d * (4.0 + (dtype == FASTAV_BF16 ? 2.0 : 4.0)), s);
-  if (dtype == FASTAV_BF16)
-    hipLaunchKernelGGL(k_rmsnorm<bf16_t>, dim3((unsigned)rows), dim3(256), 0, s, x, (const bf16_t*)g, (bf16_t*)y, d, eps);
+  const size_t es = dtype == FASTAV_BF16 ? 2 : 4;
+  const bool reg = (d % 4) == 0 && d <= 8192 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)g % (4 * es)) == 0 && ((uintptr_t)y % (4 * es)) == 0;
+  const dim3 grid((unsigned)rows), blk(256);
+#define FASTAV_RMS_REG(TT, NVV) hipLaunchKernelGGL((k_rmsnorm_reg<TT, NVV>), grid, blk, 0, s, x, (const TT*)g, (TT*)y, d, eps)
+  if (reg && dtype == FASTAV_BF16) {
+    if (d <= 1024) FASTAV_RMS_REG(bf16_t, 1); else if (d <= 2048) FASTAV_RMS_REG(bf16_t, 2);
+    else if (d <= 4096) FASTAV_RMS_REG(bf16_t, 4); else FASTAV_RMS_REG(bf16_t, 8);
+  } else if (reg) {
+    if (d <= 1024) FASTAV_RMS_REG(float, 1); else if (d <= 2048) FASTAV_RMS_REG(float, 2);
+    else if (d <= 4096) FASTAV_RMS_REG(float, 4); else FASTAV_RMS_REG(float, 8);
+  } else if (dtype == FASTAV_BF16)
+    hipLaunchKernelGGL(k_rmsnorm<bf16_t>, grid, blk, 0, s, x, (const bf16_t*)g, (bf16_t*)y, d, eps);
   else
-    hipLaunchKernelGGL(k_rmsnorm<float>, dim3((unsigned)rows), dim3(256), 0, s, x, (const float*)g, (float*)y, d, eps);
+    hipLaunchKernelGGL(k_rmsnorm<float>, grid, blk, 0, s, x, (const float*)g, (float*)y, d, eps);
+#undef FASTAV_RMS_REG
   return check_launch("rmsnorm");
 }
 
@@ -166,11 +221,76 @@ __global__ void k_rope(T* __restrict__ x, int64_t row_stride, T* __restrict__ x2
   }
 }
 
+// (cos, sin) of pos * base^(-2i/dh) for every position below n_pos and frequency index i < dh/2, angles evaluated
+// in fp64 as above: computed once per prefill (a token keeps its original position through every prune), so that
+// the per-layer rotation is a pure streaming pass.
+__global__ void k_rope_table(float2* __restrict__ table, int n_pos, int half, double neg_log2_base_2_over_dh) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n_pos * half) return;
+  const int p = idx / half, i = idx % half;
+  double sd, cd;
+  sincos((double)p * exp2((double)i * neg_log2_base_2_over_dh), &sd, &cd);
+  table[idx] = make_float2((float)cd, (float)sd);
+}
+
+// Rotation from the table, bf16, head_dim a multiple of 16: a thread owns 8 consecutive frequency indices (16-byte
+// loads and stores of both halves of the pair) of every 8th head of one row, so the 64 bytes of table it needs are
+// read once for several heads; the lanes of a wave cover eight neighbouring heads at a time, whole 128-byte runs.
+constexpr int kRopeHeadGroups = 8;
+__global__ __launch_bounds__(256) void k_rope_tab(bf16_t* __restrict__ x, int64_t row_stride, bf16_t* __restrict__ x2,
+                                                  int64_t row_stride2, const int32_t* __restrict__ pos,
+                                                  const float2* __restrict__ table, int n_heads, int n_heads2, int head_dim,
+                                                  int64_t rows) {
+  const int half = head_dim >> 1, cph = half >> 3;               // 8-index chunks per head
+  const int per_row = kRopeHeadGroups * cph;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t r = idx / per_row;
+  if (r >= rows) return;
+  const int w = (int)(idx - r * per_row);
+  const int hg = w / cph, c = w % cph;
+  const float2* tr = table + (int64_t)pos[r] * half;
+  const f32x4_t t0 = *(const f32x4_t*)(tr + 8 * c), t1 = *(const f32x4_t*)(tr + 8 * c + 2);
+  const f32x4_t t2 = *(const f32x4_t*)(tr + 8 * c + 4), t3 = *(const f32x4_t*)(tr + 8 * c + 6);
+  const float cs[8] = {t0[0], t0[2], t1[0], t1[2], t2[0], t2[2], t3[0], t3[2]};
+  const float sn[8] = {t0[1], t0[3], t1[1], t1[3], t2[1], t2[3], t3[1], t3[3]};
+  for (int h = hg; h < n_heads + n_heads2; h += kRopeHeadGroups) {
+    bf16_t* p = (h < n_heads ? x + r * row_stride + h * head_dim : x2 + r * row_stride2 + (h - n_heads) * head_dim) + 8 * c;
+    const bf16x8_t a = *(const bf16x8_t*)p, b = *(const bf16x8_t*)(p + half);
+    bf16x8_t oa, ob;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float fa = (float)a[e], fb = (float)b[e];
+      oa[e] = (bf16_t)(fa * cs[e] - fb * sn[e]);
+      ob[e] = (bf16_t)(fb * cs[e] + fa * sn[e]);
+    }
+    *(bf16x8_t*)p = oa;
+    *(bf16x8_t*)(p + half) = ob;
+  }
+}
+
+size_t rope_table_bytes(int n_pos, int head_dim) { return (size_t)n_pos * (head_dim / 2) * sizeof(float2); }
+
+fastav_status_t launch_rope_table(void* table, int n_pos, int head_dim, float base, hipStream_t s) {
+  if (n_pos == 0) return FASTAV_OK;
+  const int half = head_dim / 2;
+  const double e = -log2((double)base) * 2.0 / (double)head_dim;
+  hipLaunchKernelGGL(k_rope_table, dim3((unsigned)ceil_div((int64_t)n_pos * half, 256)), dim3(256), 0, s, (float2*)table, n_pos, half, e);
+  return check_launch("rope_table");
+}
+
 fastav_status_t launch_rope2(void* x, int64_t row_stride, int n_heads, void* x2, int64_t row_stride2, int n_heads2,
-                             const int32_t* pos, int64_t rows, int head_dim, float base, int dtype, hipStream_t s) {
+                             const int32_t* pos, int64_t rows, int head_dim, float base, int dtype, hipStream_t s,
+                             const void* table) {
   const int nh = n_heads + n_heads2;
   if (rows == 0 || nh == 0) return FASTAV_OK;
   ProfScope prof(FASTAV_PROF_ROPE, 2.0 * rows * nh * head_dim * (dtype == FASTAV_BF16 ? 2.0 : 4.0), s);
+  if (table != nullptr && dtype == FASTAV_BF16 && head_dim % 16 == 0 && row_stride % 8 == 0 && row_stride2 % 8 == 0 &&
+      (((uintptr_t)x | (uintptr_t)x2 | (uintptr_t)table) % 16) == 0) {
+    const int64_t items = rows * kRopeHeadGroups * (head_dim / 16);
+    hipLaunchKernelGGL(k_rope_tab, dim3((unsigned)ceil_div(items, 256)), dim3(256), 0, s, (bf16_t*)x, row_stride, (bf16_t*)x2, row_stride2, pos,
+                       (const float2*)table, n_heads, n_heads2, head_dim, rows);
+    return check_launch("rope_tab");
+  }
   const int half = head_dim / 2;
   int hpb = 256 / half; if (hpb < 1) hpb = 1; if (hpb > nh) hpb = nh;
   const double e = -log2((double)base) * 2.0 / (double)head_dim;
@@ -184,8 +304,8 @@ fastav_status_t launch_rope2(void* x, int64_t row_stride, int n_heads, void* x2,
 }
 
 fastav_status_t launch_rope(void* x, int64_t row_stride, const int32_t* pos, int64_t rows, int n_heads, int head_dim,
-                            float base, int dtype, hipStream_t s) {
-  return launch_rope2(x, row_stride, n_heads, x, row_stride, 0, pos, rows, head_dim, base, dtype, s);
+                            float base, int dtype, hipStream_t s, const void* table) {
+  return launch_rope2(x, row_stride, n_heads, x, row_stride, 0, pos, rows, head_dim, base, dtype, s, table);
 }
 
 }  // namespace fastav

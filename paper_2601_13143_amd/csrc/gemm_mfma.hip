@@ -535,9 +535,10 @@ static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, void* scratch, size_
   if (tiles_big < 192) return launch_cfg_16<128, 128, 2, 2, EPI>(g, 0, g.N / OUT_SMALL, 1, s);
 
   // Whole rounds of big tiles, then the leftover tile columns with 128 x 128 tiles (two workgroups per CU)
-  // when the last round would leave three quarters of the CUs idle.
+  // when the last round would leave half of the CUs or more idle: up to 512 small tiles still are one round, and
+  // that round takes about 0.6 of a big one (QKV at 4096 tokens: 384 big tiles = 1 + 0.5 rounds, 175 -> ? us).
   const int64_t rem = tiles_big % kCUs;
-  if (tiles_big > kCUs && rem != 0 && rem <= kCUs / 4) {
+  if (tiles_big > kCUs && rem != 0 && rem <= kCUs / 2) {
     const int cols_full = (int)((tiles_big - rem) / tm);          // whole tile columns inside the full rounds
     if (cols_full > 0 && cols_full < tn) {
       fastav_status_t st = launch_big<EPI>(g, 0, cols_full, tiles_big - rem, s);

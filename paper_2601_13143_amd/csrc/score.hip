@@ -341,7 +341,7 @@ __global__ __launch_bounds__(256) void k_score_finalize(const float* __restrict_
         if (idx + u < P) {
           const float m = mls[2 * (idx + u)], il = mls[2 * (idx + u) + 1];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) s[e] += expf(L[u][e] - m) * il;
+          for (int e = 0; e < 4; ++e) s[e] = fmaf(expf(L[u][e] - m), il, s[e]);
         }
       }
     }
@@ -359,7 +359,7 @@ __global__ __launch_bounds__(256) void k_score_finalize(const float* __restrict_
     if (j >= n) return;
     const float* lp = logits + row0 + j;
     float s = 0.f;
-    for (int idx = 0; idx < P; ++idx) s += expf(lp[(int64_t)idx * T_total] - mls[2 * idx]) * mls[2 * idx + 1];
+    for (int idx = 0; idx < P; ++idx) s = fmaf(expf(lp[(int64_t)idx * T_total] - mls[2 * idx]), mls[2 * idx + 1], s);
     scores[row0 + j] = s / (float)P;
   }
 }

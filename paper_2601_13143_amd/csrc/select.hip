@@ -15,6 +15,7 @@ namespace fastav {
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kSelLdsKeys = 32768;          // samples up to this length keep their keys in LDS (128 KB)
+constexpr int kSelMaxHeads = 128;           // most query heads the fused Eq. 4 finish holds (max, 1/sum) for
 
 // fp32 -> unsigned key, larger key = better.  NaN ranks as -inf; -0.0 equals +0.0.
 __device__ __forceinline__ uint32_t score_key(float s) {
@@ -62,11 +63,10 @@ uint32_t select_random_key(uint32_t seed, int layer) { return mix32(seed + kGold
 // Key of candidate j (unprotected row) of sample b under the rule's order; never 0.
 // Random order: the draw is the top 24 bits of mix32(mix32(key + G (b + 1)) + position id) as a fraction in
 // [0, 1), ranked like a score, so that a token's draw does not depend on what was pruned before it.
-__device__ __forceinline__ uint32_t cand_key(const SelectRule& r, const float* scores, uint32_t sample_key, int row0,
-                                             int n, int j) {
+__device__ __forceinline__ uint32_t cand_key_of(const SelectRule& r, float score, uint32_t sample_key, int row0, int n, int j) {
   switch (r.order) {
-    case kSelHighScore: return score_key(scores[row0 + j]);
-    case kSelLowScore: return score_key(-scores[row0 + j]);
+    case kSelHighScore: return score_key(score);
+    case kSelLowScore: return score_key(-score);
     case kSelEarliest: return (uint32_t)(n - j);                        // n - j >= 1
     case kSelLatest: return (uint32_t)(j + 1);
     default: {
@@ -74,6 +74,11 @@ __device__ __forceinline__ uint32_t cand_key(const SelectRule& r, const float* s
       return score_key((float)(mix32(sample_key + p) >> 8) * 0x1p-24f);
     }
   }
+}
+__device__ __forceinline__ uint32_t cand_key(const SelectRule& r, const float* scores, uint32_t sample_key, int row0,
+                                             int n, int j) {
+  const bool by_score = r.order == kSelHighScore || r.order == kSelLowScore;
+  return cand_key_of(r, by_score ? scores[row0 + j] : 0.f, sample_key, row0, n, j);
 }
 
 template <bool KEYS_IN_LDS>
@@ -95,12 +100,34 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
   if (n <= 0) return;
   const uint32_t sample_key = mix32(rule.key + kGolden * (uint32_t)(b + 1));
 
-  // ---- load keys, count protected rows
+  // ---- load keys, count protected rows.  With the attention side output at hand (rule.logits: the last query
+  // row's scaled logits per head, rule.ml: that row's (max, sum of exp) per head) Eq. 4 is finished right here -
+  // s_j = 1/Hq sum_h exp(L[h][j] - m_h) / l_h, the terms added in head order exactly as k_score_finalize adds them
+  // - and goes straight into the key array (and to rule.scores_out for the caller), which saves a launch per prune.
   int my_prot = 0;
-  for (int j = tid; j < n; j += kSelThreads) {
-    const bool p = prot[row0 + j] != 0;
-    my_prot += p ? 1 : 0;
-    if (KEYS_IN_LDS) keys[j] = p ? 0u : cand_key(rule, scores, sample_key, row0, n, j);
+  if (KEYS_IN_LDS && rule.logits != nullptr) {
+    __shared__ float sh_ml[2 * kSelMaxHeads];
+    for (int h = tid; h < rule.n_heads; h += kSelThreads) {
+      const float* pm = rule.ml + ((int64_t)b * rule.n_heads + h) * 2;
+      sh_ml[2 * h] = pm[0]; sh_ml[2 * h + 1] = 1.0f / pm[1];
+    }
+    __syncthreads();
+    for (int j = tid; j < n; j += kSelThreads) {
+      const bool p = prot[row0 + j] != 0;
+      my_prot += p ? 1 : 0;
+      const float* lp = rule.logits + row0 + j;
+      float sc = 0.f;
+      for (int h = 0; h < rule.n_heads; ++h) sc = fmaf(expf(lp[(int64_t)h * rule.T] - sh_ml[2 * h]), sh_ml[2 * h + 1], sc);
+      sc = sc / (float)rule.n_heads;
+      if (rule.scores_out) rule.scores_out[row0 + j] = sc;
+      keys[j] = p ? 0u : cand_key_of(rule, sc, sample_key, row0, n, j);
+    }
+  } else {
+    for (int j = tid; j < n; j += kSelThreads) {
+      const bool p = prot[row0 + j] != 0;
+      my_prot += p ? 1 : 0;
+      if (KEYS_IN_LDS) keys[j] = p ? 0u : cand_key(rule, scores, sample_key, row0, n, j);
+    }
   }
   int n_prot;
   block_exclusive_scan(my_prot, wave_tot, n_prot);
@@ -218,11 +245,15 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
   }
 }
 
+bool select_fuses_score(int max_seqlen, int n_heads) { return max_seqlen <= kSelLdsKeys && n_heads >= 1 && n_heads <= kSelMaxHeads; }
+
 fastav_status_t launch_select(const float* scores, const uint8_t* prot, const int32_t* cu, const int32_t* cu_out,
                               int batch, int max_seqlen, int32_t* keep_idx, double bytes_hint, hipStream_t s,
                               SelectRule rule) {
   if (batch == 0 || max_seqlen == 0) return FASTAV_OK;
-  if ((rule.order == kSelHighScore || rule.order == kSelLowScore) && !scores) return fail(FASTAV_EINVAL, "select: this order needs scores");
+  if ((rule.order == kSelHighScore || rule.order == kSelLowScore) && !scores && !rule.logits) return fail(FASTAV_EINVAL, "select: this order needs scores");
+  if (rule.logits && (max_seqlen > kSelLdsKeys || rule.n_heads > kSelMaxHeads || rule.n_heads < 1 || !rule.ml))
+    return fail(FASTAV_EUNSUPPORTED, "select: the fused score finish needs samples of at most %d rows and at most %d heads", kSelLdsKeys, kSelMaxHeads);
   ProfScope prof(FASTAV_PROF_SELECT, bytes_hint, s);
   if (max_seqlen <= kSelLdsKeys) {
     const size_t shmem = (size_t)max_seqlen * sizeof(uint32_t);

@@ -604,6 +604,40 @@ def test_prefill_batched_equals_per_sample():
         row += n
 
 
+def test_prefill_fused_score_select_equals_separate_kernels():
+    """A FINE prune finishes Eq. 4 inside the selection kernel (one launch less per prune); with the switch off it
+    runs the separate finishing kernel.  Scores, kept rows, surviving positions and hidden states must agree bit for
+    bit, on a ragged batch with several FINE prunes."""
+    m = fi.Model(6, 512, 8, 2, 128, 1024, 1.0e4, 1e-6, "bf16")
+    base = fi.Workload("small6", m, [[(fi.VIDEO, 288), (fi.AUDIO, 150), (fi.TEXT, 30)], [(fi.VIDEO, 144), (fi.AUDIO, 97), (fi.TEXT, 9)],
+                                     [(fi.VIDEO, 1000), (fi.AUDIO, 301), (fi.TEXT, 5)]], [], seed=51)
+    w = fi.paper_schedule(base, global_keep=0.6, fine_drop=0.2)
+    weights = [fi.layer_weights(m, l, 13) for l in range(m.n_layers)]
+    dec = make_decoder(m, weights)
+    spans, offs = fi.span_table(w)
+    xd = dev(fi.embeddings(w), "bf16")
+    res = []
+    try:
+        for fused in (1, 0):
+            fa.fastav_set_option(fa.OPT_FUSED_SCORE_SELECT, fused)
+            o = dec.fastav_prefill(xd, fi.cu_seqlens(w), spans, offs, prune_tuples(w), 1, want_trace=True)
+            torch.cuda.synchronize()
+            res.append((o["x_out"].clone(), o["kept_pos"].clone(), [t.clone() for t in o["prune_keep_idx"]],
+                        [None if t is None else t.clone() for t in o["prune_scores"]]))
+    finally:
+        fa.fastav_set_option(fa.OPT_FUSED_SCORE_SELECT, 1)
+    (xa, pa, ka, sa), (xb, pb, kb, sb) = res
+    assert torch.equal(xa, xb) and torch.equal(pa, pb)
+    for i, (a, b) in enumerate(zip(ka, kb)):
+        assert torch.equal(a, b), i
+    n_scored = 0
+    for i, (a, b) in enumerate(zip(sa, sb)):
+        if a is not None:
+            assert torch.equal(a, b), i
+            n_scored += int(float(a.sum()) > 0)
+    assert n_scored == 3                                            # the three FINE prunes wrote their scores
+
+
 def test_prefill_n_last_greater_than_one():
     w, weights, x = _small_bf16()
     w.n_last = 3
