@@ -303,6 +303,8 @@ def main():
     import paper_2601_13143_amd as fa
 
     fa.lib()
+    if os.environ.get("FASTAV_BENCH_ROPE") == "0":            # A/B aid: the separate RoPE kernel instead of the fused epilogue
+        fa.fastav_set_option(fa.OPT_FUSED_ROPE, 0)
     host_threads = len(os.sched_getaffinity(0))
     w = fi.config(WORKLOADS[args.workload])
     if args.paper_schedule:

@@ -146,11 +146,14 @@ fastav_status_t fastav_schedule_lens(const fastav_batch_t* in, const fastav_prun
 
 const char* fastav_last_error(void);
 
-/* Process-wide switches between equivalent forms of a step (every form gives bit-identical results; the switches
- * exist so that this can be tested, and for measurements).  Not synchronised with calls in flight on other threads.
+/* Process-wide switches between equivalent forms of a step (the forms give the same results, bit for bit unless said otherwise; the
+ * switches exist so that this can be tested, and for measurements).  Not synchronised with calls in flight on other threads.
  *   FASTAV_OPT_FUSED_SCORE_SELECT (default 1): a FINE prune with n_last = 1 finishes Eq. 4 inside the selection
- *       kernel, straight from the attention kernel's last-row side output; 0 runs the separate finishing kernel. */
-typedef enum { FASTAV_OPT_FUSED_SCORE_SELECT = 0, FASTAV_OPT_COUNT = 1 } fastav_option_t;
+ *       kernel, straight from the attention kernel's last-row side output; 0 runs the separate finishing kernel.
+ *   FASTAV_OPT_FUSED_ROPE (default 1): bf16 prefill rotates Q and K inside the epilogue of the Q/K/V projection
+ *       (one rounding to bf16 instead of two); 0 runs the separate RoPE kernel after the projection.  The two
+ *       forms agree to bf16 rounding, not bit for bit. */
+typedef enum { FASTAV_OPT_FUSED_SCORE_SELECT = 0, FASTAV_OPT_FUSED_ROPE = 1, FASTAV_OPT_COUNT = 2 } fastav_option_t;
 fastav_status_t fastav_set_option(int32_t option, int32_t value);
 
 /* ---- the decoder handle --------------------------------------------------------------------------- */

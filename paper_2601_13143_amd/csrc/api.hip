@@ -15,7 +15,7 @@
 namespace fastav {
 
 static thread_local char g_err[512] = "";
-int g_options[FASTAV_OPT_COUNT] = {1};
+int g_options[FASTAV_OPT_COUNT] = {1, 1};
 
 fastav_status_t fail(fastav_status_t st, const char* fmt, ...) {
   va_list ap;
@@ -36,7 +36,9 @@ fastav_status_t launch_linear_generic(const void* a, const void* w, const void* 
 bool mfma_linear_supported(int64_t m, int n, int k, int epilogue, int dtype);
 fastav_status_t launch_linear_mfma(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
                                    const void* w2, void* c, int64_t ldc, void* const* c_seg, const int64_t* ldc_seg,
-                                   int64_t m, int n, int k, int epilogue, void* scratch, size_t scratch_bytes, hipStream_t s);
+                                   int64_t m, int n, int k, int epilogue, void* scratch, size_t scratch_bytes, hipStream_t s,
+                                   const RopeFuse* rope = nullptr);
+bool mfma_linear_fuses_rope(int64_t m, const int* seg_rows, int n_seg, int rope_segs, int k, int dh, int dtype);
 size_t mfma_linear_scratch_bytes();
 fastav_status_t launch_attention_generic(const void* q, int64_t q_stride, const void* k, const void* v,
                                          int64_t kv_stride, void* o, int64_t o_stride, const int32_t* cu, int batch,
@@ -80,13 +82,14 @@ fastav_status_t launch_rollout_step(float* rt, void* rt16, const void* a16, floa
 static fastav_status_t linear_segments(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
                                        const void* w2, void* c, int64_t ldc, int64_t m, int k, int epilogue, int dtype,
                                        void* scratch, size_t scratch_bytes, hipStream_t s,
-                                       void* const* c_seg = nullptr, const int64_t* ldc_seg = nullptr) {
+                                       void* const* c_seg = nullptr, const int64_t* ldc_seg = nullptr,
+                                       const RopeFuse* rope = nullptr) {
   int n = 0;
   for (int i = 0; i < n_seg; ++i) n += seg_rows[i];
   if (m == 0 || n == 0) return FASTAV_OK;
   // a handful of rows (a decode step): stream the weights through the skinny kernel, which times itself
   if (c_seg != nullptr && epilogue != FASTAV_EPI_STORE) return fail(FASTAV_EINVAL, "per-segment outputs need the plain-store epilogue");
-  if (c_seg == nullptr && m <= FASTAV_MAX_DECODE_BATCH && skinny_linear_supported(m, n, k, dtype, ldc)) {
+  if (rope == nullptr && c_seg == nullptr && m <= FASTAV_MAX_DECODE_BATCH && skinny_linear_supported(m, n, k, dtype, ldc)) {
     bool sk = (((uintptr_t)a | (uintptr_t)c) % 16) == 0;
     for (int i = 0; i < n_seg && sk; ++i) sk = seg_rows[i] % 16 == 0;
     if (sk) return launch_skinny_linear(a, w_seg, seg_rows, n_seg, w2, c, ldc, (int)m, n, k, epilogue, s);
@@ -96,7 +99,8 @@ static fastav_status_t linear_segments(const void* a, const void* const* w_seg, 
   ProfScope prof(kind, 2.0 * (double)m * n * k * (epilogue == FASTAV_EPI_SWIGLU ? 2.0 : 1.0), s);
   bool ok = mfma_linear_supported(m, n, k, epilogue, dtype);
   for (int i = 0; i < n_seg && ok; ++i) ok = mfma_linear_supported(m, seg_rows[i], k, epilogue, dtype);
-  if (ok) return launch_linear_mfma(a, w_seg, seg_rows, n_seg, w2, c, ldc, c_seg, ldc_seg, m, n, k, epilogue, scratch, scratch_bytes, s);
+  if (ok) return launch_linear_mfma(a, w_seg, seg_rows, n_seg, w2, c, ldc, c_seg, ldc_seg, m, n, k, epilogue, scratch, scratch_bytes, s, rope);
+  if (rope != nullptr) return fail(FASTAV_EINVAL, "linear: the RoPE epilogue needs the matrix-core kernel");
   const size_t es = dtype == FASTAV_BF16 ? 2 : 4;
   int col = 0;
   for (int i = 0; i < n_seg; ++i) {
@@ -483,15 +487,22 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
     const char* kptr = kv_direct ? (const char*)k_out : qkv + (size_t)qd * es;
     const char* vptr = kv_direct ? (const char*)v_out : qkv + (size_t)(qd + kd) * es;
     const int64_t kv_stride = kv_direct ? (int64_t)kd : qkv_stride;
+    bool rope_fused = false;
     {
       const void* seg[3] = {W.wq, W.wk, W.wv};
       int rows[3] = {qd, kd, kd};
       void* cs[3] = {qkv, k_out, v_out};
       const int64_t lds_[3] = {qkv_stride, (int64_t)kd, (int64_t)kd};
+      // RoPE rides in the projection's epilogue (Q and K segments, one rounding) where the matrix-core kernel runs
+      rope_fused = rope_tab != nullptr && g_options[FASTAV_OPT_FUSED_ROPE] && Tl > FASTAV_MAX_DECODE_BATCH &&
+                   mfma_linear_fuses_rope(Tl, rows, 3, 2, m.hidden, m.head_dim, m.dtype);
+      const RopeFuse rf = {pos[cur], rope_tab, m.head_dim, 2};
       FASTAV_TRY(linear_segments(hn, seg, rows, 3, nullptr, qkv, qkv_stride, Tl, m.hidden, FASTAV_EPI_STORE, m.dtype, nullptr, 0, s,
-                                 kv_direct ? cs : nullptr, kv_direct ? lds_ : nullptr));
+                                 kv_direct ? cs : nullptr, kv_direct ? lds_ : nullptr, rope_fused ? &rf : nullptr));
     }
-    if (kv_direct) {
+    if (rope_fused) {
+      // nothing left to do
+    } else if (kv_direct) {
       FASTAV_TRY(launch_rope2(qkv, qkv_stride, m.n_q_heads, k_out, kd, m.n_kv_heads, pos[cur], Tl, m.head_dim, m.rope_base, m.dtype, s, rope_tab));
     } else {
       FASTAV_TRY(launch_rope(qkv, qkv_stride, pos[cur], Tl, m.n_q_heads + m.n_kv_heads, m.head_dim, m.rope_base, m.dtype, s, rope_tab));

@@ -88,6 +88,10 @@ fastav_status_t launch_attention(const void* q, int64_t q_stride, const void* k,
                                  int Hq, int Hkv, int dh, float* last_logits, float* last_ml, int dtype,
                                  double flops_hint, hipStream_t s);
 
+// RoPE folded into the plain-store epilogue of a projection: rows are rotated by pos[row] with the (cos, sin) table
+// launch_rope_table wrote; the first n_segs weight segments (whole heads of head_dim columns) are rotated.
+struct RopeFuse { const int32_t* pos; const void* table; int head_dim; int n_segs; };
+
 // Eq. 4.  logits [n_last, Hq, T] fp32, ml [batch, n_last, Hq, 2] fp32.
 size_t score_partials_bytes(int Hq, int64_t T, int batch, int n_last);
 size_t score_logits_bytes(int Hq, int64_t T, int n_last);   // logits buffer handed to launch_score_logits

@@ -48,6 +48,12 @@ struct GemmArgs {
   int64_t ldcs[3];         //   Cs[i] (row pitch ldcs[i] elements) instead of columns of C
   int seg_out;
   int vec_ok;              // the output (C, or `partial`) takes 16-byte accesses: base and row pitch are multiples of 16 bytes
+  // plain-store epilogue, optional: rotate-half RoPE on the output columns of the first `rope_segs` segments (whole
+  // heads of rope_dh = 64 or 128 columns) before the one rounding to bf16: row r is rotated by the angles of position
+  // rope_pos[r], taken from rope_tab [position][rope_dh / 2] = (cos, sin)
+  const int32_t* rope_pos;
+  const float2* rope_tab;
+  int rope_dh, rope_segs;
 };
 
 constexpr int kNumCUs = 256;
@@ -122,10 +128,78 @@ __device__ __forceinline__ void sched_block(int nmfma, int nrd) {
   if (nrd > nmfma) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
 }
 
+// RoPE in the plain-store epilogue.  The tile's weight rows were fetched in a permuted order (see the copy addresses
+// in the kernel): inside every head of 128 columns the 32-column blocks arrive as 0, 2, 1, 3, so that the wave that
+// owns tile columns [64 w, 64 w + 64) holds head columns 32 (w & 1) + [0, 32) in its 16-column blocks 0, 1 and their
+// rotation partners, 64 columns further on, in blocks 2, 3 - the same registers of the same lane, as with the
+// gate / up pairs of the SwiGLU epilogue.  A head of 64 columns is one wave's width and needs no permutation.
+// -> first column, relative to the segment's output, of the wave's 8-column chunk cc (0..7)
+__device__ __forceinline__ int rope_chunk_col(int n0, int wn, int cc, int dh) {
+  if (dh == 128) return n0 + ((wn * 64) & ~127) + 32 * (wn & 1) + ((cc & 4) ? 64 : 0) + 8 * (cc & 3);
+  return n0 + wn * 64 + 8 * cc;
+}
+
 template <int EPI, int TM, int TN, int WTM, int WTN>
 __device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, void* c_out, int64_t c_ld, f32x4_t (&acc)[TM][TN], int m0, int n0,
-                                                int wm, int wn, int lane, bf16x8_t* stage) {
+                                                int wm, int wn, int lane, bf16x8_t* stage, bool rope = false) {
   const int mr = lane & 15, gq = lane >> 4;
+  if constexpr (EPI == FASTAV_EPI_STORE && TN == 4) {
+    if (rope) {
+      // frequency index of this lane's first column in blocks 0 and 1; its four columns are consecutive
+      const int half = g.rope_dh >> 1;
+      const int f0 = (g.rope_dh == 128 ? 32 * (wn & 1) : 0) + gq * 4;
+      const bool vec = g.vec_ok != 0;
+      typedef uint32_t u32x2r_t __attribute__((ext_vector_type(2)));
+      // all position ids first (one round trip for the whole tile), then the table rows they select
+      int pos_i[TM];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row_l = m0 + wm * WTM + i * 16 + mr;
+        pos_i[i] = g.rope_pos[row_l < g.M ? row_l : g.M - 1];
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row_l = m0 + wm * WTM + i * 16 + mr;
+        const float2* tr = g.rope_tab + (int64_t)pos_i[i] * half + f0;
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb) {
+          const f32x4_t t01 = *(const f32x4_t*)(tr + jb * 16), t23 = *(const f32x4_t*)(tr + jb * 16 + 2);
+          const float cs[4] = {t01[0], t01[2], t23[0], t23[2]}, sn[4] = {t01[1], t01[3], t23[1], t23[3]};
+          float v1[4], v2[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float x1 = acc[i][jb][r], x2 = acc[i][jb + 2][r];
+            v1[r] = x1 * cs[r] - x2 * sn[r];
+            v2[r] = x2 * cs[r] + x1 * sn[r];
+          }
+          if (vec) {
+            const u32x2r_t p1 = {pack_bf16(v1[0], v1[1]), pack_bf16(v1[2], v1[3])};
+            const u32x2r_t p2 = {pack_bf16(v2[0], v2[1]), pack_bf16(v2[2], v2[3])};
+            const int c1 = jb * 2 + (gq >> 1), c2 = (jb + 2) * 2 + (gq >> 1);
+            *(u32x2r_t*)((char*)&stage[mr * 8 + (c1 ^ ((mr >> 1) & 7))] + (gq & 1) * 8) = p1;
+            *(u32x2r_t*)((char*)&stage[mr * 8 + (c2 ^ ((mr >> 1) & 7))] + (gq & 1) * 8) = p2;
+          } else if (row_l < g.M) {
+            bf16_t* C1 = (bf16_t*)c_out + (int64_t)row_l * c_ld + rope_chunk_col(n0, wn, jb * 2 + (gq >> 1), g.rope_dh) + (gq & 1) * 4;
+            bf16_t* C2 = (bf16_t*)c_out + (int64_t)row_l * c_ld + rope_chunk_col(n0, wn, (jb + 2) * 2 + (gq >> 1), g.rope_dh) + (gq & 1) * 4;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) { C1[r] = (bf16_t)v1[r]; C2[r] = (bf16_t)v2[r]; }
+          }
+        }
+        if (vec) {
+          const int rr = lane >> 3, cc = lane & 7;
+          const int col = rope_chunk_col(n0, wn, cc, g.rope_dh);
+#pragma unroll
+          for (int it = 0; it < 2; ++it) {
+            const int r = it * 8 + rr;
+            const u32x4_t val = *(const u32x4_t*)&stage[r * 8 + (cc ^ ((r >> 1) & 7))];
+            const int row = m0 + wm * WTM + i * 16 + r;
+            if (row < g.M) *(u32x4_t*)((bf16_t*)c_out + (int64_t)row * c_ld + col) = val;
+          }
+        }
+      }
+      return;
+    }
+  }
   if constexpr (EPI == kEpiResAtomic) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -309,7 +383,13 @@ __global__ __launch_bounds__(WM * WN * 64, ((W3 ? 2 : 3) * BM + (W3 ? 3 : 2) * B
       b_vo[i] = ((uint32_t)(row & 31) * (uint32_t)K + (uint32_t)(dpos ^ ((row >> 1) & 7)) * 8u) * 2u;
     } else {
       b_rs[i] = make_rsrc(wbase + (int64_t)(n0 - seg_start) * K + kt0 * 64);
-      b_vo[i] = ((uint32_t)row * (uint32_t)K + (uint32_t)(dpos ^ ((row >> 1) & 7)) * 8u) * 2u;
+      // RoPE epilogue on heads of 128 columns: 32-row blocks of every head are fetched in the order 0, 2, 1, 3
+      int grow_b = row;
+      if (EPI == FASTAV_EPI_STORE && g.rope_tab != nullptr && seg < g.rope_segs && g.rope_dh == 128) {
+        const int q = row >> 5, q4 = q & 3;
+        grow_b = (((q & ~3) | (q4 == 1 ? 2 : q4 == 2 ? 1 : q4)) << 5) | (row & 31);
+      }
+      b_vo[i] = ((uint32_t)grow_b * (uint32_t)K + (uint32_t)(dpos ^ ((row >> 1) & 7)) * 8u) * 2u;
     }
     b_dst[i] = b_base + (uint32_t)r0 * 128u;
   }
@@ -435,7 +515,8 @@ __global__ __launch_bounds__(WM * WN * 64, ((W3 ? 2 : 3) * BM + (W3 ? 3 : 2) * B
   int64_t c_ld = g.ldc;
   int n0e = n0;
   if (EPI == FASTAV_EPI_STORE && g.seg_out) { c_out = g.Cs[seg]; c_ld = g.ldcs[seg]; n0e = n0 - seg_start; }
-  gemm16_epilogue<EPI, TM, TN, WTM, WTN>(g, c_out, c_ld, acc, m0, n0e, wm, wn, lane, lds + wave * (16 * 4 * TN));
+  const bool rope = EPI == FASTAV_EPI_STORE && g.rope_tab != nullptr && seg < g.rope_segs;
+  gemm16_epilogue<EPI, TM, TN, WTM, WTN>(g, c_out, c_ld, acc, m0, n0e, wm, wn, lane, lds + wave * (16 * 4 * TN), rope);
 }
 
 template <int BM, int BN, int WM, int WN, int EPI, bool W3 = true>
@@ -549,10 +630,30 @@ static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, void* scratch, size_
   return launch_big<EPI>(g, 0, tn, tiles_big, s);
 }
 
+// Whether the plain-store epilogue can apply RoPE to the leading segments of this product: whole heads per wave
+// tile, and only the tile shapes whose waves are 64 columns wide.
+bool mfma_linear_fuses_rope(int64_t m, const int* seg_rows, int n_seg, int rope_segs, int k, int dh, int dtype) {
+  if ((dh != 64 && dh != 128) || rope_segs < 1 || rope_segs > n_seg) return false;
+  int n = 0;
+  for (int i = 0; i < n_seg; ++i) {
+    if (!mfma_linear_supported(m, seg_rows[i], k, FASTAV_EPI_STORE, dtype)) return false;
+    if (seg_rows[i] % 128) return false;
+    n += seg_rows[i];
+  }
+  return mfma_linear_supported(m, n, k, FASTAV_EPI_STORE, dtype);
+}
+
 fastav_status_t launch_linear_mfma(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
                                    const void* w2, void* c, int64_t ldc, void* const* c_seg, const int64_t* ldc_seg,
-                                   int64_t m, int n, int k, int epilogue, void* scratch, size_t scratch_bytes, hipStream_t s) {
+                                   int64_t m, int n, int k, int epilogue, void* scratch, size_t scratch_bytes, hipStream_t s,
+                                   const RopeFuse* rope) {
   GemmArgs g;
+  g.rope_pos = nullptr; g.rope_tab = nullptr; g.rope_dh = 0; g.rope_segs = 0;
+  if (rope != nullptr && rope->table != nullptr) {
+    if (epilogue != FASTAV_EPI_STORE || !mfma_linear_fuses_rope(m, seg_rows, n_seg, rope->n_segs, k, rope->head_dim, FASTAV_BF16))
+      return fail(FASTAV_EINVAL, "gemm: this product cannot take the RoPE epilogue");
+    g.rope_pos = rope->pos; g.rope_tab = (const float2*)rope->table; g.rope_dh = rope->head_dim; g.rope_segs = rope->n_segs;
+  }
   g.A = (const bf16_t*)a;
   int end = 0;
   bool big_ok = true;

@@ -474,9 +474,10 @@ def _check_prefill(w: fi.Workload, out, ref, x_scale_from_ref=True):
                     assert p in pos_to_local, (b, i, p, "differs, yet was never within a tie band")
                     assert abs(s_ref[pos_to_local[p]] - kth) <= TIE_BAND, (b, i, p, s_ref[pos_to_local[p]], kth)
                 # beyond the literal band (loose where scores are ~1/n): bf16 noise may only exchange a small part of
-                # the kept set.  Measured on the full-size configurations: 0.3-0.7 % of k exchanged per prune
-                # (profiles/parity_cfg*.txt); the cap is 1 % of k exchanged = 2 % of k in the symmetric difference
-                assert len(diff) <= max(4, int(0.02 * pr["k"])), (b, i, len(diff), pr["k"])
+                # the kept set.  Measured on the full-size configurations: 0.3-1.0 % of k exchanged per prune, moving by
+                # a few tokens between builds whose bf16 rounding differs (profiles/parity_cfg*.txt); the cap is 1.5 %
+                # of k exchanged = 3 % of k in the symmetric difference
+                assert len(diff) <= max(4, int(0.03 * pr["k"])), (b, i, len(diff), pr["k"])
             stats["flips_per_prune"].append((b, i, len(diff) // 2, pr["k"]))
             stats["flipped"] += (len(diff) + 1) // 2
             # diagnostics: overlap of the two kept sets, and how many differing tokens lie outside a STRICT band
@@ -638,6 +639,45 @@ def test_prefill_fused_score_select_equals_separate_kernels():
     assert n_scored == 3                                            # the three FINE prunes wrote their scores
 
 
+@pytest.mark.parametrize("dh,Hq,Hkv,hidden", [(128, 8, 2, 512), (64, 8, 4, 512), (128, 32, 8, 1024)])
+def test_prefill_rope_in_the_projection_epilogue(dh, Hq, Hkv, hidden):
+    """bf16 prefill rotates Q and K inside the epilogue of the Q/K/V projection (one rounding); with the switch off
+    the separate RoPE kernel runs on the rounded projection (two roundings).  Both must give the oracle's rotated
+    keys at the stage tolerance (the first layer's cache: no pruning before it, original positions), agree with each
+    other to bf16 rounding, and leave V alone.  Ragged batch: row tiles with a tail, small and large tile shapes."""
+    m = fi.Model(2, hidden, Hq, Hkv, dh, 1024, 1.0e4, 1e-6, "bf16")
+    w = fi.Workload("rope", m, [[(fi.VIDEO, 700), (fi.AUDIO, 150), (fi.TEXT, 30)], [(fi.VIDEO, 144), (fi.AUDIO, 97), (fi.TEXT, 9)]],
+                    [fi.Prune(1, fi.GLOBAL, 0.6)], seed=61)
+    weights = [fi.layer_weights(m, l, 17) for l in range(m.n_layers)]
+    x = fi.embeddings(w)
+    dec = make_decoder(m, weights)
+    spans, offs = fi.span_table(w)
+    xd = dev(x, "bf16")
+    res = {}
+    try:
+        for fused in (1, 0):
+            fa.fastav_set_option(fa.OPT_FUSED_ROPE, fused)
+            for want_kv in (True, False):                          # K/V produced in the caller's cache, or in the workspace
+                o = dec.fastav_prefill(xd, fi.cu_seqlens(w), spans, offs, prune_tuples(w), 1, want_kv=want_kv)
+                torch.cuda.synchronize()
+                res[(fused, want_kv)] = (o["x_out"].clone(), [(k.clone(), v.clone()) for k, v in o["kv"]] if want_kv else None)
+    finally:
+        fa.fastav_set_option(fa.OPT_FUSED_ROPE, 1)
+    ref = orc.prefill(w, weights, x)
+    rk = np.concatenate([ref[b]["kv"][0][0] for b in range(len(ref))])
+    rv = np.concatenate([ref[b]["kv"][0][1] for b in range(len(ref))])
+    for fused in (1, 0):
+        k0, v0 = res[(fused, True)][1][0]
+        assert_close(host(k0).reshape(rk.shape), rk, "bf16", what=f"K layer 0, fused={fused}")
+        assert_close(host(v0).reshape(rv.shape), rv, "bf16", what=f"V layer 0, fused={fused}")
+        assert torch.equal(res[(fused, True)][0], res[(fused, False)][0])      # cache or workspace: the same forward
+    assert torch.equal(res[(1, True)][1][0][1], res[(0, True)][1][0][1])       # V of layer 0 is untouched by either form
+    xa, xb = host(res[(1, True)][0]), host(res[(0, True)][0])
+    assert rel_l2(xa, xb) <= 1e-2
+    k_f, k_u = host(res[(1, True)][1][0][0]), host(res[(0, True)][1][0][0])
+    assert np.max(np.abs(k_f - k_u)) <= 2e-2 * max(1.0, np.abs(k_u).max())
+
+
 def test_prefill_n_last_greater_than_one():
     w, weights, x = _small_bf16()
     w.n_last = 3
@@ -733,7 +773,7 @@ def _record_parity(cfg, w, st):
             f.write("sample  x_rel_l2  x_max_abs_over_rms\n")
             for b in range(len(w.samples)):
                 f.write(f"{b:6d}  {st[f'x_rel_l2_{b}']:.4e}  {st[f'x_max_abs_over_rms_{b}']:.4e}\n")
-            f.write("limits asserted: x_rel_l2 <= 3e-2, x_max_abs_over_rms <= 0.25, tokens exchanged per prune <= max(2, 1 % of k), "
+            f.write("limits asserted: x_rel_l2 <= 3e-2, x_max_abs_over_rms <= 0.25, tokens exchanged per prune <= max(2, 1.5 % of k), "
                     "every exchanged token within 1e-3 of the k-th score\n")
             f.write("sample  prune  kept_k  tokens_exchanged  share_of_k  jaccard  differing_tokens_outside_1pct_band_of_kth_score\n")
             for (b, i, fl, k), (_, _, jac), (_, _, ns) in zip(st["flips_per_prune"], st["jaccard"], st["outside_strict_band"]):
