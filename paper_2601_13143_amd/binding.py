@@ -14,7 +14,8 @@ import numpy as np
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libfastav.so")
+# FASTAV_LIBRARY selects another build of the same library (e.g. the host-sanitized one the CPU tests make)
+LIB_PATH = os.environ.get("FASTAV_LIBRARY") or os.path.join(HERE, "libfastav.so")
 
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, 1, 2, 3, 4
 TEXT, VIDEO, AUDIO = 0, 1, 2
