@@ -152,8 +152,12 @@ const char* fastav_last_error(void);
  *       kernel, straight from the attention kernel's last-row side output; 0 runs the separate finishing kernel.
  *   FASTAV_OPT_FUSED_ROPE (default 1): bf16 prefill rotates Q and K inside the epilogue of the Q/K/V projection
  *       (one rounding to bf16 instead of two); 0 runs the separate RoPE kernel after the projection.  The two
- *       forms agree to bf16 rounding, not bit for bit. */
-typedef enum { FASTAV_OPT_FUSED_SCORE_SELECT = 0, FASTAV_OPT_FUSED_ROPE = 1, FASTAV_OPT_COUNT = 2 } fastav_option_t;
+ *       forms agree to bf16 rounding, not bit for bit.
+ *   FASTAV_OPT_FUSED_SPLITK_NORM (default 1): in the prefill, a residual projection that splits K over workgroups
+ *       (few output tiles: the pruned layers) leaves the ordered sum of its partial tiles to the RMSNorm that reads
+ *       the residual next; 0 runs the separate reduction kernel.  Same additions in the same order. */
+typedef enum { FASTAV_OPT_FUSED_SCORE_SELECT = 0, FASTAV_OPT_FUSED_ROPE = 1, FASTAV_OPT_FUSED_SPLITK_NORM = 2,
+               FASTAV_OPT_COUNT = 3 } fastav_option_t;
 fastav_status_t fastav_set_option(int32_t option, int32_t value);
 
 /* ---- the decoder handle --------------------------------------------------------------------------- */

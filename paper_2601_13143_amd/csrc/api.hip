@@ -15,7 +15,7 @@
 namespace fastav {
 
 static thread_local char g_err[512] = "";
-int g_options[FASTAV_OPT_COUNT] = {1, 1};
+int g_options[FASTAV_OPT_COUNT] = {1, 1, 1};
 
 fastav_status_t fail(fastav_status_t st, const char* fmt, ...) {
   va_list ap;
@@ -37,7 +37,7 @@ bool mfma_linear_supported(int64_t m, int n, int k, int epilogue, int dtype);
 fastav_status_t launch_linear_mfma(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
                                    const void* w2, void* c, int64_t ldc, void* const* c_seg, const int64_t* ldc_seg,
                                    int64_t m, int n, int k, int epilogue, void* scratch, size_t scratch_bytes, hipStream_t s,
-                                   const RopeFuse* rope = nullptr);
+                                   const RopeFuse* rope = nullptr, SplitKPending* pend = nullptr);
 bool mfma_linear_fuses_rope(int64_t m, const int* seg_rows, int n_seg, int rope_segs, int k, int dh, int dtype);
 size_t mfma_linear_scratch_bytes();
 fastav_status_t launch_attention_generic(const void* q, int64_t q_stride, const void* k, const void* v,
@@ -83,7 +83,8 @@ static fastav_status_t linear_segments(const void* a, const void* const* w_seg, 
                                        const void* w2, void* c, int64_t ldc, int64_t m, int k, int epilogue, int dtype,
                                        void* scratch, size_t scratch_bytes, hipStream_t s,
                                        void* const* c_seg = nullptr, const int64_t* ldc_seg = nullptr,
-                                       const RopeFuse* rope = nullptr) {
+                                       const RopeFuse* rope = nullptr, SplitKPending* pend = nullptr) {
+  if (pend != nullptr) *pend = SplitKPending();
   int n = 0;
   for (int i = 0; i < n_seg; ++i) n += seg_rows[i];
   if (m == 0 || n == 0) return FASTAV_OK;
@@ -99,7 +100,7 @@ static fastav_status_t linear_segments(const void* a, const void* const* w_seg, 
   ProfScope prof(kind, 2.0 * (double)m * n * k * (epilogue == FASTAV_EPI_SWIGLU ? 2.0 : 1.0), s);
   bool ok = mfma_linear_supported(m, n, k, epilogue, dtype);
   for (int i = 0; i < n_seg && ok; ++i) ok = mfma_linear_supported(m, seg_rows[i], k, epilogue, dtype);
-  if (ok) return launch_linear_mfma(a, w_seg, seg_rows, n_seg, w2, c, ldc, c_seg, ldc_seg, m, n, k, epilogue, scratch, scratch_bytes, s, rope);
+  if (ok) return launch_linear_mfma(a, w_seg, seg_rows, n_seg, w2, c, ldc, c_seg, ldc_seg, m, n, k, epilogue, scratch, scratch_bytes, s, rope, pend);
   if (rope != nullptr) return fail(FASTAV_EINVAL, "linear: the RoPE epilogue needs the matrix-core kernel");
   const size_t es = dtype == FASTAV_BF16 ? 2 : 4;
   int col = 0;
@@ -113,10 +114,11 @@ static fastav_status_t linear_segments(const void* a, const void* const* w_seg, 
 }
 
 fastav_status_t launch_linear(const void* a, const void* w, const void* w2, void* c, int64_t m, int n, int k,
-                              int epilogue, int dtype, void* scratch, size_t scratch_bytes, hipStream_t s) {
+                              int epilogue, int dtype, void* scratch, size_t scratch_bytes, hipStream_t s,
+                              SplitKPending* pend) {
   const void* seg[1] = {w};
   int rows[1] = {n};
-  return linear_segments(a, seg, rows, 1, w2, c, n, m, k, epilogue, dtype, scratch, scratch_bytes, s);
+  return linear_segments(a, seg, rows, 1, w2, c, n, m, k, epilogue, dtype, scratch, scratch_bytes, s, nullptr, nullptr, nullptr, pend);
 }
 
 fastav_status_t launch_attention(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
@@ -452,6 +454,7 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
   const int qd = m.n_q_heads * m.head_dim, kd = m.n_kv_heads * m.head_dim;
   const int64_t qkv_stride = qd + 2 * kd;                     // elements per row of the fused Q|K|V buffer
   int cur = 0, stage = 0, pi = 0;
+  SplitKPending pend_down;
   for (int l = 0; l < m.n_layers; ++l) {
     const fastav_layer_weights_t& W = h->w[l];
     // ---- GLOBAL prune on the layer input: positional selection, then compaction of the residual stream
@@ -477,7 +480,9 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
     const bool fine_scored = fine && prunes[pi].selector != FASTAV_SEL_RANDOM;   // Eq. 4 is needed
     const bool side = fine_scored && n_last == 1;
 
-    FASTAV_TRY(launch_rmsnorm(resid[cur], W.g_attn, hn, Tl, m.hidden, m.rms_eps, m.dtype, s));
+    // the previous layer's down projection may have left its split-K partial sums to this normalisation
+    FASTAV_TRY(launch_rmsnorm(resid[cur], W.g_attn, hn, Tl, m.hidden, m.rms_eps, m.dtype, s, &pend_down));
+    pend_down = SplitKPending();
     void* const k_out = out->kv_out ? out->kv_out[2 * l] : nullptr;
     void* const v_out = out->kv_out ? out->kv_out[2 * l + 1] : nullptr;
     // A layer that keeps all its tokens writes K and V straight into the caller's cache (the projection stores
@@ -550,10 +555,20 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
       if (!kv_direct && (k_out || v_out)) FASTAV_TRY(launch_gather(kvc, 2, nullptr, Tl, s));
     }
     const int64_t To = T_stage[stage];
-    FASTAV_TRY(launch_linear(attn_cur, W.wo, nullptr, resid[cur], To, m.hidden, qd, FASTAV_EPI_RESADD, m.dtype, gscr, ws.gemm_scratch_bytes, s));
-    FASTAV_TRY(launch_rmsnorm(resid[cur], W.g_mlp, hn, To, m.hidden, m.rms_eps, m.dtype, s));
+    // A split-K residual product leaves its ordered sum of partial tiles to the RMSNorm that follows, which reads
+    // the residual anyway (same additions in the same order as the separate reduction kernel, one launch less).
+    const bool defer = g_options[FASTAV_OPT_FUSED_SPLITK_NORM] != 0;
+    SplitKPending pend_o;
+    FASTAV_TRY(launch_linear(attn_cur, W.wo, nullptr, resid[cur], To, m.hidden, qd, FASTAV_EPI_RESADD, m.dtype, gscr, ws.gemm_scratch_bytes, s,
+                             defer ? &pend_o : nullptr));
+    FASTAV_TRY(launch_rmsnorm(resid[cur], W.g_mlp, hn, To, m.hidden, m.rms_eps, m.dtype, s, &pend_o));
     FASTAV_TRY(launch_linear(hn, W.w_gate, W.w_up, hmlp, To, m.mlp_dim, m.hidden, FASTAV_EPI_SWIGLU, m.dtype, nullptr, 0, s));
-    FASTAV_TRY(launch_linear(hmlp, W.w_down, nullptr, resid[cur], To, m.hidden, m.mlp_dim, FASTAV_EPI_RESADD, m.dtype, gscr, ws.gemm_scratch_bytes, s));
+    // the down projection's sum can wait for the next layer's first RMSNorm unless something reads the residual first:
+    // the last layer's output, a per-layer output, or a GLOBAL prune at the next layer's input
+    const bool next_reads_resid = l + 1 == m.n_layers || (out->layer_x_out && out->layer_x_out[l]) ||
+                                  (pi < n_prunes && prunes[pi].layer == l + 1 && prunes[pi].kind == FASTAV_GLOBAL);
+    FASTAV_TRY(launch_linear(hmlp, W.w_down, nullptr, resid[cur], To, m.hidden, m.mlp_dim, FASTAV_EPI_RESADD, m.dtype, gscr, ws.gemm_scratch_bytes, s,
+                             defer && !next_reads_resid ? &pend_down : nullptr));
     if (out->layer_x_out && out->layer_x_out[l])
       FASTAV_TRY(launch_copy_rows(resid[cur], (int64_t)m.hidden * 4, out->layer_x_out[l], (int64_t)m.hidden * 4, To, nullptr, s));
   }
@@ -693,7 +708,7 @@ fastav_status_t fastav_rmsnorm(const float* x, const void* g, void* y, int64_t r
   if (!x || !g || !y) return fail(FASTAV_EINVAL, "a pointer argument is NULL");
   if (rows < 0 || d < 1 || (dtype != FASTAV_BF16 && dtype != FASTAV_F32)) return fail(FASTAV_EINVAL, "bad rows/d/dtype");
   if ((d % 4 == 0) && ((uintptr_t)x % 16)) return fail(FASTAV_EINVAL, "x must be 16-byte aligned");
-  return launch_rmsnorm(x, g, y, rows, d, eps, dtype, (hipStream_t)stream);
+  return launch_rmsnorm(const_cast<float*>(x), g, y, rows, d, eps, dtype, (hipStream_t)stream);
 }
 
 fastav_status_t fastav_rope(void* x, int64_t row_stride, const int32_t* pos, int64_t rows, int32_t n_heads,

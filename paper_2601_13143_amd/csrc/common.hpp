@@ -68,8 +68,15 @@ fastav_status_t launch_to_f32(const void* x, float* y, int64_t n, int dtype, hip
 // dst_row_bytes_stride == 0: destination rows are packed
 fastav_status_t launch_copy_rows(const void* src, int64_t src_row_bytes_stride, void* dst, int64_t row_bytes,
                                  int64_t rows, const int32_t* idx, hipStream_t s, int64_t dst_row_bytes_stride = 0);
-fastav_status_t launch_rmsnorm(const float* x, const void* g, void* y, int64_t rows, int d, float eps, int dtype,
-                               hipStream_t s);
+// A residual update whose split-K partial sums have not been added yet: R[M][N] += sum over splits of
+// partial[s][M][N], in split order.  launch_linear fills it (splits = 0 if the product was not split) when asked to
+// leave the sum to the consumer; launch_rmsnorm can take it over (it reads the residual anyway), launch_splitk_reduce
+// finishes it on its own.
+struct SplitKPending { const float* partial = nullptr; int splits = 0; int64_t M = 0; int N = 0; };
+fastav_status_t launch_splitk_reduce(float* r, int64_t ldc, const SplitKPending& p, hipStream_t s);
+// pend (optional, splits > 0): x is first completed with the pending partial sums and written back, then normalised
+fastav_status_t launch_rmsnorm(float* x, const void* g, void* y, int64_t rows, int d, float eps, int dtype,
+                               hipStream_t s, const SplitKPending* pend = nullptr);
 // table (optional): (cos, sin) per (position, frequency index) as launch_rope_table writes it; positions in `pos`
 // must be below the n_pos it was built for.  Without it every launch evaluates the angles itself.
 size_t rope_table_bytes(int n_pos, int head_dim);
@@ -81,8 +88,10 @@ fastav_status_t launch_rope2(void* x, int64_t row_stride, int n_heads, void* x2,
                              const int32_t* pos, int64_t rows, int head_dim, float base, int dtype, hipStream_t s,
                              const void* table = nullptr);
 // scratch (optional): device memory for split-K partial tiles; without it small-M residual GEMMs are not split
+// pend (optional, residual epilogue): a split-K product leaves its partial sums pending instead of reducing them
 fastav_status_t launch_linear(const void* a, const void* w, const void* w2, void* c, int64_t m, int n, int k,
-                              int epilogue, int dtype, void* scratch, size_t scratch_bytes, hipStream_t s);
+                              int epilogue, int dtype, void* scratch, size_t scratch_bytes, hipStream_t s,
+                              SplitKPending* pend = nullptr);
 fastav_status_t launch_attention(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
                                  void* o, int64_t o_stride, const int32_t* cu, int batch, int64_t T, int max_seqlen,
                                  int Hq, int Hkv, int dh, float* last_logits, float* last_ml, int dtype,

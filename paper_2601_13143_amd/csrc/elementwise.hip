@@ -128,11 +128,14 @@ __global__ __launch_bounds__(256) void k_rmsnorm(const float* __restrict__ x, co
 
 // The same for rows of up to 1024 * NV floats with d a multiple of 4: the row is read ONCE, 16 bytes per lane and
 // load, kept in registers across the reduction, and written back 4 elements per store.
+// With `partial` (splits > 0) the row is first completed: x += partial[0] + partial[1] + ... (the pending split-K sums
+// of the residual projection that produced it, added in split order like k_splitk_reduce adds them) and written back.
 template <typename T, int NV>
-__global__ __launch_bounds__(256) void k_rmsnorm_reg(const float* __restrict__ x, const T* __restrict__ g,
-                                                     T* __restrict__ y, int d, float eps) {
+__global__ __launch_bounds__(256) void k_rmsnorm_reg(float* __restrict__ x, const T* __restrict__ g,
+                                                     T* __restrict__ y, int d, float eps,
+                                                     const float* __restrict__ partial, int splits, int64_t split_stride) {
   __shared__ float red[4];
-  const f32x4_t* xv = (const f32x4_t*)(x + (int64_t)blockIdx.x * d);
+  f32x4_t* xv = (f32x4_t*)(x + (int64_t)blockIdx.x * d);
   T* yr = y + (int64_t)blockIdx.x * d;
   const int n4 = d >> 2;
   f32x4_t v[NV];
@@ -141,6 +144,24 @@ __global__ __launch_bounds__(256) void k_rmsnorm_reg(const float* __restrict__ x
   for (int u = 0; u < NV; ++u) {
     const int i = threadIdx.x + u * 256;
     v[u] = (i < n4) ? xv[i] : f32x4_t{0.f, 0.f, 0.f, 0.f};
+  }
+  if (splits > 0) {
+    const f32x4_t* pv = (const f32x4_t*)(partial + (int64_t)blockIdx.x * d);
+    for (int sp = 0; sp < splits; ++sp) {
+#pragma unroll
+      for (int u = 0; u < NV; ++u) {
+        const int i = threadIdx.x + u * 256;
+        if (i < n4) {
+          const f32x4_t q = pv[(int64_t)sp * (split_stride / 4) + i];
+          v[u][0] += q[0]; v[u][1] += q[1]; v[u][2] += q[2]; v[u][3] += q[3];
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+      const int i = threadIdx.x + u * 256;
+      if (i < n4) xv[i] = v[u];
+    }
   }
 #pragma unroll
   for (int u = 0; u < NV; ++u) ss += v[u][0] * v[u][0] + v[u][1] * v[u][1] + v[u][2] * v[u][2] + v[u][3] * v[u][3];
@@ -170,14 +191,22 @@ __global__ __launch_bounds__(256) void k_rmsnorm_reg(const float* __restrict__ x
   }
 }
 
-fastav_status_t launch_rmsnorm(const float* x, const void* g, void* y, int64_t rows, int d, float eps, int dtype,
-                               hipStream_t s) {
+fastav_status_t launch_rmsnorm(float* x, const void* g, void* y, int64_t rows, int d, float eps, int dtype,
+                               hipStream_t s, const SplitKPending* pend) {
   if (rows == 0) return FASTAV_OK;
   ProfScope prof(FASTAV_PROF_RMSNORM, (double)rows * d * (4.0 + (dtype == FASTAV_BF16 ? 2.0 : 4.0)), s);
   const size_t es = dtype == FASTAV_BF16 ? 2 : 4;
   const bool reg = (d % 4) == 0 && d <= 8192 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)g % (4 * es)) == 0 && ((uintptr_t)y % (4 * es)) == 0;
+  const float* partial = nullptr;
+  int splits = 0;
+  int64_t split_stride = 0;
+  if (pend != nullptr && pend->splits > 0) {
+    const bool fits = reg && pend->N == d && pend->M == rows && ((uintptr_t)pend->partial % 16) == 0;
+    if (fits) { partial = pend->partial; splits = pend->splits; split_stride = pend->M * (int64_t)pend->N; }
+    else { fastav_status_t st = launch_splitk_reduce(x, d, *pend, s); if (st != FASTAV_OK) return st; }
+  }
   const dim3 grid((unsigned)rows), blk(256);
-#define FASTAV_RMS_REG(TT, NVV) hipLaunchKernelGGL((k_rmsnorm_reg<TT, NVV>), grid, blk, 0, s, x, (const TT*)g, (TT*)y, d, eps)
+#define FASTAV_RMS_REG(TT, NVV) hipLaunchKernelGGL((k_rmsnorm_reg<TT, NVV>), grid, blk, 0, s, x, (const TT*)g, (TT*)y, d, eps, partial, splits, split_stride)
   if (reg && dtype == FASTAV_BF16) {
     if (d <= 1024) FASTAV_RMS_REG(bf16_t, 1); else if (d <= 2048) FASTAV_RMS_REG(bf16_t, 2);
     else if (d <= 4096) FASTAV_RMS_REG(bf16_t, 4); else FASTAV_RMS_REG(bf16_t, 8);

@@ -557,6 +557,14 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(float* __restrict__ R, in
   }
 }
 
+fastav_status_t launch_splitk_reduce(float* r, int64_t ldc, const SplitKPending& p, hipStream_t s) {
+  if (p.splits <= 0 || p.M == 0) return FASTAV_OK;
+  const int64_t total = p.M * (p.N / 4);
+  const unsigned blocks = (unsigned)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
+  hipLaunchKernelGGL(k_splitk_reduce, dim3(blocks), dim3(256), 0, s, r, ldc, p.partial, (int)p.M, p.N, p.splits);
+  return check_launch("splitk_reduce");
+}
+
 constexpr int kCUs = kNumCUs;
 
 // 256 x 256 tiles.  A residual epilogue over several rounds of tiles uses the hardware-add form (it overlaps
@@ -574,7 +582,7 @@ constexpr size_t kSplitKScratchBytes = (size_t)2 * kCUs * 256 * 256 * sizeof(flo
 size_t mfma_linear_scratch_bytes() { return kSplitKScratchBytes; }
 
 template <int EPI>
-static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, void* scratch, size_t scratch_bytes, hipStream_t s) {
+static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, void* scratch, size_t scratch_bytes, hipStream_t s, SplitKPending* pend) {
   constexpr int OUT_BIG = (EPI == FASTAV_EPI_SWIGLU) ? 128 : 256, OUT_SMALL = OUT_BIG / 2;
   const int tm = (g.M + 255) / 256;
   const int tn = g.N / OUT_BIG;                         // tile columns of the 256 x 256 tiling (valid if big_ok)
@@ -606,6 +614,10 @@ static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, void* scratch, size_
       gp.vec_ok = ((uintptr_t)scratch % 16 == 0) ? 1 : 0;   // partial rows are N floats, N a multiple of 128
       fastav_status_t st = launch_cfg_16<256, 256, 2, 4, kEpiPartial>(gp, 0, tn, best, s);
       if (st != FASTAV_OK) return st;
+      if (pend != nullptr && g.ldc == g.N) {                 // the consumer adds the partial sums
+        pend->partial = (const float*)scratch; pend->splits = best; pend->M = g.M; pend->N = g.N;
+        return FASTAV_OK;
+      }
       const int64_t total = (int64_t)g.M * (g.N / 4);
       const unsigned blocks = (unsigned)(ceil_div(total, 256) < 4096 ? ceil_div(total, 256) : 4096);
       hipLaunchKernelGGL(k_splitk_reduce, dim3(blocks), dim3(256), 0, s, (float*)g.C, g.ldc, (const float*)scratch, g.M, g.N, best);
@@ -646,8 +658,9 @@ bool mfma_linear_fuses_rope(int64_t m, const int* seg_rows, int n_seg, int rope_
 fastav_status_t launch_linear_mfma(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
                                    const void* w2, void* c, int64_t ldc, void* const* c_seg, const int64_t* ldc_seg,
                                    int64_t m, int n, int k, int epilogue, void* scratch, size_t scratch_bytes, hipStream_t s,
-                                   const RopeFuse* rope) {
+                                   const RopeFuse* rope, SplitKPending* pend) {
   GemmArgs g;
+  if (pend != nullptr) *pend = SplitKPending();
   g.rope_pos = nullptr; g.rope_tab = nullptr; g.rope_dh = 0; g.rope_segs = 0;
   if (rope != nullptr && rope->table != nullptr) {
     if (epilogue != FASTAV_EPI_STORE || !mfma_linear_fuses_rope(m, seg_rows, n_seg, rope->n_segs, k, rope->head_dim, FASTAV_BF16))
@@ -682,9 +695,9 @@ fastav_status_t launch_linear_mfma(const void* a, const void* const* w_seg, cons
     }
   }
   if (((uintptr_t)a | (uintptr_t)w_seg[0]) % 16) return fail(FASTAV_EINVAL, "gemm: A and W must be 16-byte aligned");
-  if (epilogue == FASTAV_EPI_STORE) return launch_epi<FASTAV_EPI_STORE>(g, big_ok, scratch, scratch_bytes, s);
-  if (epilogue == FASTAV_EPI_RESADD) return launch_epi<FASTAV_EPI_RESADD>(g, big_ok, scratch, scratch_bytes, s);
-  return launch_epi<FASTAV_EPI_SWIGLU>(g, big_ok, scratch, scratch_bytes, s);
+  if (epilogue == FASTAV_EPI_STORE) return launch_epi<FASTAV_EPI_STORE>(g, big_ok, scratch, scratch_bytes, s, nullptr);
+  if (epilogue == FASTAV_EPI_RESADD) return launch_epi<FASTAV_EPI_RESADD>(g, big_ok, scratch, scratch_bytes, s, pend);
+  return launch_epi<FASTAV_EPI_SWIGLU>(g, big_ok, scratch, scratch_bytes, s, nullptr);
 }
 
 }  // namespace fastav

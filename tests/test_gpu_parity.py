@@ -678,6 +678,42 @@ def test_prefill_rope_in_the_projection_epilogue(dh, Hq, Hkv, hidden):
     assert np.max(np.abs(k_f - k_u)) <= 2e-2 * max(1.0, np.abs(k_u).max())
 
 
+def test_prefill_splitk_sum_left_to_the_next_rmsnorm_is_the_same_forward():
+    """The residual projections of short sequences split K over workgroups; the ordered sum of their partial tiles is
+    then done by the RMSNorm that follows (or, where something else reads the residual first - a per-layer output, a
+    GLOBAL prune, the end of the stack - by the reduction kernel).  Every combination must give the same bits as
+    always reducing separately."""
+    m = fi.Model(5, 512, 8, 2, 128, 1024, 1.0e4, 1e-6, "bf16")
+    w = fi.Workload("splitk", m, [[(fi.VIDEO, 288), (fi.AUDIO, 150), (fi.TEXT, 30)], [(fi.VIDEO, 1000), (fi.AUDIO, 301), (fi.TEXT, 5)]],
+                    [fi.Prune(2, fi.GLOBAL, 0.6), fi.Prune(3, fi.FINE, 0.7)], seed=71)
+    weights = [fi.layer_weights(m, l, 19) for l in range(m.n_layers)]
+    dec = make_decoder(m, weights)
+    spans, offs = fi.span_table(w)
+    xd = dev(fi.embeddings(w), "bf16")
+    res = {}
+    try:
+        for fused in (1, 0):
+            fa.fastav_set_option(fa.OPT_FUSED_SPLITK_NORM, fused)
+            for layers in (False, True):
+                o = dec.fastav_prefill(xd, fi.cu_seqlens(w), spans, offs, prune_tuples(w), 1, want_kv=True, want_layers=layers)
+                torch.cuda.synchronize()
+                res[(fused, layers)] = (o["x_out"].clone(), o["kept_pos"].clone(), [k.clone() for k, _ in o["kv"]],
+                                        [t.clone() for t in o["layer_x"]] if layers else None)
+    finally:
+        fa.fastav_set_option(fa.OPT_FUSED_SPLITK_NORM, 1)
+    base = res[(0, True)]
+    for key, r in res.items():
+        assert torch.equal(r[0], base[0]) and torch.equal(r[1], base[1]), key
+        assert all(torch.equal(a, b) for a, b in zip(r[2], base[2])), key
+        if r[3] is not None:
+            assert all(torch.equal(a, b) for a, b in zip(r[3], base[3])), key
+    # and the forward is the oracle's
+    out, ref = _oracle_and_gpu(w, weights, fi.embeddings(w), want_kv=False)
+    st = _check_prefill(w, out, ref)
+    for b in range(2):
+        assert st[f"x_rel_l2_{b}"] <= 1e-2, st
+
+
 def test_prefill_n_last_greater_than_one():
     w, weights, x = _small_bf16()
     w.n_last = 3
