@@ -349,12 +349,14 @@ fastav_status_t fastav_profile_reset(void);
 
 /* "Achievable peak" probes, reported by the benchmark next to the datasheet peaks.
  * fastav_probe_mfma: every CU runs `iters` rounds of 32 independent v_mfma_f32_16x16x32_bf16 per wave (2 waves per
- * SIMD, no memory traffic); *flops_out (host, optional) receives the flops of the launch.  sink: dev, >= 2 MB,
- * never written in practice.
+ * SIMD, no memory traffic inside the loop); *flops_out (host, optional) receives the flops of the launch.
+ * operands: dev, optional: 64 KB of bf16 (16-byte aligned) that fill the operand registers - values drawn like the
+ * model's activations give the ceiling under realistic switching activity; NULL = small integer constants.
+ * sink: dev, >= 2 MB, never written in practice.
  * fastav_probe_read: one streaming pass over src (dev, 16-byte aligned, `bytes` >= 16 KB; the tail beyond a multiple
  * of 16 KB per workgroup step may be skipped), 16 bytes per lane and load.  sink: dev, >= 256 KB.
  * Both only enqueue the kernel; the caller times it with events on the same stream. */
-fastav_status_t fastav_probe_mfma(int32_t iters, float* sink, double* flops_out, void* stream);
+fastav_status_t fastav_probe_mfma(int32_t iters, const void* operands, float* sink, double* flops_out, void* stream);
 fastav_status_t fastav_probe_read(const void* src, size_t bytes, float* sink, void* stream);
 
 #ifdef __cplusplus

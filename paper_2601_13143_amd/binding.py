@@ -113,7 +113,7 @@ _SIGS = {
     "fastav_profile_enable": (C.c_int, [C.c_uint32]),
     "fastav_profile_collect": (C.c_int, [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
     "fastav_profile_reset": (C.c_int, []),
-    "fastav_probe_mfma": (C.c_int, [C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]),
+    "fastav_probe_mfma": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]),
     "fastav_probe_read": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
 }
 
@@ -507,10 +507,13 @@ def fastav_profile_reset() -> None:
     _check(lib().fastav_profile_reset())
 
 
-def fastav_probe_mfma(iters: int, sink: torch.Tensor) -> float:
-    """Enqueues the matrix-instruction-only probe on the current stream; -> flops of the launch."""
+def fastav_probe_mfma(iters: int, sink: torch.Tensor, operands: Optional[torch.Tensor] = None) -> float:
+    """Enqueues the matrix-instruction-only probe on the current stream; -> flops of the launch.  ``operands``:
+    optional bf16 tensor of at least 32768 elements that fills the operand registers."""
     fl = C.c_double()
-    _check(lib().fastav_probe_mfma(iters, sink.data_ptr(), C.byref(fl), _stream()))
+    if operands is not None and (operands.dtype != torch.bfloat16 or operands.numel() < 32768 or not operands.is_contiguous()):
+        raise ValueError("operands: contiguous bf16 tensor of at least 32768 elements")
+    _check(lib().fastav_probe_mfma(iters, operands.data_ptr() if operands is not None else None, sink.data_ptr(), C.byref(fl), _stream()))
     return fl.value
 
 

@@ -45,12 +45,24 @@ ProfScope::~ProfScope() {
 }
 
 // ---- "achievable peak" probes: what this chip sustains with nothing in the way, next to the datasheet figures.
-// A loop of independent bf16 matrix instructions only (no memory traffic), two waves per SIMD on every CU.
-__global__ __launch_bounds__(256, 2) void k_probe_mfma(int iters, float* __restrict__ sink) {
+// A loop of independent bf16 matrix instructions only (no memory traffic inside the loop), two waves per SIMD on
+// every CU.  The operand registers are filled once: with small integers, or from `operands` (8 A/B pairs of 16 bytes
+// per lane, rotated through) - what a matrix instruction costs in power, and with it the clock the chip holds,
+// depends on how many operand bits toggle, so operands drawn like a model's activations give a lower, more honest
+// ceiling than constants do (2.05 against 2.46 PFLOP/s on this part).
+__global__ __launch_bounds__(256, 2) void k_probe_mfma(int iters, const bf16x8_t* __restrict__ operands, float* __restrict__ sink) {
   const int lane = threadIdx.x & 63;
-  bf16x8_t a, b;
+  bf16x8_t a[8], b[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) { a[e] = (bf16_t)(float)((lane + e) & 3); b[e] = (bf16_t)(float)((lane * 3 + e) & 1); }
+  for (int i = 0; i < 8; ++i) {
+    if (operands != nullptr) {
+      a[i] = operands[(2 * i) * 256 + threadIdx.x];
+      b[i] = operands[(2 * i + 1) * 256 + threadIdx.x];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { a[i][e] = (bf16_t)(float)((lane + e) & 3); b[i][e] = (bf16_t)(float)((lane * 3 + e) & 1); }
+    }
+  }
   f32x4_t acc[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -58,12 +70,12 @@ __global__ __launch_bounds__(256, 2) void k_probe_mfma(int iters, float* __restr
 #pragma unroll
     for (int u = 0; u < 4; ++u)
 #pragma unroll
-      for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[i], 0, 0, 0);
+      for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[(i + u) & 7], acc[i], 0, 0, 0);
   }
   float t = 0.f;
 #pragma unroll
   for (int i = 0; i < 8; ++i) t += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
-  if (t == -1.0f) sink[blockIdx.x * 256 + threadIdx.x] = t;      // never true: keeps the loop alive
+  if (t == -1.2345e30f) sink[blockIdx.x * 256 + threadIdx.x] = t;      // never true in practice: keeps the loop alive
 }
 
 // A plain streaming read: every lane loads 16 bytes per step, workgroups walk memory in launch order.
@@ -118,10 +130,11 @@ fastav_status_t fastav_profile_collect(int32_t kind, double* total_ms, int64_t* 
   return FASTAV_OK;
 }
 
-fastav_status_t fastav_probe_mfma(int32_t iters, float* sink, double* flops_out, void* stream) {
+fastav_status_t fastav_probe_mfma(int32_t iters, const void* operands, float* sink, double* flops_out, void* stream) {
   if (iters < 1 || !sink) return fail(FASTAV_EINVAL, "probe: iters must be >= 1 and sink non-NULL");
+  if (operands && ((uintptr_t)operands % 16)) return fail(FASTAV_EINVAL, "probe: operands must be 16-byte aligned");
   const int blocks = 2048;                                      // 8 workgroups of 4 waves per CU
-  hipLaunchKernelGGL(k_probe_mfma, dim3(blocks), dim3(256), 0, (hipStream_t)stream, iters, sink);
+  hipLaunchKernelGGL(k_probe_mfma, dim3(blocks), dim3(256), 0, (hipStream_t)stream, iters, (const bf16x8_t*)operands, sink);
   if (flops_out) *flops_out = (double)blocks * 4.0 * iters * 32.0 * (2.0 * 16 * 16 * 32);
   return check_launch("probe_mfma");
 }
