@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
                                                         const int32_t* __restrict__ cu,
                                                         const int32_t* __restrict__ cu_out,
                                                         int32_t* __restrict__ keep_idx, SelectRule rule) {
-  extern __shared__ uint32_t keys[];                      // [n] when KEYS_IN_LDS; key 0 = protected (never a candidate)
+  extern __shared__ __align__(16) uint32_t keys[];                      // [n] when KEYS_IN_LDS; key 0 = protected (never a candidate)
   __shared__ int hist[kSelWaves][256];
   __shared__ int wave_tot[kSelWaves];
   __shared__ uint32_t sh_prefix;
@@ -117,7 +117,15 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
       my_prot += p ? 1 : 0;
       const float* lp = rule.logits + row0 + j;
       float sc = 0.f;
-      for (int h = 0; h < rule.n_heads; ++h) sc = fmaf(expf(lp[(int64_t)h * rule.T] - sh_ml[2 * h]), sh_ml[2 * h + 1], sc);
+      int h = 0;
+      for (; h + 8 <= rule.n_heads; h += 8) {               // eight loads in flight, then the terms in head order
+        float lg[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) lg[u] = lp[(int64_t)(h + u) * rule.T];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sc = fmaf(expf(lg[u] - sh_ml[2 * (h + u)]), sh_ml[2 * (h + u) + 1], sc);
+      }
+      for (; h < rule.n_heads; ++h) sc = fmaf(expf(lp[(int64_t)h * rule.T] - sh_ml[2 * h]), sh_ml[2 * h + 1], sc);
       sc = sc / (float)rule.n_heads;
       if (rule.scores_out) rule.scores_out[row0 + j] = sc;
       keys[j] = p ? 0u : cand_key_of(rule, sc, sample_key, row0, n, j);
@@ -195,49 +203,83 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
   const bool take_all = (need == n_cand), take_none = (need == 0);
 
   // ---- flags and ordered output.  Thread t owns the contiguous rows [t*per, (t+1)*per).
-  const int per = (n + kSelThreads - 1) / kSelThreads;
-  const int j_lo = tid * per, j_hi = (j_lo + per < n) ? j_lo + per : n;
-  int eq_cnt = 0;
-  for (int j = j_lo; j < j_hi; ++j) {
-    uint32_t key;
-    if (KEYS_IN_LDS) key = keys[j];
-    else key = prot[row0 + j] ? 0u : cand_key(rule, scores, sample_key, row0, n, j);
-    eq_cnt += (key != 0u && key == prefix) ? 1 : 0;
-  }
-  int dummy;
-  int eq_before = block_exclusive_scan(eq_cnt, wave_tot, dummy);
-  int keep_cnt = 0;
-  {
-    int e = eq_before;
-    for (int j = j_lo; j < j_hi; ++j) {
-      uint32_t key;
-      if (KEYS_IN_LDS) key = keys[j];
-      else key = prot[row0 + j] ? 0u : cand_key(rule, scores, sample_key, row0, n, j);
-      bool kp;
-      if (key == 0u) kp = true;                            // protected
-      else if (take_all) kp = true;
-      else if (take_none) kp = false;
-      else if (key > prefix) kp = true;
-      else if (key == prefix) { kp = e < need_eq; ++e; }
-      else kp = false;
-      keep_cnt += kp ? 1 : 0;
+  auto keeps = [&](uint32_t key, int& e) __attribute__((always_inline)) -> bool {
+    if (key == 0u) return true;                            // protected
+    if (take_all) return true;
+    if (take_none) return false;
+    if (key > prefix) return true;
+    if (key == prefix) { const bool kp = e < need_eq; ++e; return kp; }
+    return false;
+  };
+  if constexpr (KEYS_IN_LDS) {
+    // The thread's rows come out of LDS once, 16 bytes per read (`per` is rounded up to a multiple of four, so every
+    // thread starts on a 16-byte boundary; word-by-word reads at a stride of `per` words would pile a wave's lanes
+    // on a few banks).  One scan carries both running counts: the rows kept for sure (protected, or above the
+    // threshold) in the low half and the rows equal to the threshold in the high half - either total is at most
+    // kSelLdsKeys = 2^15, so the halves do not run into each other.
+    constexpr int kMaxPer = kSelLdsKeys / kSelThreads;
+    static_assert(kMaxPer % 4 == 0 && kSelLdsKeys <= 32768, "packed scan");
+    const int per = ((n + kSelThreads - 1) / kSelThreads + 3) & ~3;
+    const int j_lo = tid * per;
+    uint32_t kr[kMaxPer];
+#pragma unroll
+    for (int i = 0; i < kMaxPer; i += 4) {
+      if (i < per) {
+        const int j = j_lo + i;
+        if (j + 3 < n) {
+          const uint4 v = *(const uint4*)(keys + j);
+          kr[i] = v.x; kr[i + 1] = v.y; kr[i + 2] = v.z; kr[i + 3] = v.w;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) kr[i + e] = (j + e < n) ? keys[j + e] : 0u;
+        }
+      }
     }
-  }
-  int keep_before = block_exclusive_scan(keep_cnt, wave_tot, dummy);
-  {
+    int sure = 0, eq = 0;
+#pragma unroll
+    for (int i = 0; i < kMaxPer; ++i) {
+      if (i < per && j_lo + i < n) {
+        const uint32_t key = kr[i];
+        const bool cand = key != 0u;
+        eq += (cand && !take_all && !take_none && key == prefix) ? 1 : 0;
+        sure += (!cand || take_all || (!take_none && key > prefix)) ? 1 : 0;
+      }
+    }
+    int dummy;
+    const uint32_t before = (uint32_t)block_exclusive_scan((int)(((uint32_t)eq << 16) | (uint32_t)sure), wave_tot, dummy);
+    const int eq_before = (int)(before >> 16), sure_before = (int)(before & 0xFFFFu);
+    int e = eq_before, o = sure_before + (eq_before < need_eq ? eq_before : need_eq);
+#pragma unroll
+    for (int i = 0; i < kMaxPer; ++i) {
+      if (i < per && j_lo + i < n) {
+        if (keeps(kr[i], e)) {
+          if (o < k_keep) keep_idx[out0 + o] = row0 + j_lo + i;   // o < k_keep always unless k_keep < #protected
+          ++o;
+        }
+      }
+    }
+  } else {
+    const int per = (n + kSelThreads - 1) / kSelThreads;
+    const int j_lo = tid * per, j_hi = (j_lo + per < n) ? j_lo + per : n;
+    auto key_at = [&](int j) __attribute__((always_inline)) -> uint32_t {
+      return prot[row0 + j] ? 0u : cand_key(rule, scores, sample_key, row0, n, j);
+    };
+    int eq_cnt = 0;
+    for (int j = j_lo; j < j_hi; ++j) {
+      const uint32_t key = key_at(j);
+      eq_cnt += (key != 0u && key == prefix) ? 1 : 0;
+    }
+    int dummy;
+    const int eq_before = block_exclusive_scan(eq_cnt, wave_tot, dummy);
+    int keep_cnt = 0;
+    {
+      int e = eq_before;
+      for (int j = j_lo; j < j_hi; ++j) keep_cnt += keeps(key_at(j), e) ? 1 : 0;
+    }
+    const int keep_before = block_exclusive_scan(keep_cnt, wave_tot, dummy);
     int e = eq_before, o = keep_before;
     for (int j = j_lo; j < j_hi; ++j) {
-      uint32_t key;
-      if (KEYS_IN_LDS) key = keys[j];
-      else key = prot[row0 + j] ? 0u : cand_key(rule, scores, sample_key, row0, n, j);
-      bool kp;
-      if (key == 0u) kp = true;
-      else if (take_all) kp = true;
-      else if (take_none) kp = false;
-      else if (key > prefix) kp = true;
-      else if (key == prefix) { kp = e < need_eq; ++e; }
-      else kp = false;
-      if (kp) {
+      if (keeps(key_at(j), e)) {
         if (o < k_keep) keep_idx[out0 + o] = row0 + j;     // o < k_keep always unless k_keep < #protected
         ++o;
       }
