@@ -879,3 +879,32 @@ def test_prefill_and_decode_replay_from_a_hip_graph():
         other = dec.fastav_prefill(xd, cu, spans, offs, [], 1)
         torch.cuda.synchronize()
         assert other["x_out"].shape[0] == sum(w.seqlens)
+
+
+def test_achievable_peak_probes_run_and_report_their_work():
+    """The measurement aids of the benchmark: both enqueue one kernel, report the work of the launch and leave the sink
+    untouched; operands drawn like activations must not raise the matrix-only rate above the constant-operand one by
+    more than measurement noise (they toggle more bits, the chip holds a lower clock)."""
+    sink = torch.zeros(1 << 20, dtype=torch.float32, device="cuda")
+    ops = torch.randn(32768, device="cuda").bfloat16()
+
+    def rate(operands):
+        fa.fastav_probe_mfma(200, sink, operands)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fl = sum(fa.fastav_probe_mfma(2000, sink, operands) for _ in range(4))
+        e1.record()
+        torch.cuda.synchronize()
+        return fl, fl / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+    fl_c, r_c = rate(None)
+    fl_n, r_n = rate(ops)
+    assert fl_c == fl_n == 4 * 2048 * 4 * 2000 * 32 * (2 * 16 * 16 * 32)
+    assert 500.0 < r_n <= r_c * 1.05 and r_c < 2600.0, (r_c, r_n)      # TFLOP/s: below the datasheet peak, well above a stall
+    src = torch.zeros(1 << 24, dtype=torch.float32, device="cuda")
+    assert fa.fastav_probe_read(src, sink) == src.numel() * 4
+    torch.cuda.synchronize()
+    assert float(sink.abs().max()) == 0.0
+    with pytest.raises(ValueError):
+        fa.fastav_probe_mfma(10, sink, torch.zeros(16, device="cuda").bfloat16())

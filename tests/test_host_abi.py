@@ -237,3 +237,20 @@ def test_decode_step_rejects_bad_arguments_before_any_launch():
     assert lib.fastav_decode_step(f32, C.byref(di), fake, fake, 1 << 20, None) == B.EUNSUPPORTED   # fp32 model
     lib.fastav_destroy(h)
     lib.fastav_destroy(f32)
+
+
+def test_probes_and_options_reject_bad_arguments():
+    """The measurement aids validate on the host like every other entry point (no launch happens here)."""
+    lib = fa.lib()
+    fl = C.c_double()
+    assert lib.fastav_probe_mfma(0, None, 4096, C.byref(fl), None) == B.EINVAL            # iters < 1
+    assert lib.fastav_probe_mfma(10, None, None, C.byref(fl), None) == B.EINVAL           # no sink
+    assert lib.fastav_probe_mfma(10, 4096 + 8, 4096, C.byref(fl), None) == B.EINVAL       # operands off a 16-byte boundary
+    assert b"operands" in lib.fastav_last_error()
+    assert lib.fastav_probe_read(None, 1 << 20, 4096, None) == B.EINVAL
+    assert lib.fastav_probe_read(4096, 1024, 4096, None) == B.EINVAL                        # under 16 KB
+    assert lib.fastav_probe_read(4096 + 4, 1 << 20, 4096, None) == B.EINVAL                 # misaligned
+    assert lib.fastav_set_option(-1, 1) == B.EINVAL and lib.fastav_set_option(99, 1) == B.EINVAL
+    for opt in (B.OPT_FUSED_SCORE_SELECT, B.OPT_FUSED_ROPE, B.OPT_FUSED_SPLITK_NORM):
+        assert lib.fastav_set_option(opt, 0) == B.OK and lib.fastav_set_option(opt, 1) == B.OK
+
