@@ -67,8 +67,8 @@ __device__ __forceinline__ uint32_t cand_key_of(const SelectRule& r, float score
   switch (r.order) {
     case kSelHighScore: return score_key(score);
     case kSelLowScore: return score_key(-score);
-    case kSelEarliest: return (uint32_t)(n - j);                        // n - j >= 1
-    case kSelLatest: return (uint32_t)(j + 1);
+    case kSelEarliest:
+    case kSelLatest: return 1u;                                         // positional orders: decided by candidate rank, below
     default: {
       const uint32_t p = r.pos ? (uint32_t)r.pos[row0 + j] : (uint32_t)j;
       return score_key((float)(mix32(sample_key + p) >> 8) * 0x1p-24f);
@@ -112,23 +112,45 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
       sh_ml[2 * h] = pm[0]; sh_ml[2 * h + 1] = 1.0f / pm[1];
     }
     __syncthreads();
-    for (int j = tid; j < n; j += kSelThreads) {
-      const bool p = prot[row0 + j] != 0;
-      my_prot += p ? 1 : 0;
-      const float* lp = rule.logits + row0 + j;
-      float sc = 0.f;
-      int h = 0;
-      for (; h + 8 <= rule.n_heads; h += 8) {               // eight loads in flight, then the terms in head order
-        float lg[8];
+    // Two rows per round and sixteen heads per batch: 32 independent loads in flight per thread (the planes of the
+    // heads are T floats apart, so every load is a trip to L2 or beyond, and one workgroup has to cover the whole
+    // sample).  A row's terms are still added in head order.
+    for (int j = tid; j < n; j += 2 * kSelThreads) {
+      const int j1 = j + kSelThreads;
+      const bool two = j1 < n;
+      const float* lp0 = rule.logits + row0 + j;
+      const float* lp1 = rule.logits + row0 + (two ? j1 : j);
+      float sc0 = 0.f, sc1 = 0.f;
+      for (int h0 = 0; h0 < rule.n_heads; h0 += 16) {
+        float g0[16], g1[16];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) lg[u] = lp[(int64_t)(h + u) * rule.T];
+        for (int u = 0; u < 16; ++u) {
+          const int h = (h0 + u < rule.n_heads) ? h0 + u : rule.n_heads - 1;
+          g0[u] = lp0[(int64_t)h * rule.T];
+          g1[u] = lp1[(int64_t)h * rule.T];
+        }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) sc = fmaf(expf(lg[u] - sh_ml[2 * (h + u)]), sh_ml[2 * (h + u) + 1], sc);
+        for (int u = 0; u < 16; ++u) {
+          if (h0 + u < rule.n_heads) {
+            sc0 = fmaf(expf(g0[u] - sh_ml[2 * (h0 + u)]), sh_ml[2 * (h0 + u) + 1], sc0);
+            sc1 = fmaf(expf(g1[u] - sh_ml[2 * (h0 + u)]), sh_ml[2 * (h0 + u) + 1], sc1);
+          }
+        }
       }
-      for (; h < rule.n_heads; ++h) sc = fmaf(expf(lp[(int64_t)h * rule.T] - sh_ml[2 * h]), sh_ml[2 * h + 1], sc);
-      sc = sc / (float)rule.n_heads;
-      if (rule.scores_out) rule.scores_out[row0 + j] = sc;
-      keys[j] = p ? 0u : cand_key_of(rule, sc, sample_key, row0, n, j);
+      sc0 = sc0 / (float)rule.n_heads;
+      sc1 = sc1 / (float)rule.n_heads;
+      {
+        const bool p = prot[row0 + j] != 0;
+        my_prot += p ? 1 : 0;
+        if (rule.scores_out) rule.scores_out[row0 + j] = sc0;
+        keys[j] = p ? 0u : cand_key_of(rule, sc0, sample_key, row0, n, j);
+      }
+      if (two) {
+        const bool p = prot[row0 + j1] != 0;
+        my_prot += p ? 1 : 0;
+        if (rule.scores_out) rule.scores_out[row0 + j1] = sc1;
+        keys[j1] = p ? 0u : cand_key_of(rule, sc1, sample_key, row0, n, j1);
+      }
     }
   } else {
     for (int j = tid; j < n; j += kSelThreads) {
@@ -148,7 +170,14 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
   //      `need_eq` = how many candidates equal to the threshold are kept (lowest indices first).
   uint32_t prefix = 0, mask = 0;
   int need_eq = need;
-  if (need > 0 && need < n_cand) {
+  int eq_lo = 0;                                          // candidates equal to the threshold are kept from this rank on
+  const bool positional = rule.order == kSelEarliest || rule.order == kSelLatest;
+  if (positional && need > 0 && need < n_cand) {
+    // every candidate carries the same key: the first (earliest) or the last (latest) `need` of them in row order are
+    // kept by the rank rule alone, no pass over the keys is needed
+    prefix = 1u; mask = 0xFFFFFFFFu;
+    eq_lo = rule.order == kSelLatest ? n_cand - need : 0;
+  } else if (need > 0 && need < n_cand) {
     for (int shift = 24; shift >= 0; shift -= 8) {
       for (int i = tid; i < kSelWaves * 256; i += kSelThreads) (&hist[0][0])[i] = 0;
       __syncthreads();
@@ -208,7 +237,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
     if (take_all) return true;
     if (take_none) return false;
     if (key > prefix) return true;
-    if (key == prefix) { const bool kp = e < need_eq; ++e; return kp; }
+    if (key == prefix) { const bool kp = e >= eq_lo && e < eq_lo + need_eq; ++e; return kp; }
     return false;
   };
   if constexpr (KEYS_IN_LDS) {
@@ -248,7 +277,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const float* __restrict_
     int dummy;
     const uint32_t before = (uint32_t)block_exclusive_scan((int)(((uint32_t)eq << 16) | (uint32_t)sure), wave_tot, dummy);
     const int eq_before = (int)(before >> 16), sure_before = (int)(before & 0xFFFFu);
-    int e = eq_before, o = sure_before + (eq_before < need_eq ? eq_before : need_eq);
+    const int eq_kept_before = eq_before - eq_lo < 0 ? 0 : (eq_before - eq_lo < need_eq ? eq_before - eq_lo : need_eq);
+    int e = eq_before, o = sure_before + eq_kept_before;
 #pragma unroll
     for (int i = 0; i < kMaxPer; ++i) {
       if (i < per && j_lo + i < n) {
