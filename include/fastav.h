@@ -155,9 +155,12 @@ const char* fastav_last_error(void);
  *       forms agree to bf16 rounding, not bit for bit.
  *   FASTAV_OPT_FUSED_SPLITK_NORM (default 1): in the prefill, a residual projection that splits K over workgroups
  *       (few output tiles: the pruned layers) leaves the ordered sum of its partial tiles to the RMSNorm that reads
- *       the residual next; 0 runs the separate reduction kernel.  Same additions in the same order. */
+ *       the residual next; 0 runs the separate reduction kernel.  Same additions in the same order.
+ *   FASTAV_OPT_FUSED_GATHER_OPROJ (default 1): after a FINE prune the O projection (bf16) reads the surviving rows
+ *       of the attention output through the keep list in its operand copies; 0 compacts the attention output with
+ *       the other tensors first.  Same values into the same arithmetic. */
 typedef enum { FASTAV_OPT_FUSED_SCORE_SELECT = 0, FASTAV_OPT_FUSED_ROPE = 1, FASTAV_OPT_FUSED_SPLITK_NORM = 2,
-               FASTAV_OPT_COUNT = 3 } fastav_option_t;
+               FASTAV_OPT_FUSED_GATHER_OPROJ = 3, FASTAV_OPT_COUNT = 4 } fastav_option_t;
 fastav_status_t fastav_set_option(int32_t option, int32_t value);
 
 /* ---- the decoder handle --------------------------------------------------------------------------- */

@@ -527,6 +527,7 @@ def fastav_probe_read(src: torch.Tensor, sink: torch.Tensor) -> int:
 OPT_FUSED_SCORE_SELECT = 0
 OPT_FUSED_ROPE = 1
 OPT_FUSED_SPLITK_NORM = 2
+OPT_FUSED_GATHER_OPROJ = 3
 
 
 def fastav_set_option(option: int, value: int) -> None:

@@ -15,7 +15,7 @@
 namespace fastav {
 
 static thread_local char g_err[512] = "";
-int g_options[FASTAV_OPT_COUNT] = {1, 1, 1};
+int g_options[FASTAV_OPT_COUNT] = {1, 1, 1, 1};
 
 fastav_status_t fail(fastav_status_t st, const char* fmt, ...) {
   va_list ap;
@@ -37,7 +37,8 @@ bool mfma_linear_supported(int64_t m, int n, int k, int epilogue, int dtype);
 fastav_status_t launch_linear_mfma(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
                                    const void* w2, void* c, int64_t ldc, void* const* c_seg, const int64_t* ldc_seg,
                                    int64_t m, int n, int k, int epilogue, void* scratch, size_t scratch_bytes, hipStream_t s,
-                                   const RopeFuse* rope = nullptr, SplitKPending* pend = nullptr);
+                                   const RopeFuse* rope = nullptr, SplitKPending* pend = nullptr, RowGather rows = RowGather());
+bool mfma_linear_takes_rows(int k, int64_t n_src);
 bool mfma_linear_fuses_rope(int64_t m, const int* seg_rows, int n_seg, int rope_segs, int k, int dh, int dtype);
 size_t mfma_linear_scratch_bytes();
 fastav_status_t launch_attention_generic(const void* q, int64_t q_stride, const void* k, const void* v,
@@ -83,14 +84,15 @@ static fastav_status_t linear_segments(const void* a, const void* const* w_seg, 
                                        const void* w2, void* c, int64_t ldc, int64_t m, int k, int epilogue, int dtype,
                                        void* scratch, size_t scratch_bytes, hipStream_t s,
                                        void* const* c_seg = nullptr, const int64_t* ldc_seg = nullptr,
-                                       const RopeFuse* rope = nullptr, SplitKPending* pend = nullptr) {
+                                       const RopeFuse* rope = nullptr, SplitKPending* pend = nullptr, RowGather rows = RowGather()) {
   if (pend != nullptr) *pend = SplitKPending();
   int n = 0;
   for (int i = 0; i < n_seg; ++i) n += seg_rows[i];
   if (m == 0 || n == 0) return FASTAV_OK;
   // a handful of rows (a decode step): stream the weights through the skinny kernel, which times itself
   if (c_seg != nullptr && epilogue != FASTAV_EPI_STORE) return fail(FASTAV_EINVAL, "per-segment outputs need the plain-store epilogue");
-  if (rope == nullptr && c_seg == nullptr && m <= FASTAV_MAX_DECODE_BATCH && skinny_linear_supported(m, n, k, dtype, ldc)) {
+  if (rows.idx != nullptr && !linear_takes_rows(m, n, k, epilogue, dtype, rows.n_src)) return fail(FASTAV_EINVAL, "linear: this product cannot take a row list");
+  if (rows.idx == nullptr && rope == nullptr && c_seg == nullptr && m <= FASTAV_MAX_DECODE_BATCH && skinny_linear_supported(m, n, k, dtype, ldc)) {
     bool sk = (((uintptr_t)a | (uintptr_t)c) % 16) == 0;
     for (int i = 0; i < n_seg && sk; ++i) sk = seg_rows[i] % 16 == 0;
     if (sk) return launch_skinny_linear(a, w_seg, seg_rows, n_seg, w2, c, ldc, (int)m, n, k, epilogue, s);
@@ -100,7 +102,8 @@ static fastav_status_t linear_segments(const void* a, const void* const* w_seg, 
   ProfScope prof(kind, 2.0 * (double)m * n * k * (epilogue == FASTAV_EPI_SWIGLU ? 2.0 : 1.0), s);
   bool ok = mfma_linear_supported(m, n, k, epilogue, dtype);
   for (int i = 0; i < n_seg && ok; ++i) ok = mfma_linear_supported(m, seg_rows[i], k, epilogue, dtype);
-  if (ok) return launch_linear_mfma(a, w_seg, seg_rows, n_seg, w2, c, ldc, c_seg, ldc_seg, m, n, k, epilogue, scratch, scratch_bytes, s, rope, pend);
+  if (ok) return launch_linear_mfma(a, w_seg, seg_rows, n_seg, w2, c, ldc, c_seg, ldc_seg, m, n, k, epilogue, scratch, scratch_bytes, s, rope, pend, rows);
+  if (rows.idx != nullptr) return fail(FASTAV_EINVAL, "linear: the row list needs the matrix-core kernel");
   if (rope != nullptr) return fail(FASTAV_EINVAL, "linear: the RoPE epilogue needs the matrix-core kernel");
   const size_t es = dtype == FASTAV_BF16 ? 2 : 4;
   int col = 0;
@@ -113,12 +116,17 @@ static fastav_status_t linear_segments(const void* a, const void* const* w_seg, 
   return FASTAV_OK;
 }
 
+// The matrix-core kernel is the one that can read its A rows through a list; a handful of rows go to the skinny kernel.
+bool linear_takes_rows(int64_t m, int n, int k, int epilogue, int dtype, int64_t n_src) {
+  return m > FASTAV_MAX_DECODE_BATCH && mfma_linear_supported(m, n, k, epilogue, dtype) && mfma_linear_takes_rows(k, n_src);
+}
+
 fastav_status_t launch_linear(const void* a, const void* w, const void* w2, void* c, int64_t m, int n, int k,
                               int epilogue, int dtype, void* scratch, size_t scratch_bytes, hipStream_t s,
-                              SplitKPending* pend) {
+                              SplitKPending* pend, RowGather rows) {
   const void* seg[1] = {w};
-  int rows[1] = {n};
-  return linear_segments(a, seg, rows, 1, w2, c, n, m, k, epilogue, dtype, scratch, scratch_bytes, s, nullptr, nullptr, nullptr, pend);
+  int seg_rows[1] = {n};
+  return linear_segments(a, seg, seg_rows, 1, w2, c, n, m, k, epilogue, dtype, scratch, scratch_bytes, s, nullptr, nullptr, nullptr, pend, rows);
 }
 
 fastav_status_t launch_attention(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
@@ -516,6 +524,7 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
                                 m.n_q_heads, m.n_kv_heads, m.head_dim, side ? logits : nullptr, side ? ml : nullptr,
                                 m.dtype, attn_flops[stage], s));
     void* attn_cur = attn[0];
+    RowGather o_rows;
     if (fine) {
       // ---- FINE prune: Eq. 4 scores of the last query row(s), top-k, compaction of everything later work reads
       float* sc = (out->prune_scores_out && out->prune_scores_out[pi]) ? out->prune_scores_out[pi] : scores_ws;
@@ -539,15 +548,20 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
       int32_t* kidx = (out->prune_keep_idx_out && out->prune_keep_idx_out[pi]) ? out->prune_keep_idx_out[pi] : keep_idx_ws;
       FASTAV_TRY(launch_select(sc, prot[cur], cu_l, cu_nx, B, maxlen_stage[stage], kidx,
                                5.0 * Tl + 4.0 * T_stage[stage + 1], s, rule));
+      // The attention output is not compacted where the O projection can read its rows through the keep list (one
+      // tensor less to move here; the projection's operand copies fetch the same bytes either way).
+      if (g_options[FASTAV_OPT_FUSED_GATHER_OPROJ] && linear_takes_rows(T_stage[stage + 1], m.hidden, qd, FASTAV_EPI_RESADD, m.dtype, Tl)) {
+        o_rows.idx = kidx; o_rows.n_src = Tl;
+      }
       GatherTensor g[6] = {{resid[cur], resid[cur ^ 1], (int64_t)m.hidden * 4, 0},
-                           {attn[0], attn[1], (int64_t)qd * (int64_t)es, 0},
                            {pos[cur], pos[cur ^ 1], 4, 0},
                            {prot[cur], prot[cur ^ 1], 1, 0},
                            {kptr, k_out, k_out ? (int64_t)kd * (int64_t)es : 0, qkv_stride * (int64_t)es},
-                           {vptr, v_out, v_out ? (int64_t)kd * (int64_t)es : 0, qkv_stride * (int64_t)es}};
-      FASTAV_TRY(launch_gather(g, 6, kidx, T_stage[stage + 1], s));
+                           {vptr, v_out, v_out ? (int64_t)kd * (int64_t)es : 0, qkv_stride * (int64_t)es},
+                           {attn[0], attn[1], (int64_t)qd * (int64_t)es, 0}};
+      FASTAV_TRY(launch_gather(g, o_rows.idx ? 5 : 6, kidx, T_stage[stage + 1], s));
       cur ^= 1; ++stage; ++pi;
-      attn_cur = attn[1];
+      attn_cur = o_rows.idx ? attn[0] : attn[1];
     } else {
       // this layer's K and V rows go to the caller's cache in one launch, unless they were produced there
       GatherTensor kvc[2] = {{kptr, k_out, k_out ? (int64_t)kd * (int64_t)es : 0, qkv_stride * (int64_t)es},
@@ -560,7 +574,7 @@ fastav_status_t fastav_prefill(fastav_handle_t h, const fastav_batch_t* in, cons
     const bool defer = g_options[FASTAV_OPT_FUSED_SPLITK_NORM] != 0;
     SplitKPending pend_o;
     FASTAV_TRY(launch_linear(attn_cur, W.wo, nullptr, resid[cur], To, m.hidden, qd, FASTAV_EPI_RESADD, m.dtype, gscr, ws.gemm_scratch_bytes, s,
-                             defer ? &pend_o : nullptr));
+                             defer ? &pend_o : nullptr, o_rows));
     FASTAV_TRY(launch_rmsnorm(resid[cur], W.g_mlp, hn, To, m.hidden, m.rms_eps, m.dtype, s, &pend_o));
     FASTAV_TRY(launch_linear(hn, W.w_gate, W.w_up, hmlp, To, m.mlp_dim, m.hidden, FASTAV_EPI_SWIGLU, m.dtype, nullptr, 0, s));
     // the down projection's sum can wait for the next layer's first RMSNorm unless something reads the residual first:

@@ -89,9 +89,13 @@ fastav_status_t launch_rope2(void* x, int64_t row_stride, int n_heads, void* x2,
                              const void* table = nullptr);
 // scratch (optional): device memory for split-K partial tiles; without it small-M residual GEMMs are not split
 // pend (optional, residual epilogue): a split-K product leaves its partial sums pending instead of reducing them
+// rows (optional, rows.idx != nullptr): row r of the product reads row rows.idx[r] of `a` instead of row r - a row
+// gather folded into the operand copies; rows.n_src = number of rows `a` holds.  Only where linear_takes_rows says so.
+struct RowGather { const int32_t* idx = nullptr; int64_t n_src = 0; };
+bool linear_takes_rows(int64_t m, int n, int k, int epilogue, int dtype, int64_t n_src);
 fastav_status_t launch_linear(const void* a, const void* w, const void* w2, void* c, int64_t m, int n, int k,
                               int epilogue, int dtype, void* scratch, size_t scratch_bytes, hipStream_t s,
-                              SplitKPending* pend = nullptr);
+                              SplitKPending* pend = nullptr, RowGather rows = RowGather());
 fastav_status_t launch_attention(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
                                  void* o, int64_t o_stride, const int32_t* cu, int batch, int64_t T, int max_seqlen,
                                  int Hq, int Hkv, int dh, float* last_logits, float* last_ml, int dtype,

@@ -54,6 +54,8 @@ struct GemmArgs {
   const int32_t* rope_pos;
   const float2* rope_tab;
   int rope_dh, rope_segs;
+  // optional: output row r is computed from row a_rows[r] of A (a row gather folded into the operand copies)
+  const int32_t* a_rows;
 };
 
 constexpr int kNumCUs = 256;
@@ -365,13 +367,16 @@ __global__ __launch_bounds__(WM * WN * 64, ((W3 ? 2 : 3) * BM + (W3 ? 3 : 2) * B
   u32x4_t a_rs, b_rs[B_D];
   const uint32_t a_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
   const uint32_t b_base = a_base + (uint32_t)NSA * BM * 128u;
-  a_rs = make_rsrc(g.A + (int64_t)m0 * K + kt0 * 64);
+  a_rs = make_rsrc(g.A + (g.a_rows ? (int64_t)0 : (int64_t)m0 * K) + kt0 * 64);
 #pragma unroll
   for (int i = 0; i < A_D; ++i) {
     const int r0 = (i * NW + wave_u) * 8, row = r0 + drow;
     int grow = m0 + row;
     grow = grow < g.M ? grow : g.M - 1;                 // clamp: stay inside A, the epilogue masks the row
-    a_vo[i] = ((uint32_t)(grow - m0) * (uint32_t)K + (uint32_t)(dpos ^ ((row >> 1) & 7)) * 8u) * 2u;
+    // with a row list the lane offset addresses the source row from the start of A (the launcher checks that all of A
+    // lies within the 32-bit offset range)
+    const uint32_t arow = g.a_rows ? (uint32_t)g.a_rows[grow] : (uint32_t)(grow - m0);
+    a_vo[i] = (arow * (uint32_t)K + (uint32_t)(dpos ^ ((row >> 1) & 7)) * 8u) * 2u;
     a_dst[i] = a_base + (uint32_t)r0 * 128u;
   }
 #pragma unroll
@@ -645,6 +650,9 @@ static fastav_status_t launch_epi(GemmArgs& g, bool big_ok, void* scratch, size_
 
 // Whether the plain-store epilogue can apply RoPE to the leading segments of this product: whole heads per wave
 // tile, and only the tile shapes whose waves are 64 columns wide.
+// A row list is addressed through the copies' 32-bit lane offsets from the start of A.
+bool mfma_linear_takes_rows(int k, int64_t n_src) { return n_src > 0 && (n_src + 8) * (int64_t)k * 2 < ((int64_t)1 << 32); }
+
 bool mfma_linear_fuses_rope(int64_t m, const int* seg_rows, int n_seg, int rope_segs, int k, int dh, int dtype) {
   if ((dh != 64 && dh != 128) || rope_segs < 1 || rope_segs > n_seg) return false;
   int n = 0;
@@ -659,9 +667,14 @@ bool mfma_linear_fuses_rope(int64_t m, const int* seg_rows, int n_seg, int rope_
 fastav_status_t launch_linear_mfma(const void* a, const void* const* w_seg, const int* seg_rows, int n_seg,
                                    const void* w2, void* c, int64_t ldc, void* const* c_seg, const int64_t* ldc_seg,
                                    int64_t m, int n, int k, int epilogue, void* scratch, size_t scratch_bytes, hipStream_t s,
-                                   const RopeFuse* rope, SplitKPending* pend) {
+                                   const RopeFuse* rope, SplitKPending* pend, RowGather rows) {
   GemmArgs g;
   if (pend != nullptr) *pend = SplitKPending();
+  g.a_rows = nullptr;
+  if (rows.idx != nullptr) {
+    if (!mfma_linear_takes_rows(k, rows.n_src)) return fail(FASTAV_EINVAL, "gemm: the row list needs all of A within 4 GB");
+    g.a_rows = rows.idx;
+  }
   g.rope_pos = nullptr; g.rope_tab = nullptr; g.rope_dh = 0; g.rope_segs = 0;
   if (rope != nullptr && rope->table != nullptr) {
     if (epilogue != FASTAV_EPI_STORE || !mfma_linear_fuses_rope(m, seg_rows, n_seg, rope->n_segs, k, rope->head_dim, FASTAV_BF16))

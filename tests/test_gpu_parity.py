@@ -908,3 +908,42 @@ def test_achievable_peak_probes_run_and_report_their_work():
     assert float(sink.abs().max()) == 0.0
     with pytest.raises(ValueError):
         fa.fastav_probe_mfma(10, sink, torch.zeros(16, device="cuda").bfloat16())
+
+
+@pytest.mark.parametrize("case", ["short", "long"])
+def test_prefill_o_projection_reads_surviving_rows_through_the_keep_list(case):
+    """After a FINE prune the O projection can fetch the surviving rows of the attention output through the keep list
+    in its operand copies instead of having them compacted first.  Same values into the same arithmetic: every output
+    must have the same bits either way (short samples take the split-K form of the projection, the long one whole
+    tiles), and the forward is the oracle's."""
+    if case == "short":
+        m = fi.Model(4, 512, 8, 2, 128, 1024, 1.0e4, 1e-6, "bf16")
+        samples = [[(fi.VIDEO, 288), (fi.AUDIO, 150), (fi.TEXT, 30)], [(fi.VIDEO, 1000), (fi.AUDIO, 301), (fi.TEXT, 5)]]
+        prunes = [fi.Prune(1, fi.GLOBAL, 0.6), fi.Prune(1, fi.FINE, 0.7), fi.Prune(2, fi.FINE, 0.8)]
+    else:
+        m = fi.Model(3, 1024, 8, 2, 128, 2048, 1.0e4, 1e-6, "bf16")
+        samples = [[(fi.VIDEO, 2600), (fi.AUDIO, 700), (fi.TEXT, 23)]]
+        prunes = [fi.Prune(1, fi.FINE, 0.75), fi.Prune(2, fi.FINE, 0.5)]
+    w = fi.Workload("rowlist_" + case, m, samples, prunes, seed=83)
+    weights = [fi.layer_weights(m, l, 29) for l in range(m.n_layers)]
+    dec = make_decoder(m, weights)
+    spans, offs = fi.span_table(w)
+    xd = dev(fi.embeddings(w), "bf16")
+    res = {}
+    try:
+        for fused in (1, 0):
+            fa.fastav_set_option(fa.OPT_FUSED_GATHER_OPROJ, fused)
+            o = dec.fastav_prefill(xd, fi.cu_seqlens(w), spans, offs, prune_tuples(w), 1, want_kv=True, want_layers=True)
+            torch.cuda.synchronize()
+            res[fused] = (o["x_out"].clone(), o["kept_pos"].clone(), [k.clone() for k, _ in o["kv"]], [v.clone() for _, v in o["kv"]],
+                          [t.clone() for t in o["layer_x"]])
+    finally:
+        fa.fastav_set_option(fa.OPT_FUSED_GATHER_OPROJ, 1)
+    a, b = res[1], res[0]
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    for i in (2, 3, 4):
+        assert all(torch.equal(x, y) for x, y in zip(a[i], b[i])), i
+    out, ref = _oracle_and_gpu(w, weights, fi.embeddings(w), want_kv=False)
+    st = _check_prefill(w, out, ref)
+    for bb in range(len(samples)):
+        assert st[f"x_rel_l2_{bb}"] <= 1e-2, st

@@ -250,7 +250,7 @@ def test_probes_and_options_reject_bad_arguments():
     assert lib.fastav_probe_read(None, 1 << 20, 4096, None) == B.EINVAL
     assert lib.fastav_probe_read(4096, 1024, 4096, None) == B.EINVAL                        # under 16 KB
     assert lib.fastav_probe_read(4096 + 4, 1 << 20, 4096, None) == B.EINVAL                 # misaligned
-    assert lib.fastav_set_option(-1, 1) == B.EINVAL and lib.fastav_set_option(99, 1) == B.EINVAL
-    for opt in (B.OPT_FUSED_SCORE_SELECT, B.OPT_FUSED_ROPE, B.OPT_FUSED_SPLITK_NORM):
+    assert lib.fastav_set_option(-1, 1) == B.EINVAL and lib.fastav_set_option(4, 1) == B.EINVAL
+    for opt in (B.OPT_FUSED_SCORE_SELECT, B.OPT_FUSED_ROPE, B.OPT_FUSED_SPLITK_NORM, B.OPT_FUSED_GATHER_OPROJ):
         assert lib.fastav_set_option(opt, 0) == B.OK and lib.fastav_set_option(opt, 1) == B.OK
 
