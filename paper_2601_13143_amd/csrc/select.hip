@@ -5,8 +5,10 @@
 //   k_select  one 1024-thread workgroup per sample.  The sample's order-preserving 32-bit keys live in LDS;
 //             four 8-bit MSB-first radix passes (per-wave LDS histograms, so that the narrow exponent range
 //             of softmax scores does not serialise on one counter) find the k-th largest key; ties at
-//             the threshold go to the lowest indices; two workgroup scans turn the keep flags into the
-//             ascending list of kept rows.  Integer work only, so the result is exact.
+//             the threshold go to the lowest indices; one workgroup scan (two where the keys do not fit in
+//             LDS) turns the keep flags into the ascending list of kept rows.  The positional orders need no
+//             radix pass: all candidates tie, and the tie rule by rank in row order is the selection.
+//             Integer work only, so the result is exact.
 //   k_gather  dst[r] = src[keep_idx[r]] for several tensors in one launch, 16 bytes per lane.
 #include "common.hpp"
 
